@@ -1,0 +1,450 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU needed).
+
+Each test checks the oracle against something that is not the oracle: a hand-worked
+example, a closed form, an invariant the paper states, a special case that reduces to
+a library routine (torch.topk, numpy/torch matmul, scipy softmax), or brute force.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import softmax as sp_softmax
+
+from paper_2503_05066_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+NONE, TD, ED = synth.MODE_NONE, synth.MODE_TOKEN_DROP, synth.MODE_EXPANDED_DROP
+LOCAL, GLOBAL = synth.SCOPE_LOCAL, synth.SCOPE_GLOBAL
+
+
+def small_logits(n, e, seed, bias_sigma=1.0):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, e)) + bias_sigma * rng.standard_normal(e)[None, :]).astype(np.float32)
+
+
+def read_golden(name):
+    sections, cur = {}, None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line.startswith("["):
+                cur = line.strip("[]")
+                sections[cur] = []
+            else:
+                sections[cur].append([float(v) for v in line.split()])
+    return {k: np.array(v) for k, v in sections.items()}
+
+
+# ----------------------------------------------------------------------------
+# hand-worked example (tests/golden/hand_worked_drop.txt)
+# ----------------------------------------------------------------------------
+def test_hand_worked_example(orc):
+    g = read_golden("hand_worked_drop.txt")
+    logits = (g["logits_ln2"] * math.log(2.0)).astype(np.float32)
+    nd = g["scores_num_den"]
+    expect_scores = nd[:, :3] / nd[:, 3:4]
+    r = orc.route_and_drop(logits, 1, 1, TD, GLOBAL, 1.0)
+    assert r.cap == 2
+    np.testing.assert_allclose(r.scores, expect_scores, rtol=2e-6)
+    np.testing.assert_array_equal(r.keep, g["keep_token_drop"].astype(np.uint8))
+    # Eq. (11) on this example: one third of the pairs is dropped
+    assert 1.0 - r.plan.rows / 6.0 == pytest.approx(1.0 / 3.0)
+    r = orc.route_and_drop(logits, 1, 3, ED, GLOBAL, 1.0)
+    np.testing.assert_array_equal(r.keep, g["keep_expanded_drop_global"].astype(np.uint8))
+
+
+# ----------------------------------------------------------------------------
+# router logits: reduce to a library matmul
+# ----------------------------------------------------------------------------
+def test_router_logits_match_fp64_matmul(orc):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((37, 53)).astype(np.float32)
+    w = rng.standard_normal((11, 53)).astype(np.float32)
+    b = rng.standard_normal(11).astype(np.float32)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    np.testing.assert_allclose(orc.router_logits(x, w), ref, rtol=0, atol=2e-6)
+    np.testing.assert_allclose(orc.router_logits(x, w, b), ref + b, rtol=0, atol=2e-6)
+    # operand order: a transposed weight would not even have the right shape; a swapped
+    # index shows on a non-symmetric case
+    assert abs(orc.router_logits(x[:1], w[:1])[0, 0] - float(x[0].astype(np.float64) @ w[0])) < 1e-5
+
+
+# ----------------------------------------------------------------------------
+# softmax, Eq. (1)
+# ----------------------------------------------------------------------------
+def test_softmax_close_to_fp64_definition(orc):
+    rng = np.random.default_rng(2)
+    for e, scale in [(8, 1.0), (64, 3.0), (128, 10.0), (5, 30.0)]:
+        l = (rng.standard_normal((200, e)) * scale).astype(np.float32)
+        s = orc.softmax_scores(l)
+        ref = sp_softmax(l.astype(np.float64), axis=1)
+        big = ref > 1e-30
+        # the fp32 subtraction l - max rounds z by up to half an ulp of |z|, which exp turns into
+        # a relative error of that size; the rest (polynomial, sum, division) stays below 1e-6
+        z = np.abs(l.astype(np.float64) - l.max(1, keepdims=True))
+        tol = 1e-6 + z * 2.0 ** -23
+        assert np.all(np.abs(s[big] - ref[big]) / ref[big] < tol[big])
+        assert np.all(s[~big] < 1e-29)
+        np.testing.assert_allclose(s.sum(1, dtype=np.float64), 1.0, atol=1e-5)
+        assert np.all(s >= 0) and np.all(s <= 1)
+
+
+def test_softmax_two_experts_is_logistic(orc):
+    # E = 2, logits (0, z): s_1 = e^z / (1 + e^z) for z over the whole non-underflowing range
+    z = np.linspace(-79.5, 0.0, 3181).astype(np.float32)
+    l = np.stack([np.zeros_like(z), z], axis=1)
+    s = orc.softmax_scores(l)
+    zz = z.astype(np.float64)
+    ref = np.exp(zz) / (1.0 + np.exp(zz))
+    assert np.all(np.abs(s[:, 1] - ref) / ref < 1e-6)   # z is given exactly here: no subtraction error
+    assert np.all(s[:, 1] > 0)
+
+
+def test_softmax_exact_cases(orc):
+    # equal logits: exactly 1/E when E is a power of two
+    for e in (2, 8, 64):
+        s = orc.softmax_scores(np.full((3, e), 1.25, np.float32))
+        assert np.all(s == np.float32(1.0 / e))
+    # a logit more than 80 below the maximum contributes exactly zero
+    s = orc.softmax_scores(np.array([[0.0, -80.5, -1000.0, 0.0]], np.float32))
+    assert s[0, 1] == 0.0 and s[0, 2] == 0.0 and s[0, 0] == 0.5 and s[0, 3] == 0.5
+    # shifting all logits of a token by an exactly representable amount changes nothing
+    l = np.random.default_rng(3).integers(-8, 8, size=(50, 16)).astype(np.float32)
+    np.testing.assert_array_equal(orc.softmax_scores(l), orc.softmax_scores(l + np.float32(32.0)))
+    # order is preserved: a larger logit never gets a smaller score
+    l = small_logits(64, 32, 4)
+    s = orc.softmax_scores(l)
+    for t in range(64):
+        o = np.argsort(l[t], kind="stable")
+        assert np.all(np.diff(s[t][o]) >= 0)
+
+
+# ----------------------------------------------------------------------------
+# top-k, Eq. (1)
+# ----------------------------------------------------------------------------
+def test_topk_matches_library_topk_without_ties(orc):
+    rng = np.random.default_rng(5)
+    for n, e, k in [(64, 8, 2), (33, 64, 8), (10, 128, 6), (7, 5, 5), (9, 16, 1)]:
+        s = orc.softmax_scores(rng.standard_normal((n, e)).astype(np.float32) * 2)
+        for t in range(n):  # tie-free rows only
+            assert len(np.unique(s[t])) == e
+        idx, val = orc.topk(s, k)
+        tv, ti = torch.from_numpy(s).topk(k, dim=1)
+        np.testing.assert_array_equal(idx, ti.numpy().astype(np.int32))
+        np.testing.assert_array_equal(val, tv.numpy())
+
+
+def test_topk_ties_go_to_lower_expert(orc):
+    s = np.array([[0.2, 0.3, 0.3, 0.2, 0.0], [0.25, 0.25, 0.25, 0.25, 0.0], [0.0, 0.0, 0.0, 0.0, 1.0]], np.float32)
+    idx, val = orc.topk(s, 3)
+    np.testing.assert_array_equal(idx, [[1, 2, 0], [0, 1, 2], [4, 0, 1]])
+    np.testing.assert_array_equal(val, np.array([[0.3, 0.3, 0.2], [0.25, 0.25, 0.25], [1.0, 0.0, 0.0]], np.float32))
+
+
+# ----------------------------------------------------------------------------
+# capacity, Sec. 3 (C = gamma * N_bar) and the integer form of Alg. 1
+# ----------------------------------------------------------------------------
+def test_capacity_values(orc):
+    # the five workloads: N_bar = N k / E is an integer, C = gamma N_bar
+    assert orc.capacity(1.0, 128, 2, 8) == 32
+    assert [orc.capacity(g, 4096, 8, 64) for g in (1.0, 1.5, 2.0)] == [512, 768, 1024]
+    assert orc.capacity(1.0, 8192, 2, 8) == 2048 and orc.capacity(1.0, 2048, 2, 8) == 512
+    assert [orc.capacity(g, 16384, 8, 128) for g in (1.0, 1.25)] == [1024, 1280]
+    assert [orc.capacity(g, 2048, 8, 128) for g in (1.0, 1.25)] == [128, 160]
+    assert orc.capacity(1.0, 256, 6, 64) == 24 and orc.capacity(1.0, 32, 6, 64) == 3
+    # truncation toward zero (41.6 -> 41), as Python's int() does
+    assert orc.capacity(1.3, 128, 2, 8) == 41 == int(1.3 * (128 * 2) / 8)
+    for g, n, k, e in [(0.7, 100, 3, 7), (1.1, 40, 2, 8), (2.5, 33, 4, 16), (0.05, 10, 1, 4)]:
+        assert orc.capacity(g, n, k, e) == min(n, int(g * (n * k) / e))
+    assert orc.capacity(0.0, 128, 2, 8) == 0
+    assert orc.capacity(math.inf, 128, 2, 8) == 128      # no limit
+    assert orc.capacity(100.0, 128, 2, 8) == 128         # an expert cannot hold more tokens than exist
+
+
+# ----------------------------------------------------------------------------
+# Token Drop / Expanded Drop against an independent dense-matrix derivation
+# ----------------------------------------------------------------------------
+def dense_reference(scores, k, gamma, local_experts=None):
+    """The method on one device's tokens, written with dense masks and library sorts.
+
+    Candidate mask from the top-k columns (plus the device's own experts for Expanded
+    Drop); every expert column keeps its `cap` largest masked scores.  Valid when no
+    two candidate scores of a column are equal.
+    """
+    s = torch.from_numpy(scores.astype(np.float64))
+    n, e = s.shape
+    mask = torch.zeros(n, e, dtype=torch.bool)
+    mask[torch.arange(n)[:, None], s.topk(k, dim=1).indices] = True
+    if local_experts is not None:
+        mask[:, local_experts] = True
+    cap = min(n, int(gamma * (n * k) / e)) if math.isfinite(gamma) else n
+    masked = torch.where(mask, s, torch.full_like(s, -1.0))
+    order = torch.argsort(masked, dim=0, descending=True)
+    col_keep = torch.zeros(n, e, dtype=torch.bool)
+    col_keep[order[:cap], torch.arange(e)[None, :].expand(cap, e)] = True
+    return (mask & col_keep).numpy().astype(np.uint8)
+
+
+@pytest.mark.parametrize("n,e,k,g,gamma", [
+    (128, 8, 2, 1, 1.0), (128, 8, 2, 4, 1.0), (256, 16, 4, 4, 0.5), (256, 16, 4, 8, 1.5),
+    (96, 12, 3, 3, 2.0), (64, 64, 6, 8, 1.0), (120, 8, 2, 2, 1.3), (64, 4, 4, 2, 0.75),
+])
+def test_drop_equals_dense_derivation(orc, n, e, k, g, gamma):
+    logits = small_logits(n, e, 100 + n + e + k)
+    scores = orc.softmax_scores(logits)
+    assert all(len(np.unique(scores[:, j])) == n for j in range(e))
+    m = e // g
+    # Token Drop, capacity over all tokens
+    r = orc.route_and_drop(logits, k, g, TD, GLOBAL, gamma)
+    np.testing.assert_array_equal(r.keep, dense_reference(scores, k, gamma))
+    # Token Drop / Expanded Drop with local capacity: every device runs the method on its own tokens
+    ng = n // g
+    for mode in (TD, ED):
+        r = orc.route_and_drop(logits, k, g, mode, LOCAL, gamma)
+        for b in range(g):
+            loc = list(range(b * m, (b + 1) * m)) if mode == ED else None
+            # the capacity of Alg. 1 with N = the device's token count
+            ref = dense_reference(scores[b * ng:(b + 1) * ng], k, gamma, loc)
+            np.testing.assert_array_equal(r.keep[b * ng:(b + 1) * ng], ref)
+
+
+# ----------------------------------------------------------------------------
+# Eqs. (8)-(10): threshold tau = C-th highest candidate score, kept = {score >= tau}
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(4))
+def test_threshold_definition(orc, seed):
+    n, e, k, gamma = 200, 10, 3, 0.8
+    logits = small_logits(n, e, 200 + seed, 1.5)
+    r = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma)
+    cap = int(gamma * n * k / e)
+    assert r.cap == cap
+    overflowed = 0
+    for j in range(e):
+        cand = np.flatnonzero(r.cand[:, j])
+        if len(cand) <= cap:  # "no difference" for experts below capacity
+            np.testing.assert_array_equal(r.keep[:, j], r.cand[:, j])
+            continue
+        overflowed += 1
+        tau = np.sort(r.scores[cand, j])[::-1][cap - 1]
+        expect = np.zeros(n, np.uint8)
+        expect[cand[r.scores[cand, j] >= tau]] = 1
+        np.testing.assert_array_equal(r.keep[:, j], expect)
+    assert overflowed > 0
+
+
+# ----------------------------------------------------------------------------
+# load invariants: Sec. 2.2 (sum and range of loads), Sec. 3 (bound under gamma), Eq. (11)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("gamma", [0.25, 0.5, 1.0, 1.5, 2.0])
+def test_load_invariants_and_dropped_ratio(orc, gamma):
+    n, e, k = 512, 16, 4
+    nbar = n * k // e
+    logits = small_logits(n, e, 300, 2.0)
+    r = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma)
+    loads = r.cand.sum(0).astype(np.int64)
+    assert loads.sum() == n * k                                   # sum_i N_i = t k
+    assert nbar <= loads.max() <= n                               # max load in [N_bar, n N_bar / k]
+    kept = r.keep.sum(0).astype(np.int64)
+    cap = int(gamma * nbar)
+    np.testing.assert_array_equal(kept, np.minimum(loads, cap))   # overflowed experts keep exactly C
+    if gamma < 1:
+        assert kept.max() == cap
+    else:
+        assert kept.max() <= cap and (kept.max() >= nbar or loads.max() < nbar + 1)
+    dt = np.maximum(loads - gamma * nbar, 0).sum() / loads.sum()  # Eq. (11)
+    assert 1.0 - kept.sum() / (n * k) == pytest.approx(dt)
+    np.testing.assert_array_equal(r.plan.expert_count, kept)
+    assert np.all(r.keep <= r.cand)
+
+
+def test_gamma_infinite_and_mode_none_reproduce_plain_topk(orc):
+    logits = small_logits(96, 8, 7)
+    scores = orc.softmax_scores(logits)
+    topk_mask = np.zeros((96, 8), np.uint8)
+    topk_mask[np.arange(96)[:, None], torch.from_numpy(scores).topk(2, dim=1).indices.numpy()] = 1
+    for mode, gamma, scope, g in [(TD, math.inf, GLOBAL, 1), (NONE, 1.0, GLOBAL, 1), (TD, math.inf, LOCAL, 4),
+                                  (NONE, 0.1, LOCAL, 2)]:
+        r = orc.route_and_drop(logits, 2, g, mode, scope, gamma)
+        np.testing.assert_array_equal(r.keep, topk_mask)
+    r = orc.route_and_drop(logits, 2, 1, TD, GLOBAL, 0.0)
+    assert r.keep.sum() == 0 and r.plan.rows == 0
+
+
+# ----------------------------------------------------------------------------
+# Expanded Drop properties, Sec. 3 "Expanded Drop" and Alg. 2
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("scope", [LOCAL, GLOBAL])
+def test_expanded_drop_properties(orc, scope):
+    n, e, k, g, gamma = 256, 16, 2, 4, 1.0
+    m, ng = e // g, n // g
+    logits = small_logits(n, e, 400, 1.5)
+    td = orc.route_and_drop(logits, k, g, TD, scope, gamma)
+    ed = orc.route_and_drop(logits, k, g, ED, scope, gamma)
+    dev_of_token = np.arange(n) // ng
+    dev_of_expert = np.arange(e) // m
+    own = dev_of_token[:, None] == dev_of_expert[None, :]
+    topk_mask = td.cand.astype(bool)
+    np.testing.assert_array_equal(ed.cand.astype(bool), topk_mask | own)        # candidates: top-k plus own device
+    assert np.all(~(ed.keep.astype(bool) & ~topk_mask) | own)                   # added experts are local only
+    assert ed.cand.sum(1).max() <= k + m and ed.keep.sum(1).max() <= k + m      # up to k + m experts per token
+    assert ed.keep.sum(1).max() > k                                             # and no limit of k per token
+    cap = ed.cap
+    if scope == LOCAL:
+        for b in range(g):
+            rows = slice(b * ng, (b + 1) * ng)
+            for j in range(e):
+                if dev_of_expert[j] == b:   # every local token is a candidate of a local expert
+                    assert ed.keep[rows, j].sum() == min(cap, ng)
+                else:                       # other devices' experts see the same candidates as in Token Drop
+                    np.testing.assert_array_equal(ed.keep[rows, j], td.keep[rows, j])
+    assert ed.keep.sum(0).max() <= (cap * g if scope == LOCAL else cap)
+    assert ed.keep.sum() >= td.keep.sum()                                       # utilisation only goes up
+    # with one device every expert is local: the same as choosing all E experts
+    one = orc.route_and_drop(logits, k, 1, ED, GLOBAL, gamma)
+    allk = orc.route_and_drop(logits, e, 1, TD, GLOBAL, gamma * k / e)
+    assert one.cap == allk.cap
+    np.testing.assert_array_equal(one.keep, allk.keep)
+
+
+# ----------------------------------------------------------------------------
+# ties: exactly C kept, lower token index wins (brute force over all pairs)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (TD, LOCAL, 4), (ED, LOCAL, 4), (ED, GLOBAL, 2)])
+def test_tie_rule_brute_force(orc, mode, scope, g):
+    w = synth.scaled(synth.WORKLOADS["tiny"], n_tokens=96, n_experts=8, device_groups=g)
+    logits = synth.logits_with_ties(w)
+    r = orc.route_and_drop(logits, 2, g, mode, scope, 1.0)
+    n, e = logits.shape
+    blocks = g if scope == LOCAL else 1
+    ns = n // blocks
+    ties_seen = 0
+    for b in range(blocks):
+        for j in range(e):
+            toks = np.arange(b * ns, (b + 1) * ns)
+            cand = toks[r.cand[toks, j] == 1]
+            kept = toks[r.keep[toks, j] == 1]
+            assert len(kept) == min(len(cand), r.cap)
+            dropped = np.setdiff1d(cand, kept)
+            for a in kept:
+                for d in dropped:
+                    sa, sd = r.scores[a, j], r.scores[d, j]
+                    assert sa > sd or (sa == sd and a < d)
+                    ties_seen += sa == sd
+    assert ties_seen > 0
+
+
+def test_zero_score_candidates_rank_above_non_candidates(orc):
+    # scores that underflow to zero still belong to the candidate set (top-k of a peaked row)
+    logits = np.zeros((8, 4), np.float32)
+    logits[:, 0] = 200.0  # every other expert scores exactly 0; the top-2 is {0, 1} by the tie rule
+    r = orc.route_and_drop(logits, 2, 1, TD, GLOBAL, 1.0)
+    assert r.cap == 4
+    np.testing.assert_array_equal(r.topk_idx, np.tile([0, 1], (8, 1)))
+    np.testing.assert_array_equal(r.keep[:, 0], [1, 1, 1, 1, 0, 0, 0, 0])
+    np.testing.assert_array_equal(r.keep[:, 1], [1, 1, 1, 1, 0, 0, 0, 0])
+    assert r.keep[:, 2:].sum() == 0
+
+
+# ----------------------------------------------------------------------------
+# "Score" does not depend on the order of tokens in the batch (Sec. 3, metrics)
+# ----------------------------------------------------------------------------
+def test_score_metric_is_permutation_equivariant(orc):
+    logits = small_logits(160, 8, 9, 1.5)
+    perm = np.random.default_rng(10).permutation(160)
+    a = orc.route_and_drop(logits, 2, 1, TD, GLOBAL, 1.0)
+    b = orc.route_and_drop(logits[perm], 2, 1, TD, GLOBAL, 1.0)
+    np.testing.assert_array_equal(b.keep, a.keep[perm])
+
+
+# ----------------------------------------------------------------------------
+# dispatch plan
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (ED, LOCAL, 4), (ED, GLOBAL, 4), (NONE, LOCAL, 2)])
+def test_plan_is_the_kept_set_in_canonical_order(orc, mode, scope, g):
+    n, e, k = 128, 8, 2
+    logits = small_logits(n, e, 11, 1.5)
+    r = orc.route_and_drop(logits, k, g, mode, scope, 1.0)
+    p = r.plan
+    tt, ee = np.nonzero(r.keep.T)[1], np.nonzero(r.keep.T)[0]      # expert-major, token ascending
+    np.testing.assert_array_equal(p.row_token, tt)
+    np.testing.assert_array_equal(p.row_weight, r.scores[tt, ee])
+    np.testing.assert_array_equal(p.expert_count, r.keep.sum(0))
+    np.testing.assert_array_equal(p.expert_offset, np.concatenate([[0], np.cumsum(r.keep.sum(0))]))
+    blocks = g if scope == LOCAL else 1
+    np.testing.assert_array_equal(p.seg_count, r.keep.reshape(blocks, n // blocks, e).sum(1))
+    s = k + (e // g if mode == ED else 0)
+    assert p.pair_row.shape == (n, s)
+    expect = -np.ones((n, s), np.int64)
+    for row, (t, j) in enumerate(zip(tt, ee)):
+        expect[t, int(r.cand[t, :j].sum())] = row
+    np.testing.assert_array_equal(p.pair_row, expect)
+
+
+# ----------------------------------------------------------------------------
+# layer output, Eq. (2)
+# ----------------------------------------------------------------------------
+def torch_swiglu(v, wg, wu, wd):
+    v, wg, wu, wd = (torch.from_numpy(np.asarray(a, np.float64)) for a in (v, wg, wu, wd))
+    return ((torch.nn.functional.silu(v @ wg.T) * (v @ wu.T)) @ wd.T).numpy()
+
+
+def test_single_expert_is_one_dense_ffn(orc):
+    rng = np.random.default_rng(12)
+    n, d, h = 9, 24, 40
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    wg, wu = rng.standard_normal((2, h, d)).astype(np.float32) * 0.2
+    wd = rng.standard_normal((d, h)).astype(np.float32) * 0.2
+    r = orc.route_and_drop(np.zeros((n, 1), np.float32), 1, 1, TD, GLOBAL, math.inf)
+    assert np.all(r.scores == 1.0)
+    y = orc.layer_output(x, r.scores, r.keep, [wg], [wu], [wd])
+    np.testing.assert_allclose(y, torch_swiglu(x, wg, wu, wd), rtol=1e-12, atol=1e-12)
+
+
+def test_layer_output_is_weighted_sum_over_kept_pairs(orc):
+    w = synth.scaled(synth.WORKLOADS["tiny"], n_tokens=48, d_model=32, d_hidden=56, n_experts=6)
+    x = synth.tokens(w).f32
+    logits = small_logits(48, 6, 13, 1.5)
+    ws = [synth.expert_weights(w, j) for j in range(6)]
+    wg, wu, wd = ([a[i].f32 for a in ws] for i in range(3))
+    ffn = np.stack([torch_swiglu(x, wg[j], wu[j], wd[j]) for j in range(6)], axis=1)      # [N,E,d]
+    for mode, gamma in [(TD, math.inf), (TD, 1.0), (ED, 1.0), (TD, 0.0)]:
+        r = orc.route_and_drop(logits, 2, 2, mode, LOCAL, gamma)
+        y = orc.layer_output(x, r.scores, r.keep, wg, wu, wd)
+        ref = np.einsum("te,ted->td", r.scores.astype(np.float64) * r.keep, ffn)          # Eq. (2), masked scores
+        np.testing.assert_allclose(y, ref, rtol=1e-11, atol=1e-13)
+        empty = r.keep.sum(1) == 0
+        assert np.all(y[empty] == 0.0)
+        if gamma == 0.0:
+            assert np.all(y == 0.0)
+        if mode == TD and gamma == 1.0:
+            assert empty.any() or r.keep.sum() == 96
+        sub = np.array([5, 0, 47, 5], np.int32)
+        np.testing.assert_array_equal(orc.layer_output(x, r.scores, r.keep, wg, wu, wd, token_list=sub), y[sub])
+
+
+def test_layer_output_needs_the_weights_it_uses(orc):
+    x = np.ones((2, 4), np.float32)
+    scores = np.array([[0.5, 0.5], [0.5, 0.5]], np.float32)
+    keep = np.array([[1, 0], [0, 1]], np.uint8)
+    wgt = np.ones((3, 4), np.float32)
+    wdn = np.ones((4, 3), np.float32)
+    y = orc.layer_output(x, scores, keep, [wgt, None], [wgt, None], [wdn, None], token_list=[0])
+    assert y.shape == (1, 4)
+    with pytest.raises(ValueError):
+        orc.layer_output(x, scores, keep, [wgt, None], [wgt, None], [wdn, None])
+
+
+# ----------------------------------------------------------------------------
+# the synthetic workloads have the skew the paper reports (Sec. 2.1; App. layer-wise load)
+# ----------------------------------------------------------------------------
+def test_workload_skew(orc):
+    w = synth.WORKLOADS["olmoe"]
+    logits = orc.router_logits(synth.tokens(w).f32, synth.router_weight(w), synth.router_bias(w))
+    r = orc.route_and_drop(logits, w.top_k, 1, TD, GLOBAL, 1.0)
+    nbar = w.n_tokens * w.top_k / w.n_experts
+    assert r.cand.sum(0).max() / nbar > 5.0        # peak load several times the mean
+    assert r.keep.sum(0).max() == 512
