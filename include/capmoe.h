@@ -1,0 +1,169 @@
+/*
+ * capmoe - capacity-aware Mixture-of-Experts layer forward on one AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Capacity-Aware Inference: Mitigating the Straggler Effect in
+ * Mixture of Experts" (arXiv 2503.05066): router -> softmax -> top-k (Eq. 1), expert capacity
+ * C = gamma * N_bar (Sec. 3), score-ranked Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop
+ * (Sec. 3 "Expanded Drop", Alg. 2), permutation, expert FFNs and the weighted sum (Eq. 2).
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers (HIP global memory) unless marked "host".  The caller
+ *     owns every buffer; the library allocates nothing, frees nothing and keeps no pointer after
+ *     the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work; they never synchronise.  Work of one layer must be enqueued on one stream, in the
+ *     order route_topk, capacity_drop, dispatch, grouped_ffn, combine.
+ *   - Matrices are row-major and dense (no strides).  Indices are int32.
+ *   - Every function returns a moe_status_t.  Arguments are validated on the host before any
+ *     launch; on a non-zero status nothing was enqueued.  MOE_ERR_HIP reports a failed launch.
+ *   - `workspace` is scratch device memory of at least the size moe_query reports, 256-byte
+ *     aligned, reusable between calls (its content has no meaning after a call completes).
+ *
+ * Simulated expert parallelism: with G = device_groups, token t lives on device t / (N/G) and
+ * device b hosts experts [b*E/G, (b+1)*E/G) (data parallel = expert parallel, as in the paper's
+ * deployment, Sec. 5.1).  N and E must be multiples of G.
+ */
+#ifndef CAPMOE_H
+#define CAPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1,         /* null pointer, size out of range, N or E not a multiple of G   */
+    MOE_ERR_UNSUPPORTED = 2,         /* valid but not implemented (shape granularity, dtype)          */
+    MOE_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below what moe_query reports                  */
+    MOE_ERR_HIP = 4                  /* the HIP runtime refused a launch                              */
+} moe_status_t;
+
+enum { MOE_MODE_NONE = 0, MOE_MODE_TOKEN_DROP = 1, MOE_MODE_EXPANDED_DROP = 2 };
+enum { MOE_SCOPE_LOCAL = 0, MOE_SCOPE_GLOBAL = 1 };
+enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+
+/* Shape and policy of one layer call (host memory, plain data). */
+typedef struct {
+    int32_t n_tokens;       /* N                                                                     */
+    int32_t d_model;        /* d                                                                     */
+    int32_t n_experts;      /* E, at most 256                                                        */
+    int32_t top_k;          /* k, 1 <= k <= min(E, 64)                                               */
+    int32_t d_hidden;       /* h, SwiGLU hidden width                                                */
+    int32_t device_groups;  /* G >= 1 simulated devices                                              */
+    int32_t mode;           /* MOE_MODE_*: plain top-k, Token Drop (Alg. 1), Expanded Drop (Alg. 2)  */
+    int32_t capacity_scope; /* MOE_SCOPE_LOCAL: capacity per (device's tokens, expert), with
+                               N/G tokens in the capacity formula (Sec. 3: constraints are applied
+                               within each local device).  MOE_SCOPE_GLOBAL: per expert over all N.  */
+    double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 3)                           */
+    int32_t dtype;          /* MOE_DTYPE_*: type of x, expert weights, xp, yp, y.  The router
+                               (logits, softmax, scores) is always fp32.                             */
+    int32_t reserved;       /* set to 0                                                              */
+} moe_desc_t;
+
+const char* moe_status_string(int status);
+
+/*
+ * Static sizes of a layer call (host-only, launches nothing).
+ *   cap             capacity of one segment: min(Ns, trunc(gamma * (Ns*k) / E)), Ns = N (GLOBAL) or
+ *                   N/G (LOCAL); Ns for MOE_MODE_NONE or gamma = +inf.  (Sec. 3; Alg. 1)
+ *   slots_per_token S = k, or k + E/G for Expanded Drop (a token may keep up to k+m experts, Sec. 3)
+ *   max_rows        P_max, an upper bound on surviving token-expert pairs: size xp, yp, row_token,
+ *                   row_weight for this many rows
+ *   workspace_bytes enough for any single call of this descriptor
+ * Any output pointer may be NULL.
+ */
+int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, int64_t* max_rows,
+              size_t* workspace_bytes);
+
+/*
+ * Router, softmax and top-k: K = TopK(Softmax(G(x)), k), Eq. (1).
+ *   x            [N,d] in desc->dtype (ignored when use_given_logits != 0)
+ *   w_router     [E,d] fp32;  bias [E] fp32 or NULL        (ignored when use_given_logits != 0)
+ *   logits       [N,E] fp32: written, or read as input when use_given_logits != 0
+ *   scores       [N,E] fp32 out: softmax over experts, computed in fp32 by a fixed operation
+ *                sequence (max, exp by range reduction and a degree-7 polynomial, ascending sum,
+ *                IEEE division), so equal logits give bit-equal scores
+ *   topk_idx     [N,k] int32 out, topk_score [N,k] fp32 out: best first; equal scores go to the
+ *                lower expert id
+ * Logits must be finite.
+ */
+int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                   int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Capacity enforcement: Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop (Alg. 2), or none.
+ * Candidates of token t: its top-k experts; Expanded Drop adds the E/G experts of the token's own
+ * device.  In every capacity segment (expert, or device-block x expert for LOCAL scope) the `cap`
+ * candidates with the highest score are kept; equal scores go to the lower token index.
+ * Outputs (the dispatch plan; B = G for LOCAL scope, 1 for GLOBAL):
+ *   expert_count  [E]     kept pairs per expert
+ *   seg_count     [B,E]   kept pairs per (device block, expert)
+ *   expert_offset [E+1]   exclusive prefix sum of expert_count; expert_offset[E] = P
+ *   row_token     [P_max] token of each row; rows are expert-major, ascending token inside an expert
+ *   row_weight    [P_max] softmax score of the pair (un-renormalised; final_scores of Alg. 1)
+ *   pair_row      [N,S]   row of the token's slot-th candidate expert (candidates in ascending
+ *                         expert id), or -1 if dropped / slot unused
+ * Entries of row_token / row_weight at or beyond P are left untouched.
+ */
+int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,
+                      int32_t* expert_count, int32_t* seg_count, int32_t* expert_offset, int32_t* row_token,
+                      float* row_weight, int32_t* pair_row, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
+ * Permutation (the "permutation" stage of the latency breakdown, Sec. 5.1):
+ * xp[r,:] = x[row_token[r],:] for r < P = expert_offset[E].  xp is [P_max,d]; rows >= P untouched.
+ */
+int moe_dispatch(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
+                 void* xp, void* stream);
+
+/*
+ * Expert computation E_i(x) of Eq. (2) on the permuted rows.  The paper leaves E_i open; here it
+ * is a bias-free SwiGLU FFN: yp[r,:] = W_down[e] ( silu(W_gate[e] xp[r,:]) * (W_up[e] xp[r,:]) ) for
+ * the rows r of expert e, i.e. expert_offset[e] <= r < expert_offset[e+1].
+ *   w_gate, w_up [E,h,d], w_down [E,d,h] in desc->dtype.  bf16: fp32 accumulation on the matrix
+ *   cores, the hidden activation is rounded to bf16 once; d and h must be multiples of 128.
+ *   yp [P_max,d]; rows >= P untouched.
+ */
+int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* expert_offset, const void* w_gate,
+                    const void* w_up, const void* w_down, void* yp, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/*
+ * Weighted sum of Eq. (2) over the surviving pairs: y[t,:] = sum_slots row_weight[r] * yp[r,:],
+ * r = pair_row[t,slot] >= 0, slots in ascending order (= ascending expert id), accumulated in
+ * fp32.  A token with no surviving pair gets y[t,:] = 0.  y is [N,d].
+ */
+int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight, const int32_t* pair_row, void* y,
+                void* stream);
+
+/*
+ * Profiling hook (instrumentation, not part of the method).  While a pair of hipEvent_t (passed as
+ * void*) is attached to a kernel id, every launch of that kernel records `start` before and `stop`
+ * after it on the launch stream; hipEventElapsedTime(start, stop) is then that launch's duration.
+ * Pass NULL events to detach.  The table is process-wide and not thread-safe: attach from the
+ * thread that enqueues the layer.
+ */
+enum {
+    MOE_KERNEL_ROUTER_LOGITS = 0,
+    MOE_KERNEL_SOFTMAX_TOPK = 1,
+    MOE_KERNEL_DROP_PREPARE = 2,
+    MOE_KERNEL_DROP_SELECT = 3,
+    MOE_KERNEL_DROP_EMIT = 4,
+    MOE_KERNEL_DISPATCH = 5,
+    MOE_KERNEL_FFN_SCHEDULE = 6,
+    MOE_KERNEL_FFN_GATE_UP = 7,
+    MOE_KERNEL_FFN_DOWN = 8,
+    MOE_KERNEL_COMBINE = 9,
+    MOE_KERNEL_COUNT = 10
+};
+int moe_profile_attach(int kernel, void* start_event, void* stop_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAPMOE_H */

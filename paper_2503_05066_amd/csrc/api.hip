@@ -1,0 +1,230 @@
+// Host side of the C ABI: argument validation, static sizes, workspace layout, entry points.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace capmoe {
+
+int validate(const moe_desc_t* d) {
+    if (!d) return MOE_ERR_INVALID_ARG;
+    if (d->n_tokens < 0 || d->d_model < 1 || d->n_experts < 1 || d->top_k < 1 || d->d_hidden < 1 ||
+        d->device_groups < 1)
+        return MOE_ERR_INVALID_ARG;
+    if (d->top_k > d->n_experts) return MOE_ERR_INVALID_ARG;
+    if (d->n_tokens % d->device_groups != 0 || d->n_experts % d->device_groups != 0) return MOE_ERR_INVALID_ARG;
+    if (d->mode < MOE_MODE_NONE || d->mode > MOE_MODE_EXPANDED_DROP) return MOE_ERR_INVALID_ARG;
+    if (d->capacity_scope != MOE_SCOPE_LOCAL && d->capacity_scope != MOE_SCOPE_GLOBAL) return MOE_ERR_INVALID_ARG;
+    if (d->dtype != MOE_DTYPE_F32 && d->dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
+    if (std::isnan(d->gamma) || d->gamma < 0.0) return MOE_ERR_INVALID_ARG;
+    if (d->n_experts > kMaxExperts || d->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
+    const int slots = d->top_k + (d->mode == MOE_MODE_EXPANDED_DROP ? d->n_experts / d->device_groups : 0);
+    if (slots > 255) return MOE_ERR_UNSUPPORTED;
+    if ((int64_t)d->n_tokens * d->n_experts >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    if ((int64_t)d->n_tokens * slots >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    // rows are moved in 16-byte pieces
+    const int per16 = d->dtype == MOE_DTYPE_BF16 ? 8 : 4;
+    if (d->d_model % per16 != 0) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+Sizes derive(const moe_desc_t& d) {
+    Sizes s;
+    s.n_blocks = d.capacity_scope == MOE_SCOPE_LOCAL ? d.device_groups : 1;
+    s.seg_tokens = d.n_tokens / s.n_blocks;
+    s.group_experts = d.n_experts / d.device_groups;
+    s.group_tokens = d.n_tokens / d.device_groups;
+    if (d.mode == MOE_MODE_NONE || (std::isinf(d.gamma) && d.gamma > 0)) {
+        s.cap = s.seg_tokens;
+    } else {
+        // capacity as in Alg. 1: gamma times (N*k), divided by E, truncated; never above the segment size
+        const double c = d.gamma * (double)((long long)s.seg_tokens * (long long)d.top_k) / (double)d.n_experts;
+        if (!(c > 0.0))
+            s.cap = 0;
+        else if (c >= (double)s.seg_tokens)
+            s.cap = s.seg_tokens;
+        else
+            s.cap = (int)c;
+    }
+    s.slots = d.top_k + (d.mode == MOE_MODE_EXPANDED_DROP ? s.group_experts : 0);
+    const int64_t by_tokens = (int64_t)d.n_tokens * (s.slots < d.n_experts ? s.slots : d.n_experts);
+    const int64_t by_capacity = (int64_t)s.n_blocks * d.n_experts * s.cap;
+    s.max_rows = by_tokens < by_capacity ? by_tokens : by_capacity;
+    s.elem = d.dtype == MOE_DTYPE_BF16 ? 2 : 4;
+    return s;
+}
+
+DropWorkspace drop_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
+    DropWorkspace w;
+    char* p = (char*)base;
+    size_t off = 0;
+    const size_t ne = (size_t)d.n_tokens * d.n_experts;
+    const size_t segs = (size_t)s.n_blocks * d.n_experts;
+    w.key_t = (uint32_t*)(p + off);
+    off += align256(ne * 4);
+    w.slot_t = (uint8_t*)(p + off);
+    off += align256(ne);
+    w.seg_tau = (uint32_t*)(p + off);
+    off += align256(segs * 4);
+    w.seg_need = (int32_t*)(p + off);
+    off += align256(segs * 4);
+    w.bytes = off;
+    return w;
+}
+
+FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
+    FfnWorkspace w;
+    char* p = (char*)base;
+    size_t off = 0;
+    w.tile_m = d.dtype == MOE_DTYPE_BF16 ? kFfnTileM : kFfnTileMF32;
+    w.max_tiles = (int)(s.max_rows / w.tile_m) + d.n_experts;
+    w.hidden = p + off;
+    off += align256((size_t)(s.max_rows > 0 ? s.max_rows : 1) * d.d_hidden * s.elem);
+    w.tile_expert = (int32_t*)(p + off);
+    off += align256((size_t)w.max_tiles * 4);
+    w.tile_row0 = (int32_t*)(p + off);
+    off += align256((size_t)w.max_tiles * 4);
+    w.tile_rows = (int32_t*)(p + off);
+    off += align256((size_t)w.max_tiles * 4);
+    w.n_tiles = (int32_t*)(p + off);
+    off += 256;
+    w.bytes = off;
+    return w;
+}
+
+ProfileSlot g_profile[MOE_KERNEL_COUNT] = {};
+
+static int ffn_shape_supported(const moe_desc_t& d) {
+    if (d.dtype == MOE_DTYPE_BF16 && (d.d_model % 128 != 0 || d.d_hidden % 128 != 0)) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+}  // namespace capmoe
+
+using namespace capmoe;
+
+static bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported shape or type";
+        case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case MOE_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int moe_profile_attach(int kernel, void* start_event, void* stop_event) {
+    if (kernel < 0 || kernel >= MOE_KERNEL_COUNT) return MOE_ERR_INVALID_ARG;
+    if ((start_event == nullptr) != (stop_event == nullptr)) return MOE_ERR_INVALID_ARG;
+    g_profile[kernel].start = (hipEvent_t)start_event;
+    g_profile[kernel].stop = (hipEvent_t)stop_event;
+    return MOE_OK;
+}
+
+int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, int64_t* max_rows,
+              size_t* workspace_bytes) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    const Sizes s = derive(*desc);
+    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    if (cap) *cap = s.cap;
+    if (slots_per_token) *slots_per_token = s.slots;
+    if (max_rows) *max_rows = s.max_rows;
+    if (workspace_bytes) {
+        const size_t a = drop_workspace(*desc, s, nullptr).bytes;
+        const size_t b = ffn_workspace(*desc, s, nullptr).bytes;
+        *workspace_bytes = a > b ? a : b;
+    }
+    return MOE_OK;
+}
+
+int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                   int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (desc->n_tokens == 0) return MOE_OK;  // nothing to route; empty arrays may be null
+    if (!logits || !scores || !topk_idx || !topk_score) return MOE_ERR_INVALID_ARG;
+    if (!use_given_logits && (!x || !w_router)) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (!use_given_logits) {
+        if (launch_router_logits(*desc, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
+    }
+    if (launch_softmax_topk(*desc, logits, scores, topk_idx, topk_score, st) != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx, int32_t* expert_count,
+                      int32_t* seg_count, int32_t* expert_offset, int32_t* row_token, float* row_weight,
+                      int32_t* pair_row, void* workspace, size_t workspace_bytes, void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (!expert_count || !seg_count || !expert_offset || !workspace) return MOE_ERR_INVALID_ARG;
+    const Sizes s = derive(*desc);
+    // arrays that are empty for this descriptor may be null
+    if (desc->n_tokens > 0 && (!scores || !topk_idx || !pair_row)) return MOE_ERR_INVALID_ARG;
+    if (s.max_rows > 0 && (!row_token || !row_weight)) return MOE_ERR_INVALID_ARG;
+    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    const DropWorkspace ws = drop_workspace(*desc, s, workspace);
+    if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    if (launch_capacity_drop(*desc, s, ws, scores, topk_idx, expert_count, seg_count, expert_offset, row_token,
+                             row_weight, pair_row, (hipStream_t)stream) != hipSuccess)
+        return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+int moe_dispatch(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
+                 void* xp, void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    const Sizes s = derive(*desc);
+    if (s.max_rows == 0) return MOE_OK;  // no row can survive
+    if (!x || !expert_offset || !row_token || !xp) return MOE_ERR_INVALID_ARG;
+    if (misaligned16(x) || misaligned16(xp)) return MOE_ERR_INVALID_ARG;
+    if (launch_dispatch(*desc, s, x, expert_offset, row_token, xp, (hipStream_t)stream) != hipSuccess)
+        return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* expert_offset, const void* w_gate,
+                    const void* w_up, const void* w_down, void* yp, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (!xp || !expert_offset || !w_gate || !w_up || !w_down || !yp || !workspace) return MOE_ERR_INVALID_ARG;
+    if (misaligned16(xp) || misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
+        return MOE_ERR_INVALID_ARG;
+    const int sh = ffn_shape_supported(*desc);
+    if (sh != MOE_OK) return sh;
+    const Sizes s = derive(*desc);
+    const FfnWorkspace ws = ffn_workspace(*desc, s, workspace);
+    if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    if (s.max_rows == 0) return MOE_OK;
+    if (launch_grouped_ffn(*desc, s, ws, xp, expert_offset, w_gate, w_up, w_down, yp, (hipStream_t)stream) !=
+        hipSuccess)
+        return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight, const int32_t* pair_row, void* y,
+                void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (desc->n_tokens == 0) return MOE_OK;
+    if (!yp || !row_weight || !pair_row || !y) return MOE_ERR_INVALID_ARG;
+    if (misaligned16(yp) || misaligned16(y)) return MOE_ERR_INVALID_ARG;
+    const Sizes s = derive(*desc);
+    if (launch_combine(*desc, s, yp, row_weight, pair_row, y, (hipStream_t)stream) != hipSuccess) return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
+}  // extern "C"

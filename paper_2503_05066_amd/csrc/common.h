@@ -1,0 +1,93 @@
+// Internal declarations shared by the capmoe translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "capmoe.h"
+
+namespace capmoe {
+
+constexpr int kMaxExperts = 256;  // 64 tokens x E keys and slots must fit in LDS
+constexpr int kMaxTopK = 64;
+constexpr int kWave = 64;
+
+// Tile heights of the expert GEMMs; the tile schedule in the workspace is built for these.
+constexpr int kFfnTileM = 128;     // bf16 MFMA kernels
+constexpr int kFfnTileMF32 = 16;   // fp32 fallback kernels (tiny layers)
+
+inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// Static sizes derived from a descriptor (host side).
+struct Sizes {
+    int n_blocks;      // capacity blocks B
+    int seg_tokens;    // tokens per capacity segment
+    int cap;           // capacity per segment
+    int slots;         // S
+    int64_t max_rows;  // P_max
+    int group_experts; // m = E / G
+    int group_tokens;  // N / G
+    size_t elem;       // bytes per element of desc->dtype
+};
+
+int validate(const moe_desc_t* d);
+Sizes derive(const moe_desc_t& d);
+
+// Workspace layout of moe_capacity_drop.
+struct DropWorkspace {
+    uint32_t* key_t;    // [E,N]  candidate key (score bits + 1) or 0, expert-major
+    uint8_t* slot_t;    // [E,N]  slot of the pair in the token's candidate list
+    uint32_t* seg_tau;  // [B*E]  threshold key of the segment
+    int32_t* seg_need;  // [B*E]  how many candidates equal to the threshold are kept
+    size_t bytes;
+};
+DropWorkspace drop_workspace(const moe_desc_t& d, const Sizes& s, void* base);
+
+// Workspace layout of moe_grouped_ffn.
+struct FfnWorkspace {
+    void* hidden;         // [P_max, h] activations silu(gate)*up in desc->dtype
+    int32_t* tile_expert; // [max_tiles]
+    int32_t* tile_row0;   // [max_tiles] first row of the tile
+    int32_t* tile_rows;   // [max_tiles] valid rows in the tile
+    int32_t* n_tiles;     // [1]
+    int max_tiles;
+    int tile_m;
+    size_t bytes;
+};
+FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base);
+
+// Event pairs attached by moe_profile_attach; ProfileScope records them around one launch.
+struct ProfileSlot {
+    hipEvent_t start, stop;
+};
+extern ProfileSlot g_profile[MOE_KERNEL_COUNT];
+struct ProfileScope {
+    int id;
+    hipStream_t st;
+    ProfileScope(int id_, hipStream_t st_) : id(id_), st(st_) {
+        if (g_profile[id].start) (void)hipEventRecord(g_profile[id].start, st);
+    }
+    ~ProfileScope() {
+        if (g_profile[id].stop) (void)hipEventRecord(g_profile[id].stop, st);
+    }
+};
+
+// Launchers (each returns a hipError_t from hipGetLastError after its launches).
+hipError_t launch_router_logits(const moe_desc_t& d, const void* x, const float* w, const float* bias, float* logits,
+                                hipStream_t st);
+hipError_t launch_softmax_topk(const moe_desc_t& d, const float* logits, float* scores, int32_t* topk_idx,
+                               float* topk_score, hipStream_t st);
+hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
+                                const int32_t* topk_idx, int32_t* expert_count, int32_t* seg_count,
+                                int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
+                                hipStream_t st);
+hipError_t launch_dispatch(const moe_desc_t& d, const Sizes& s, const void* x, const int32_t* expert_offset,
+                           const int32_t* row_token, void* xp, hipStream_t st);
+hipError_t launch_combine(const moe_desc_t& d, const Sizes& s, const void* yp, const float* row_weight,
+                          const int32_t* pair_row, void* y, hipStream_t st);
+hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
+                              const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
+                              void* yp, hipStream_t st);
+
+}  // namespace capmoe

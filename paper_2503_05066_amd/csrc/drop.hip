@@ -1,0 +1,257 @@
+// Capacity enforcement: Token Drop (Eqs. 8-10, Alg. 1) and Expanded Drop (Alg. 2).
+//
+// Three kernels, all integer work on score bit patterns (scores are >= +0, so the unsigned
+// order of the bits is the order of the values):
+//   1. drop_prepare   per token: candidate set (top-k, plus the experts of the token's own device
+//                     for Expanded Drop) -> key = score bits + 1 for candidates, 0 otherwise,
+//                     written expert-major so that a capacity segment is one contiguous run.
+//   2. drop_select    per segment: the cap-th largest key by a 4-pass radix select over LDS
+//                     histograms (the threshold tau of Eq. 8) and how many keys equal to it survive.
+//   3. drop_emit      per segment: ordered compaction of the survivors (ballot + prefix counts),
+//                     which yields rows in ascending token order and gives ties at the threshold
+//                     to the lower token index.
+#include "common.h"
+
+namespace capmoe {
+
+constexpr int kPrepTokens = 64;
+
+// ---------------------------------------------------------------------------------------------
+// 1. candidate keys, transposed
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restrict__ scores,
+                                                           const int32_t* __restrict__ topk_idx,
+                                                           uint32_t* __restrict__ key_t, uint8_t* __restrict__ slot_t,
+                                                           int32_t* __restrict__ pair_row, int N, int E, int k, int S,
+                                                           int expanded, int group_tokens, int group_experts) {
+    extern __shared__ uint32_t lds[];
+    const int ld = E | 1;                                     // odd row pitch: conflict-free transposed reads
+    uint32_t* key_s = lds;                                    // [64][ld]
+    uint8_t* slot_s = (uint8_t*)(lds + kPrepTokens * ld);     // [64][ld]
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * kPrepTokens;
+
+    // candidate flags: a wave walks 16 tokens, lanes walk experts
+    for (int i = 0; i < 16; ++i) {
+        const int tl = wv * 16 + i;
+        for (int e = lane; e < E; e += kWave) key_s[tl * ld + e] = 0;
+    }
+    __syncthreads();
+    for (int i = 0; i < 16; ++i) {
+        const int tl = wv * 16 + i, t = t0 + tl;
+        if (t >= N) break;
+        if (lane < k) key_s[tl * ld + topk_idx[(size_t)t * k + lane]] = 1;
+        if (expanded) {
+            const int e0 = (t / group_tokens) * group_experts;
+            for (int e = lane; e < group_experts; e += kWave) key_s[tl * ld + e0 + e] = 1;
+        }
+    }
+    __syncthreads();
+    // flags -> keys and slots (slot = number of candidate experts with a lower id)
+    for (int i = 0; i < 16; ++i) {
+        const int tl = wv * 16 + i, t = t0 + tl;
+        if (t >= N) break;
+        int base = 0;
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            const bool c = e < E && key_s[tl * ld + e] != 0;
+            const uint64_t mask = __ballot(c);
+            const int slot = base + __popcll(mask & ((1ull << lane) - 1ull));
+            if (e < E) {
+                key_s[tl * ld + e] = c ? __float_as_uint(scores[(size_t)t * E + e]) + 1u : 0u;
+                slot_s[tl * ld + e] = (uint8_t)slot;
+            }
+            base += __popcll(mask);
+        }
+        // slots beyond the token's candidate count stay unused
+        for (int s = base + lane; s < S; s += kWave) pair_row[(size_t)t * S + s] = -1;
+    }
+    __syncthreads();
+    // transposed write: 64 consecutive tokens of one expert per wave
+    for (int e = wv; e < E; e += 4) {
+        const int t = t0 + lane;
+        if (t < N) {
+            key_t[(size_t)e * N + t] = key_s[lane * ld + e];
+            slot_t[(size_t)e * N + t] = slot_s[lane * ld + e];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 2. threshold per segment
+// ---------------------------------------------------------------------------------------------
+__device__ inline int block_sum_256(int v, int* red) {
+    // red: 4 ints of LDS
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __restrict__ key_t,
+                                                          uint32_t* __restrict__ seg_tau,
+                                                          int32_t* __restrict__ seg_need,
+                                                          int32_t* __restrict__ seg_count, int N, int E, int seg_tokens,
+                                                          int cap) {
+    __shared__ int hist[256];
+    __shared__ int red[4];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_rem;
+    const int seg = blockIdx.x;  // = b*E + e
+    const int b = seg / E, e = seg - b * E;
+    const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
+    const int tid = threadIdx.x;
+
+    int mine = 0;
+    for (int i = tid; i < seg_tokens; i += 256) mine += keys[i] != 0u;
+    const int n_cand = block_sum_256(mine, red);
+
+    if (n_cand <= cap || cap == 0) {
+        if (tid == 0) {
+            // cap == 0: nothing passes; otherwise every candidate (key >= 1) passes
+            seg_tau[seg] = cap == 0 ? 0xffffffffu : 0u;
+            seg_need[seg] = 0;
+            seg_count[seg] = cap == 0 ? 0 : n_cand;
+        }
+        return;
+    }
+    // cap-th largest key, most significant byte first
+    uint32_t prefix = 0;
+    int rem = cap;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+        for (int i = tid; i < seg_tokens; i += 256) {
+            const uint32_t kx = keys[i];
+            if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int acc = 0, dsel = 0;
+            for (int dg = 255; dg >= 0; --dg) {
+                if (acc + hist[dg] >= rem) {
+                    dsel = dg;
+                    break;
+                }
+                acc += hist[dg];
+            }
+            sh_prefix = prefix | ((uint32_t)dsel << shift);
+            sh_rem = rem - acc;
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        rem = sh_rem;
+    }
+    if (tid == 0) {
+        seg_tau[seg] = prefix;  // keys above it are all kept
+        seg_need[seg] = rem;    // and the first `rem` keys equal to it, in token order
+        seg_count[seg] = cap;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 3. ordered compaction
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restrict__ key_t,
+                                                        const uint8_t* __restrict__ slot_t,
+                                                        const uint32_t* __restrict__ seg_tau,
+                                                        const int32_t* __restrict__ seg_need,
+                                                        const int32_t* __restrict__ seg_count,
+                                                        int32_t* __restrict__ expert_count,
+                                                        int32_t* __restrict__ expert_offset,
+                                                        int32_t* __restrict__ row_token, float* __restrict__ row_weight,
+                                                        int32_t* __restrict__ pair_row, int N, int E, int n_blocks,
+                                                        int seg_tokens, int S) {
+    __shared__ int red[4];
+    __shared__ int wave_kept[4], wave_eq[4];
+    const int seg = blockIdx.x;
+    const int b = seg / E, e = seg - b * E;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+    // first row of this segment: all segments of lower experts, then lower blocks of this expert
+    int before = 0, own = 0;
+    for (int i = tid; i < n_blocks * E; i += 256) {
+        const int bb = i / E, ee = i - bb * E;
+        const int c = seg_count[i];
+        if (ee < e || (ee == e && bb < b)) before += c;
+        if (ee == e) own += c;
+    }
+    const int row0 = block_sum_256(before, red);
+    const int own_total = block_sum_256(own, red);
+    if (b == 0 && tid == 0) {
+        expert_count[e] = own_total;
+        expert_offset[e] = row0;
+        if (e == E - 1) expert_offset[E] = row0 + own_total;
+    }
+
+    const uint32_t tau = seg_tau[seg];
+    const int need = seg_need[seg];
+    const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
+    const uint8_t* slots = slot_t + (size_t)e * N + (size_t)b * seg_tokens;
+    int kept_before = 0, eq_before = 0;  // running counts over the chunks already done
+    for (int c0 = 0; c0 < seg_tokens; c0 += 256) {
+        const int i = c0 + tid;
+        const uint32_t kx = i < seg_tokens ? keys[i] : 0u;
+        const bool cand = kx != 0u;
+        const bool eq = cand && kx == tau;
+        const uint64_t eq_mask = __ballot(eq);
+        if (lane == 0) wave_eq[wv] = __popcll(eq_mask);
+        __syncthreads();
+        int eq_rank = eq_before + __popcll(eq_mask & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wv; ++w) eq_rank += wave_eq[w];
+        const bool keep = cand && (kx > tau || (eq && eq_rank < need));
+        const uint64_t keep_mask = __ballot(keep);
+        if (lane == 0) wave_kept[wv] = __popcll(keep_mask);
+        __syncthreads();
+        int pos = kept_before + __popcll(keep_mask & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wv; ++w) pos += wave_kept[w];
+        if (cand) {
+            const int t = b * seg_tokens + i;
+            const int row = row0 + pos;
+            if (keep) {
+                row_token[row] = t;
+                row_weight[row] = __uint_as_float(kx - 1u);
+            }
+            pair_row[(size_t)t * S + slots[i]] = keep ? row : -1;
+        }
+        kept_before += wave_kept[0] + wave_kept[1] + wave_kept[2] + wave_kept[3];
+        eq_before += wave_eq[0] + wave_eq[1] + wave_eq[2] + wave_eq[3];
+        __syncthreads();
+    }
+}
+
+hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
+                                const int32_t* topk_idx, int32_t* expert_count, int32_t* seg_count,
+                                int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
+                                hipStream_t st) {
+    const int N = d.n_tokens, E = d.n_experts;
+    if (N > 0) {
+        const int grid = (N + kPrepTokens - 1) / kPrepTokens;
+        const size_t lds = (size_t)kPrepTokens * (E | 1) * 5;
+        if (lds > 64 * 1024)
+            (void)hipFuncSetAttribute((const void*)drop_prepare_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)lds);
+        ProfileScope prof(MOE_KERNEL_DROP_PREPARE, st);
+        hipLaunchKernelGGL(drop_prepare_kernel, dim3(grid), dim3(256), lds, st, scores, topk_idx, ws.key_t, ws.slot_t,
+                           pair_row, N, E, d.top_k, s.slots, d.mode == MOE_MODE_EXPANDED_DROP ? 1 : 0, s.group_tokens,
+                           s.group_experts);
+    }
+    const int segs = s.n_blocks * E;
+    {
+        ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
+        hipLaunchKernelGGL(drop_select_kernel, dim3(segs), dim3(256), 0, st, ws.key_t, ws.seg_tau, ws.seg_need,
+                           seg_count, N, E, s.seg_tokens, s.cap);
+    }
+    {
+        ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
+        hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, ws.key_t, ws.slot_t, ws.seg_tau,
+                           ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
+                           s.n_blocks, s.seg_tokens, s.slots);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace capmoe

@@ -18,3 +18,13 @@ def orc():
 
     oracle.build()
     return oracle
+
+
+@pytest.fixture(scope="session")
+def built_library():
+    """libcapmoe.so: what is built is loaded; it is compiled only if nothing is there."""
+    from paper_2503_05066_amd import build, capmoe
+
+    if not os.path.exists(capmoe.LIB_PATH):
+        build.build()
+    return capmoe.load()

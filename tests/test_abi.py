@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the header
+declares, sizes come out as the paper's capacity formula says, and bad arguments are refused
+before anything is launched."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2503_05066_amd import capmoe, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.usefixtures("built_library")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "capmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = capmoe.load()
+    names = declared_functions()
+    assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_combine", "moe_query",
+            "moe_status_string"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert capmoe.status_string(0) == "ok" and "workspace" in capmoe.status_string(3)
+
+
+def test_descriptor_layout_matches_header():
+    # 8 int32, one double at offset 32, two int32: 48 bytes
+    assert ctypes.sizeof(capmoe.MoeDesc) == 48 and capmoe.MoeDesc.gamma.offset == 32
+
+
+@pytest.mark.parametrize("name,mode,scope,gamma,cap,slots,rows", [
+    ("tiny", 1, 0, 1.0, 32, 2, 256), ("olmoe", 1, 0, 1.0, 512, 8, 32768), ("olmoe", 1, 0, 1.5, 768, 8, 32768),
+    ("olmoe", 1, 0, 2.0, 1024, 8, 32768), ("mixtral", 1, 0, 1.0, 512, 2, 16384), ("mixtral", 2, 0, 1.0, 512, 4, 16384),
+    ("mixtral", 1, 1, 1.0, 2048, 2, 16384), ("finegrained", 2, 0, 1.0, 128, 24, 131072),
+    ("finegrained", 2, 1, 1.25, 1280, 24, 163840), ("decode", 2, 0, 1.0, 3, 14, 1536),
+    ("olmoe", 0, 0, 1.0, 4096, 8, 32768), ("olmoe", 1, 0, math.inf, 4096, 8, 32768), ("olmoe", 1, 0, 0.0, 0, 8, 0),
+])
+def test_query_sizes(orc, name, mode, scope, gamma, cap, slots, rows):
+    w = synth.WORKLOADS[name]
+    d = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope, gamma,
+                         w.dtype)
+    got = capmoe.moe_query(d)
+    assert got[:3] == (cap, slots, rows)
+    blocks = w.device_groups if scope == 0 else 1
+    if mode != 0:
+        assert cap == orc.capacity(gamma, w.n_tokens // blocks, w.top_k, w.n_experts)
+    assert got[3] > 0
+
+
+def test_capacity_truncation_matches_oracle(orc):
+    for gamma in (1.3, 0.7, 1.1, 2.5, 0.05, 0.999):
+        for n, k, e, g in [(128, 2, 8, 1), (120, 3, 12, 4), (96, 5, 16, 2)]:
+            d = capmoe.make_desc(n, 64, e, k, 128, g, 1, 0, gamma, 0)
+            assert capmoe.moe_query(d)[0] == orc.capacity(gamma, n // g, k, e)
+
+
+def test_bad_arguments_are_refused_on_the_host():
+    lib = capmoe.load()
+    ok = capmoe.make_desc(128, 64, 8, 2, 128)
+    bad = [
+        capmoe.make_desc(128, 64, 8, 9, 128),                   # k > E
+        capmoe.make_desc(130, 64, 8, 2, 128, device_groups=4),  # N not a multiple of G
+        capmoe.make_desc(128, 64, 6, 2, 128, device_groups=4),  # E not a multiple of G
+        capmoe.make_desc(128, 64, 8, 2, 128, gamma=-1.0),
+        capmoe.make_desc(128, 64, 8, 2, 128, gamma=math.nan),
+        capmoe.make_desc(128, 64, 8, 2, 128, mode=7),
+        capmoe.make_desc(128, 64, 8, 2, 128, dtype=5),
+        capmoe.make_desc(128, 0, 8, 2, 128),
+    ]
+    for d in bad:
+        with pytest.raises(capmoe.CapMoeError) as ei:
+            capmoe.moe_query(d)
+        assert ei.value.status == 1
+    with pytest.raises(capmoe.CapMoeError) as ei:
+        capmoe.moe_query(capmoe.make_desc(128, 64, 4096, 2, 128))
+    assert ei.value.status == 2
+    # null pointers: every entry point answers MOE_ERR_INVALID_ARG without launching anything
+    z = ctypes.c_void_p(None)
+    assert lib.moe_route_topk(ctypes.byref(ok), z, z, z, 0, z, z, z, z, z, 0, z) == 1
+    assert lib.moe_capacity_drop(ctypes.byref(ok), z, z, z, z, z, z, z, z, z, 0, z) == 1
+    assert lib.moe_dispatch(ctypes.byref(ok), z, z, z, z, z) == 1
+    assert lib.moe_grouped_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, 0, z) == 1
+    assert lib.moe_combine(ctypes.byref(ok), z, z, z, z, z) == 1
+    assert lib.moe_query(None, None, None, None, None) == 1

@@ -1,0 +1,321 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Integer results (top-k indices, counts, offsets, the dispatch plan) and the fp32 scores must be
+bit-exact given identical fp32 logits; router logits within 1e-4; layer outputs within 1e-4
+(fp32) / 2e-2 (bf16) relative error.  Run with `-m gpu` on an MI355X.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_05066_amd import capmoe, synth
+
+from gpu_util import DeviceLayer, assert_output_close, assert_plan_equal, to_host_f64
+
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("built_library")]
+
+NONE, TD, ED = synth.MODE_NONE, synth.MODE_TOKEN_DROP, synth.MODE_EXPANDED_DROP
+LOCAL, GLOBAL = synth.SCOPE_LOCAL, synth.SCOPE_GLOBAL
+W = synth.WORKLOADS
+TOL = {synth.DTYPE_F32: 1e-4, synth.DTYPE_BF16: 2e-2}
+
+
+def note(*a):
+    print(*a, flush=True)
+
+
+def route_and_drop_gpu(desc, logits_host):
+    """moe_route_topk (given logits) + moe_capacity_drop; returns the buffers."""
+    buf = capmoe.LayerBuffers(desc)
+    if desc.n_tokens:
+        buf.logits.copy_(torch.from_numpy(logits_host))
+    capmoe.moe_route_topk(desc, None, None, None, 1, buf.logits, buf.scores, buf.topk_idx, buf.topk_score,
+                          buf.workspace)
+    capmoe.moe_capacity_drop(desc, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
+                             buf.row_token, buf.row_weight, buf.pair_row, buf.workspace)
+    torch.cuda.synchronize()
+    return buf
+
+
+def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what):
+    note("case", what, dict(n=n, e=e, k=k, g=g, mode=mode, scope=scope, gamma=gamma))
+    desc = capmoe.make_desc(n, 64, e, k, 128, g, mode, scope, gamma, synth.DTYPE_F32)
+    buf = route_and_drop_gpu(desc, logits)
+    ref = orc.route_and_drop(logits, k, g, mode, scope, gamma)
+    assert buf.cap == ref.cap
+    np.testing.assert_array_equal(buf.scores.cpu().numpy().view(np.uint32), ref.scores.view(np.uint32))
+    np.testing.assert_array_equal(buf.topk_idx.cpu().numpy(), ref.topk_idx)
+    np.testing.assert_array_equal(buf.topk_score.cpu().numpy().view(np.uint32), ref.topk_score.view(np.uint32))
+    assert_plan_equal(buf, ref, what)
+    assert ref.plan.rows <= buf.max_rows
+    assert ref.plan.seg_count.max(initial=0) <= ref.cap      # max load <= C
+    return buf, ref
+
+
+# ------------------------------------------------------------------------------------------------
+# router logits
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,n", [("tiny", 128), ("olmoe", 1000), ("decode", 256), ("finegrained", 777)])
+def test_router_logits(orc, name, n):
+    w = synth.scaled(W[name], n_tokens=n, device_groups=1)
+    note("router logits", w)
+    x = synth.tokens(w)
+    wr, b = synth.router_weight(w), synth.router_bias(w)
+    ref = orc.router_logits(x.f32, wr, b)
+    desc = capmoe.make_desc(n, w.d_model, w.n_experts, w.top_k, w.d_hidden, 1, TD, LOCAL, 1.0, w.dtype)
+    buf = capmoe.LayerBuffers(desc)
+    from gpu_util import to_device
+    capmoe.moe_route_topk(desc, to_device(x), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(), 0, buf.logits,
+                          buf.scores, buf.topk_idx, buf.topk_score, buf.workspace)
+    torch.cuda.synchronize()
+    got = buf.logits.cpu().numpy()
+    assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
+    # without bias
+    capmoe.moe_route_topk(desc, to_device(x), torch.from_numpy(wr).cuda(), None, 0, buf.logits, buf.scores,
+                          buf.topk_idx, buf.topk_score, buf.workspace)
+    torch.cuda.synchronize()
+    ref0 = orc.router_logits(x.f32, wr)
+    assert np.abs(buf.logits.cpu().numpy() - ref0).max() <= 1e-4 * np.abs(ref0).max()
+
+
+# ------------------------------------------------------------------------------------------------
+# scores, top-k and the dispatch plan, bit-exact from identical logits
+# ------------------------------------------------------------------------------------------------
+def oracle_logits(orc, w):
+    return orc.router_logits(synth.tokens(w).f32, synth.router_weight(w), synth.router_bias(w))
+
+
+FULL_CASES = [
+    ("tiny", NONE, LOCAL, 1.0), ("tiny", TD, LOCAL, 1.0),
+    ("olmoe", NONE, LOCAL, 1.0), ("olmoe", TD, LOCAL, 1.0), ("olmoe", TD, LOCAL, 1.5), ("olmoe", TD, LOCAL, 2.0),
+    ("mixtral", NONE, LOCAL, 1.0), ("mixtral", TD, LOCAL, 1.0), ("mixtral", ED, LOCAL, 1.0),
+    ("mixtral", TD, GLOBAL, 1.0), ("mixtral", ED, GLOBAL, 1.0),
+    ("finegrained", TD, LOCAL, 1.0), ("finegrained", ED, LOCAL, 1.0), ("finegrained", ED, LOCAL, 1.25),
+    ("finegrained", ED, GLOBAL, 1.25),
+    ("decode", TD, LOCAL, 1.0), ("decode", ED, LOCAL, 1.0), ("decode", ED, GLOBAL, 1.0),
+]
+_logit_cache = {}
+
+
+@pytest.mark.parametrize("name,mode,scope,gamma", FULL_CASES)
+def test_plan_full_size(orc, name, mode, scope, gamma):
+    w = W[name]
+    if name not in _logit_cache:
+        _logit_cache[name] = oracle_logits(orc, w)
+    check_route_and_plan(orc, _logit_cache[name], w.n_tokens, w.n_experts, w.top_k, w.device_groups, mode, scope,
+                         gamma, f"{name} full size")
+
+
+@pytest.mark.parametrize("n,e,k,g,mode,scope,gamma", [
+    (1000, 8, 2, 1, TD, GLOBAL, 1.0),       # segment longer than a block, ragged tail
+    (1000, 10, 3, 5, ED, LOCAL, 0.8),
+    (300, 3, 1, 3, ED, GLOBAL, 1.3),
+    (96, 12, 12, 4, TD, LOCAL, 1.0),        # k = E: every expert is a candidate of every token
+    (64, 100, 7, 4, ED, LOCAL, 2.0),        # E not a multiple of the wave width
+    (520, 200, 9, 8, ED, LOCAL, 1.0),
+    (64, 256, 64, 1, TD, GLOBAL, 1.0),      # largest top-k
+    (4, 4, 2, 4, ED, LOCAL, 1.0),           # one token per device
+    (1, 8, 2, 1, TD, GLOBAL, 1.0),
+    (512, 16, 4, 4, TD, LOCAL, 0.0),        # gamma = 0 drops everything
+    (512, 16, 4, 4, ED, GLOBAL, math.inf),  # no limit: all k+m candidates survive
+    (512, 16, 4, 4, NONE, GLOBAL, 0.3),     # mode none ignores gamma
+    (5000, 8, 2, 1, TD, GLOBAL, 0.05),
+])
+def test_plan_edge_shapes(orc, n, e, k, g, mode, scope, gamma):
+    rng = np.random.default_rng(n * 7 + e)
+    logits = (rng.standard_normal((n, e)) * 2 + rng.standard_normal(e)[None, :] * 1.5).astype(np.float32)
+    check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, "edge shape")
+
+
+@pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (TD, LOCAL, 4), (ED, LOCAL, 4), (ED, GLOBAL, 8)])
+def test_plan_with_forced_ties(orc, mode, scope, g):
+    w = synth.scaled(W["olmoe"], n_tokens=2048, n_experts=32, top_k=4, device_groups=g)
+    logits = synth.logits_with_ties(w)
+    buf, ref = check_route_and_plan(orc, logits, w.n_tokens, w.n_experts, w.top_k, g, mode, scope, 1.0, "ties")
+    # the input really ties at thresholds: some segment keeps only part of a run of equal scores
+    s, kp, cd = ref.scores, ref.keep.astype(bool), ref.cand.astype(bool)
+    partial = 0
+    for j in range(w.n_experts):
+        kept_scores = set(s[kp[:, j], j].tolist())
+        dropped_scores = set(s[cd[:, j] & ~kp[:, j], j].tolist())
+        partial += len(kept_scores & dropped_scores)
+    assert partial > 0
+
+
+def test_peaked_logits_zero_scores(orc):
+    # scores that underflow to exactly 0 are still ranked as candidates
+    n, e = 256, 16
+    logits = np.zeros((n, e), np.float32)
+    logits[:, 3] = 300.0
+    check_route_and_plan(orc, logits, n, e, 2, 1, TD, GLOBAL, 1.0, "peaked")
+    check_route_and_plan(orc, logits, n, e, 2, 4, ED, LOCAL, 1.0, "peaked expanded")
+
+
+def test_empty_batch():
+    desc = capmoe.make_desc(0, 64, 8, 2, 128, 1, TD, GLOBAL, 1.0, synth.DTYPE_F32)
+    buf = route_and_drop_gpu(desc, np.zeros((0, 8), np.float32))
+    assert buf.expert_count.cpu().numpy().sum() == 0 and buf.expert_offset.cpu().numpy().max() == 0
+    capmoe.moe_dispatch(desc, buf.xp, buf.expert_offset, buf.row_token, buf.xp)
+    capmoe.moe_combine(desc, buf.yp, buf.row_weight, buf.pair_row, buf.y)
+    torch.cuda.synchronize()
+
+
+def test_workspace_too_small_is_refused():
+    desc = capmoe.make_desc(128, 64, 8, 2, 128, 1, TD, GLOBAL, 1.0, synth.DTYPE_F32)
+    buf = capmoe.LayerBuffers(desc)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(capmoe.CapMoeError) as ei:
+        capmoe.moe_capacity_drop(desc, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
+                                 buf.row_token, buf.row_weight, buf.pair_row, small)
+    assert ei.value.status == 3
+    with pytest.raises(capmoe.CapMoeError) as ei:
+        capmoe.moe_grouped_ffn(desc, buf.xp, buf.expert_offset, buf.xp, buf.xp, buf.xp, buf.yp, small)
+    assert ei.value.status == 3
+    bad = capmoe.make_desc(128, 200, 8, 2, 128, 1, TD, GLOBAL, 1.0, synth.DTYPE_BF16)   # d not a multiple of 128
+    with pytest.raises(capmoe.CapMoeError) as ei:
+        capmoe.moe_grouped_ffn(bad, buf.xp, buf.expert_offset, buf.xp, buf.xp, buf.xp, buf.yp, buf.workspace)
+    assert ei.value.status == 2
+
+
+# ------------------------------------------------------------------------------------------------
+# whole layer
+# ------------------------------------------------------------------------------------------------
+def run_layer(layer: DeviceLayer, desc, logits_host=None):
+    buf = capmoe.LayerBuffers(desc)
+    given = torch.from_numpy(logits_host).cuda() if logits_host is not None else None
+    capmoe.layer_forward(buf, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down, given)
+    torch.cuda.synchronize()
+    return buf
+
+
+def check_layer(orc, layer, mode, scope, gamma, tokens=None, what=""):
+    w = layer.w
+    note("layer", what, w.name, dict(mode=mode, scope=scope, gamma=gamma))
+    logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
+    ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma)
+    desc = layer.desc(mode, scope, gamma)
+    buf = run_layer(layer, desc, logits)
+    assert_plan_equal(buf, ref, what)
+    rows = ref.plan.rows
+    # permutation: rows of xp are the rows of x named by the plan, bit for bit
+    xp = buf.xp[:rows].view(torch.int16 if w.dtype == synth.DTYPE_BF16 else torch.int32).cpu().numpy()
+    xsrc = layer.x.view(torch.int16 if w.dtype == synth.DTYPE_BF16 else torch.int32).cpu().numpy()
+    np.testing.assert_array_equal(xp, xsrc[ref.plan.row_token])
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down,
+                             token_list=tokens)
+    y = to_host_f64(buf.y)
+    if tokens is not None:
+        y = y[tokens]
+    assert np.all(np.isfinite(to_host_f64(buf.y)))
+    assert_output_close(y, y_ref, TOL[w.dtype], what)
+    return buf, ref
+
+
+def test_layer_tiny_fp32(orc):
+    layer = DeviceLayer(W["tiny"])
+    for mode, scope, gamma in [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (TD, LOCAL, 0.5), (TD, LOCAL, math.inf)]:
+        check_layer(orc, layer, mode, scope, gamma, what="tiny")
+    layer4 = DeviceLayer(synth.scaled(W["tiny"], device_groups=4))
+    for scope in (LOCAL, GLOBAL):
+        check_layer(orc, layer4, ED, scope, 1.0, what="tiny expanded")
+
+
+@pytest.mark.parametrize("n,d,e,k,h,g", [(640, 256, 8, 2, 384, 4), (1536, 128, 16, 4, 128, 2), (300, 384, 4, 2, 256, 1)])
+def test_layer_reduced_bf16(orc, n, d, e, k, h, g):
+    # several row tiles per expert with ragged tails, several column tiles, empty experts possible
+    w = synth.scaled(W["olmoe"], name="reduced", n_tokens=n, d_model=d, n_experts=e, top_k=k, d_hidden=h,
+                     device_groups=g, skew="normal", skew_param=1.5)
+    layer = DeviceLayer(w)
+    for mode, scope, gamma in [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (ED, LOCAL, 1.0), (ED, GLOBAL, 1.5),
+                               (TD, GLOBAL, 0.0)]:
+        check_layer(orc, layer, mode, scope, gamma, what="reduced bf16")
+
+
+def test_ffn_ragged_expert_sizes(orc):
+    # expert row counts around the tile height: 0, 1, 127, 128, 129, 300, 5, 0
+    counts = [0, 1, 127, 128, 129, 300, 5, 0]
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="ragged", n_tokens=n, d_model=256, n_experts=e, top_k=1, d_hidden=256,
+                     device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    np.random.default_rng(5).shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    buf = run_layer(layer, layer.desc(NONE, GLOBAL, 1.0), logits)
+    assert_plan_equal(buf, ref, "ragged")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "ragged")
+
+
+def sample_tokens(ref, n, count, seed):
+    rng = np.random.default_rng(seed)
+    kept_per_token = ref.keep.sum(1)
+    picks = list(rng.choice(n, size=count, replace=False))
+    empty = np.flatnonzero(kept_per_token == 0)
+    if len(empty):
+        picks += list(empty[:2])                       # tokens that lost every expert
+    picks += [0, n - 1, int(np.argmax(kept_per_token))]  # ends of the batch, the token with most experts
+    return np.array(sorted(set(int(p) for p in picks)), np.int32)
+
+
+@pytest.mark.parametrize("name,cases,count", [
+    ("olmoe", [(TD, LOCAL, 1.0), (TD, LOCAL, 2.0), (NONE, LOCAL, 1.0)], 48),
+    ("decode", [(TD, LOCAL, 1.0), (ED, LOCAL, 1.0)], 24),
+    ("finegrained", [(ED, LOCAL, 1.0), (ED, LOCAL, 1.25)], 32),
+    ("mixtral", [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (ED, LOCAL, 1.0)], 10),
+])
+def test_layer_full_size_sampled(orc, name, cases, count):
+    """The launch configuration the benchmark times, checked on sampled tokens the oracle computes one by one."""
+    w = W[name]
+    layer = DeviceLayer(w)
+    logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
+    for mode, scope, gamma in cases:
+        ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma)
+        toks = sample_tokens(ref, w.n_tokens, count, 11)
+        check_layer(orc, layer, mode, scope, gamma, tokens=toks, what="full size sampled")
+    del layer
+    torch.cuda.empty_cache()
+
+
+def test_own_router_end_to_end_properties(orc):
+    """The timed path (own router GEMM): its plan obeys the method's invariants for its own scores,
+    the result is deterministic, and it agrees with the oracle wherever the routing decisions agree."""
+    w = synth.scaled(W["olmoe"], n_tokens=1024, d_model=512, d_hidden=256, n_experts=32, top_k=4)
+    layer = DeviceLayer(w)
+    desc = layer.desc(TD, LOCAL, 1.0)
+    a = run_layer(layer, desc)
+    b = run_layer(layer, desc)
+    assert torch.equal(a.y, b.y) and torch.equal(a.row_token, b.row_token) and torch.equal(a.pair_row, b.pair_row)
+    scores, idx = a.scores.cpu().numpy(), a.topk_idx.cpu().numpy()
+    cnt, off = a.expert_count.cpu().numpy(), a.expert_offset.cpu().numpy()
+    rows = int(off[-1])
+    tok, wt = a.row_token.cpu().numpy()[:rows], a.row_weight.cpu().numpy()[:rows]
+    cand = np.zeros_like(scores, dtype=bool)
+    cand[np.arange(w.n_tokens)[:, None], idx] = True
+    loads = cand.sum(0)
+    np.testing.assert_array_equal(cnt, np.minimum(loads, a.cap))       # kept = min(load, C); max load <= C
+    assert loads.sum() == w.n_tokens * w.top_k
+    for j in range(w.n_experts):
+        t = tok[off[j]:off[j + 1]]
+        assert np.all(np.diff(t) > 0) and np.all(cand[t, j])
+        np.testing.assert_array_equal(wt[off[j]:off[j + 1]], scores[t, j])
+        dropped = np.setdiff1d(np.flatnonzero(cand[:, j]), t)
+        if len(dropped):
+            assert scores[t, j].min() >= scores[dropped, j].max()
+    # against the oracle: logits close, and y close on tokens whose candidate sets agree
+    ref_logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
+    assert np.abs(a.logits.cpu().numpy() - ref_logits).max() <= 1e-4 * np.abs(ref_logits).max()
+    ref = orc.route_and_drop(ref_logits, w.top_k, 1, TD, LOCAL, 1.0)
+    keep_gpu = np.zeros_like(ref.keep)
+    for j in range(w.n_experts):
+        keep_gpu[tok[off[j]:off[j + 1]], j] = 1
+    same = np.flatnonzero((keep_gpu == ref.keep).all(1))
+    assert len(same) > 0.97 * w.n_tokens
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down,
+                             token_list=same.astype(np.int32))
+    assert_output_close(to_host_f64(a.y)[same], y_ref, TOL[w.dtype], "own router")
