@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the capacity-aware MoE layer forward on one MI355X.
+
+A step is one pass of the whole hot path (route+top-k, capacity drop, dispatch, grouped FFN,
+combine: the five C-ABI calls back to back on one stream) over one batch of synthetic,
+skew-routed input that is already resident in HBM.  Prints ONE JSON line:
+  value            tokens/s of the layer (N * steps / wall time between two device syncs)
+  roofline         the dominant kernel (gate/up GEMM with the SwiGLU epilogue), timed per launch
+                   with HIP events recorded by the library around that kernel inside the timed loop
+  cpu_baseline     the CPU oracle on a bounded sample of the same workload, on the host cores
+  stages / other_workloads   per-kernel times and further configurations, for context
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 matrix peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+MODES = {"none": 0, "token": 1, "expanded": 2}
+SCOPES = {"local": 0, "global": 1}
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--workload", default="olmoe", help="tiny | olmoe | mixtral | finegrained | decode")
+    p.add_argument("--mode", default="token", choices=list(MODES))
+    p.add_argument("--scope", default="local", choices=list(SCOPES))
+    p.add_argument("--gamma", type=float, default=1.0)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none",
+                   help="comma list of workload:mode measured after the main line ('' for none)")
+    return p.parse_args()
+
+
+def upload(w):
+    """Synthetic inputs of a workload as device tensors (storage type of the workload)."""
+    import numpy as np
+    import torch
+
+    from paper_2503_05066_amd import synth
+
+    def dev(st):
+        if st.bits is not None:
+            return torch.from_numpy(st.bits.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(st.f32).cuda()
+
+    act = torch.bfloat16 if w.dtype == synth.DTYPE_BF16 else torch.float32
+    e, h, d = w.n_experts, w.d_hidden, w.d_model
+    t = {"x": dev(synth.tokens(w)), "w_router": torch.from_numpy(synth.router_weight(w)).cuda(),
+         "bias": torch.from_numpy(synth.router_bias(w)).cuda(),
+         "w_gate": torch.empty((e, h, d), dtype=act, device="cuda"),
+         "w_up": torch.empty((e, h, d), dtype=act, device="cuda"),
+         "w_down": torch.empty((e, d, h), dtype=act, device="cuda")}
+    for j in range(e):
+        g, u, dn = synth.expert_weights(w, j, keep_f32=False)
+        t["w_gate"][j].copy_(dev(g))
+        t["w_up"][j].copy_(dev(u))
+        t["w_down"][j].copy_(dev(dn))
+    return t
+
+
+def algorithmic_work(w, S, rows, active, elem):
+    """Bytes each kernel must move and flops it must do for `rows` surviving pairs."""
+    n, d, e, k, h = w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden
+    m = S - k
+    return {
+        "router_logits": {"bytes": n * d * elem + e * d * 4 + n * e * 4, "flops": 2 * n * d * e},
+        "softmax_topk": {"bytes": 2 * n * e * 4 + n * k * 8, "flops": 0},
+        "drop": {"bytes": n * k * 8 + n * m * 4 + rows * 8 + n * S * 4, "flops": 0},
+        "dispatch": {"bytes": 2 * rows * d * elem, "flops": 0},
+        "ffn_gate_up": {"bytes": active * 2 * h * d * elem + rows * (d + h) * elem, "flops": 4 * d * h * rows},
+        "ffn_down": {"bytes": active * h * d * elem + rows * (d + h) * elem, "flops": 2 * d * h * rows},
+        "combine": {"bytes": rows * d * elem + n * d * elem, "flops": 0},
+    }
+
+
+def measure(w, mode, scope, gamma, steps, warmup):
+    import torch
+
+    from paper_2503_05066_amd import capmoe, synth
+
+    t = upload(w)
+    desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
+                            gamma, w.dtype)
+    buf = capmoe.LayerBuffers(desc)
+    K_GU = capmoe.KERNELS.index("ffn_gate_up")
+
+    def step():
+        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"])
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in pairs:      # materialise the events before the timed region
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in pairs:
+        capmoe.moe_profile_attach(K_GU, a, b)
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    capmoe.moe_profile_attach(K_GU, None, None)
+    gu_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
+
+    # per-kernel durations, one kernel at a time, outside the timed region
+    kernel_ms = {}
+    reps = max(5, min(steps, 20))
+    for kid, name in enumerate(capmoe.KERNELS):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        for a, b in evs:
+            capmoe.moe_profile_attach(kid, a, b)
+            step()
+        torch.cuda.synchronize()
+        capmoe.moe_profile_attach(kid, None, None)
+        kernel_ms[name] = sum(a.elapsed_time(b) for a, b in evs) / reps
+
+    rows = int(buf.expert_offset[-1])
+    counts = buf.expert_count.cpu().numpy()
+    active = int((counts > 0).sum())
+    elem = 2 if w.dtype == synth.DTYPE_BF16 else 4
+    work = algorithmic_work(w, buf.slots, rows, active, elem)
+    nbar = w.n_tokens * w.top_k / w.n_experts
+    res = {
+        "wall_s": wall, "ms_per_step": 1e3 * wall / steps, "tokens_per_s": w.n_tokens * steps / wall,
+        "gate_up_ms": gu_ms, "kernel_ms": kernel_ms, "rows": rows, "active_experts": active, "cap": buf.cap,
+        "max_rows": buf.max_rows, "work": work, "max_load_over_mean": float(counts.max() / nbar),
+        "max_segment_load": int(buf.seg_count.max()), "kept_fraction": rows / (w.n_tokens * w.top_k),
+    }
+    del t, buf
+    torch.cuda.empty_cache()
+    return res
+
+
+def roofline_of(work, ms):
+    """The binding roof of a kernel: the larger of its MFMA time and its HBM time at peak."""
+    t_mfma = work["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    t_hbm = work["bytes"] / (HBM_PEAK_GBS * 1e9)
+    sec = ms * 1e-3
+    mfma = {"bound": "mfma", "achieved": work["flops"] / sec / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s"}
+    hbm = {"bound": "hbm", "achieved": work["bytes"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    for r in (mfma, hbm):
+        r["frac"] = r["achieved"] / r["peak"]
+        r["traffic"] = None
+    return (mfma, hbm) if t_mfma >= t_hbm else (hbm, mfma)
+
+
+def cpu_baseline(w, mode, scope, gamma):
+    """The oracle, as it stands, on the host cores: routing on the full batch, FFN on a token sample."""
+    import numpy as np
+
+    from oracle import oracle
+    from paper_2503_05066_amd import synth
+
+    x = synth.tokens(w).f32
+    wr, b = synth.router_weight(w), synth.router_bias(w)
+    t0 = time.perf_counter()
+    logits = oracle.router_logits(x, wr, b)
+    ref = oracle.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma)
+    t_route = time.perf_counter() - t0
+    rng = np.random.default_rng(1)
+    # grow the sample until the FFN leg takes a few seconds
+    sample = 16
+    weights = {}
+    while True:
+        toks = np.sort(rng.choice(w.n_tokens, size=min(sample, w.n_tokens), replace=False)).astype(np.int32)
+        need = np.flatnonzero(ref.keep[toks].sum(0))
+        for j in need:
+            if j not in weights:
+                weights[j] = tuple(s.f32 for s in synth.expert_weights(w, int(j)))
+        tabs = [[weights[j][i] if j in weights else None for j in range(w.n_experts)] for i in range(3)]
+        t0 = time.perf_counter()
+        oracle.layer_output(x, ref.scores, ref.keep, tabs[0], tabs[1], tabs[2], token_list=toks)
+        t_ffn = time.perf_counter() - t0
+        if t_ffn > 4.0 or len(toks) >= w.n_tokens or sample >= 4096:
+            break
+        sample *= 4
+    n_s = len(toks)
+    est = t_route * n_s / w.n_tokens + t_ffn   # seconds for n_s tokens
+    return {"value": n_s / est, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"routing+drop on all {w.n_tokens} tokens ({t_route:.2f} s, prorated), expert FFN+combine on "
+                      f"{n_s} sampled tokens ({t_ffn:.2f} s)"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2503_05066_amd import build, capmoe, synth
+
+    if not os.path.exists(capmoe.LIB_PATH):
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[a.workload]
+    mode, scope = MODES[a.mode], SCOPES[a.scope]
+    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup)
+    primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
+    primary["kernel"] = other["kernel"] = "grouped_gemm_bf16_kernel<SWIGLU> (gate/up GEMM + SwiGLU)"
+    stages = {}
+    km = r["kernel_ms"]
+    drop_ms = km["drop_prepare"] + km["drop_select"] + km["drop_emit"]
+    for name, ms in [("router_logits", km["router_logits"]), ("softmax_topk", km["softmax_topk"]), ("drop", drop_ms),
+                     ("dispatch", km["dispatch"]), ("ffn_gate_up", km["ffn_gate_up"]), ("ffn_down", km["ffn_down"]),
+                     ("combine", km["combine"])]:
+        wk = r["work"][name]
+        stages[name] = {"ms": round(ms, 4), "GB/s": round(wk["bytes"] / ms / 1e6, 1),
+                        "hbm_frac": round(wk["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        if wk["flops"]:
+            stages[name]["TFLOP/s"] = round(wk["flops"] / ms / 1e9, 2)
+    out = {
+        "metric": "MoE-layer tokens/sec at gamma=1.0 (Token & Expanded Drop); % MFMA/HBM roofline",
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.n_tokens} d={w.d_model} E={w.n_experts} k={w.top_k} h={w.d_hidden} "
+                               f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity",
+                   "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
+                   "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
+                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3)},
+        "roofline": primary, "roofline_other_roof": other, "stages": stages,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, mode, scope, a.gamma)
+    others = []
+    for item in [s for s in a.others.split(",") if s]:
+        name, m = item.split(":")
+        if name == a.workload and m == a.mode:
+            continue
+        ow = synth.WORKLOADS[name]
+        o = measure(ow, MODES[m], scope, a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5))
+        p1, p2 = roofline_of(o["work"]["ffn_gate_up"], o["gate_up_ms"])
+        d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
+        others.append({"workload": name, "mode": m, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
+                       "ms_per_step": o["ms_per_step"], "surviving_pairs": o["rows"], "cap": o["cap"],
+                       "max_segment_load": o["max_segment_load"], "ffn_gate_up": p1, "ffn_down": d1,
+                       "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
+    if others:
+        out["other_workloads"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
