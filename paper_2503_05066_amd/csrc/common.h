@@ -14,7 +14,7 @@ constexpr int kMaxTopK = 64;
 constexpr int kWave = 64;
 
 // Tile heights of the expert GEMMs; the tile schedule in the workspace is built for these.
-constexpr int kFfnTileM = 128;     // bf16 MFMA kernels
+constexpr int kFfnTileM = 256;     // bf16 MFMA kernels
 constexpr int kFfnTileMF32 = 16;   // fp32 fallback kernels (tiny layers)
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }

@@ -106,60 +106,100 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     return ra | rb;
 }
 
-// Block tile: BM activation rows x BN weight rows, K slab BK; 4 waves as 2 (M) x 2 (N).
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// Block tile: BM activation rows x BN weight rows, K slab of 64; WAVES_M x WAVES_N wavefronts.
+//
+// LDS holds two stages; a stage is (BM + BN) rows of 128 bytes.  Rows are filled by direct
+// global->LDS loads: one wave-wide load writes 8 rows (64 lanes x 16 bytes, contiguous in LDS), and
+// each lane chooses WHICH 16-byte piece of its row it fetches, so that piece kc of row r lands at
+// position kc ^ ((r >> 1) & 7): with 64 LDS banks a 16-lane group of a 16-byte read then touches
+// 16 different bank groups, for the fill as well as for the MFMA operand reads.
+//
 // SWIGLU: weight rows [0,BN/2) of the tile come from W_gate, [BN/2,BN) from W_up, for the same
 // BN/2 hidden columns; a wave holds matching gate and up columns and applies silu(g)*u itself.
-template <int BM, int BN, int BK, bool SWIGLU>
-__global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(const uint16_t* __restrict__ A,
-                                                                const uint16_t* __restrict__ B0,
-                                                                const uint16_t* __restrict__ B1,
-                                                                uint16_t* __restrict__ C,
-                                                                const int32_t* __restrict__ tile_expert,
-                                                                const int32_t* __restrict__ tile_row0,
-                                                                const int32_t* __restrict__ tile_rows,
-                                                                const int32_t* __restrict__ n_tiles, int K, int Nout) {
-    constexpr int CPR = BK / 8;             // 16-byte pieces per tile row
-    constexpr int WM = BM / 2, WN = BN / 2;  // wave tile
-    constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_PIECES = BM * CPR / 256, B_PIECES = BN * CPR / 256;
-    constexpr int STAGE = (BM + BN) * BK;  // bf16 elements per stage
-    static_assert(CPR == 8 || CPR == 4, "BK must be 32 or 64");
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
+//
+// Blocks are numbered so that each XCD (block id mod 8) walks a contiguous range of tiles, ordered
+// [column group][row tile][column in group]: blocks that run together share row and weight tiles in
+// their XCD's L2.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
+    uint16_t* __restrict__ C, const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ tile_row0,
+    const int32_t* __restrict__ tile_rows, const int32_t* __restrict__ n_tiles, int K, int Nout, int col_group) {
+    constexpr int BK = 64;
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int A_GROUPS = BM / 8, GROUPS = (BM + BN) / 8;  // 8-row groups of a stage
+    constexpr int LOADS = GROUPS / NW;                         // wave-wide loads per wave per stage
+    constexpr int STAGE_BYTES = (BM + BN) * 128;
+    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;  // output columns per block
+    static_assert(GROUPS % NW == 0, "loads must divide evenly over the waves");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
     static_assert(!SWIGLU || TN % 2 == 0, "a wave needs matching gate and up columns");
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
-    const int ncols = SWIGLU ? BN / 2 : BN;  // output columns per block
+    // ---- which tile ----
     const int nt = *n_tiles;
-    if (nt == 0) return;
-    const int tile = blockIdx.x % nt, nb = blockIdx.x / nt;  // row tiles vary fastest
-    if (nb * ncols >= Nout) return;
+    const int nb_total = Nout / NCOLS;
+    const int total = nt * nb_total;
+    const int chunk = (total + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int logical = xcd * chunk + slot;
+    if (slot >= chunk || logical >= total) return;
+    const int per_group = nt * col_group;
+    const int cg = logical / per_group, rem = logical - cg * per_group;
+    const int tile = rem / col_group, nb = cg * col_group + (rem - tile * col_group);
     const int e = tile_expert[tile], row0 = tile_row0[tile], rows = tile_rows[tile];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wm = wv & 1, wn = wv >> 1;
-    const int n0 = nb * ncols;
+    const int n0 = nb * NCOLS;
 
-    // per-thread source pointers of the pieces this thread stages
-    const uint16_t* a_src[A_PIECES];
-    const uint16_t* b_src[B_PIECES];
-    int a_dst[A_PIECES], b_dst[B_PIECES];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv % WAVES_M, wn = wv / WAVES_M;
+
+    // ---- sources of this lane's pieces ----
+    const uint16_t* src[LOADS];
 #pragma unroll
-    for (int i = 0; i < A_PIECES; ++i) {
-        const int c = tid + 256 * i, r = c / CPR, kc = c % CPR;
-        const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
-        a_src[i] = A + (size_t)(row0 + rr) * K + kc * 8;
-        a_dst[i] = (r * CPR + (kc ^ (CPR == 8 ? (r & 7) : ((r >> 1) & 3)))) * 8;
+    for (int i = 0; i < LOADS; ++i) {
+        const int g = wv + NW * i;           // row group inside the stage (wave-uniform)
+        const int r = g * 8 + (lane >> 3);   // row inside the stage: A rows first, then weight rows
+        const int kc = (lane & 7) ^ ((r >> 1) & 7);
+        if (g < A_GROUPS) {
+            const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
+            src[i] = A + (size_t)(row0 + rr) * K + kc * 8;
+        } else {
+            const int rb = r - BM;
+            if (SWIGLU && rb >= BN / 2)
+                src[i] = B1 + ((size_t)e * Nout + n0 + rb - BN / 2) * K + kc * 8;
+            else
+                src[i] = B0 + ((size_t)e * Nout + n0 + rb) * K + kc * 8;
+        }
+    }
+
+    // ---- LDS offsets of this lane's operand pieces (k-step 0; later steps flip piece bits) ----
+    const int lr = lane & 31, lk = lane >> 5;
+    int a_off[TM], a_sw[TM], b_off[TN], b_sw[TN];
+    bool m_live[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int r = wm * WTM + j * 32 + lr;
+        a_off[j] = r * 128;
+        a_sw[j] = (r >> 1) & 7;
+        m_live[j] = wm * WTM + j * 32 < rows;  // wave-uniform: skip sub-tiles past the expert's end
     }
 #pragma unroll
-    for (int i = 0; i < B_PIECES; ++i) {
-        const int c = tid + 256 * i, r = c / CPR, kc = c % CPR;
-        const uint16_t* base;
-        if (SWIGLU)
-            base = (r < BN / 2 ? B0 + ((size_t)e * Nout + n0 + r) * K : B1 + ((size_t)e * Nout + n0 + r - BN / 2) * K);
-        else
-            base = B0 + ((size_t)e * Nout + n0 + r) * K;
-        b_src[i] = base + kc * 8;
-        b_dst[i] = BM * BK + (r * CPR + (kc ^ (CPR == 8 ? (r & 7) : ((r >> 1) & 3)))) * 8;
+    for (int i = 0; i < TN; ++i) {
+        int r;
+        if (SWIGLU) {
+            const int half = i / (TN / 2), idx = i % (TN / 2);
+            r = half * (BN / 2) + wn * (WTN / 2) + idx * 32 + lr;
+        } else {
+            r = wn * WTN + i * 32 + lr;
+        }
+        b_off[i] = BM * 128 + r * 128;
+        b_sw[i] = (r >> 1) & 7;
     }
 
     f32x16 acc[TN][TM];
@@ -170,73 +210,54 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(const uint16_t* 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 a_reg[A_PIECES], b_reg[B_PIECES];
-    auto load_global = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < A_PIECES; ++i) a_reg[i] = *(const uint4*)(a_src[i] + (size_t)kt * BK);
-#pragma unroll
-        for (int i = 0; i < B_PIECES; ++i) b_reg[i] = *(const uint4*)(b_src[i] + (size_t)kt * BK);
-    };
-    auto store_lds = [&](int buf) {
-        uint16_t* s = smem + buf * STAGE;
-#pragma unroll
-        for (int i = 0; i < A_PIECES; ++i) *(uint4*)(s + a_dst[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_PIECES; ++i) *(uint4*)(s + b_dst[i]) = b_reg[i];
-    };
-
-    // LDS row of the weight sub-tile tn of this wave (SWIGLU: first half gate, second half up)
-    auto w_row = [&](int tn) {
-        if (SWIGLU) {
-            const int half = tn / (TN / 2), idx = tn % (TN / 2);
-            return half * (BN / 2) + wn * (WN / 2) + idx * 32;
-        }
-        return wn * WN + tn * 32;
-    };
-
     const int KT = K / BK;
-    load_global(0);
-    store_lds(0);
+    // prologue: stage 0
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i)
+        __builtin_amdgcn_global_load_lds((gptr_t)src[i], (lptr_t)(smem + (wv + NW * i) * 1024), 16, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's pieces have landed
     __syncthreads();
-    const int lr = lane & 31, lk = lane >> 5;
+
     for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) load_global(kt + 1);
-        const uint16_t* s = smem + (kt & 1) * STAGE;
+        const int cur = kt & 1;
+        if (kt + 1 < KT) {
+            uint8_t* dst = smem + (cur ^ 1) * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)(kt + 1) * BK),
+                                                 (lptr_t)(dst + (wv + NW * i) * 1024), 16, 0, 0);
+        }
+        const uint8_t* s = smem + cur * STAGE_BYTES;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int kc = ks * 2 + lk;
             bf16x8 xa[TM], wb[TN];
 #pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const int r = wm * WM + j * 32 + lr;
-                xa[j] = *(const bf16x8*)(s + (r * CPR + (kc ^ (CPR == 8 ? (r & 7) : ((r >> 1) & 3)))) * 8);
-            }
+            for (int j = 0; j < TM; ++j)
+                if (m_live[j]) xa[j] = *(const bf16x8*)(s + a_off[j] + ((kc ^ a_sw[j]) << 4));
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const int r = w_row(i) + lr;
-                wb[i] = *(const bf16x8*)(s + BM * BK + (r * CPR + (kc ^ (CPR == 8 ? (r & 7) : ((r >> 1) & 3)))) * 8);
-            }
+            for (int i = 0; i < TN; ++i) wb[i] = *(const bf16x8*)(s + b_off[i] + ((kc ^ b_sw[i]) << 4));
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
+                    if (m_live[j]) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_lds((kt + 1) & 1);
+        __builtin_amdgcn_s_waitcnt(0x0f70);
         __syncthreads();
     }
 
-    // epilogue: lane holds, for activation row (lane & 31) of each 32-row sub-tile, output columns
-    // 8*(v/4) + 4*(lane/32) + (v%4) of each 32-column sub-tile
+    // ---- epilogue: a lane holds, for activation row (lane & 31) of each 32-row sub-tile, output
+    // columns 8*q + 4*(lane/32) + v (q, v = 0..3) of each 32-column sub-tile ----
     constexpr int TNO = SWIGLU ? TN / 2 : TN;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-        const int r = wm * WM + j * 32 + lr;
+        const int r = wm * WTM + j * 32 + lr;
         if (r >= rows) continue;
         uint16_t* crow = C + (size_t)(row0 + r) * Nout + n0;
 #pragma unroll
         for (int i = 0; i < TNO; ++i) {
-            const int cbase = (SWIGLU ? wn * (WN / 2) : wn * WN) + i * 32 + 4 * lk;
+            const int cbase = (SWIGLU ? wn * (WTN / 2) : wn * WTN) + i * 32 + 4 * lk;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float o[4];
@@ -259,21 +280,29 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16_kernel(const uint16_t* 
     }
 }
 
-template <int BM, int BN, int BK, bool SWIGLU>
+static int column_group(int nb_total) {
+    for (int g = 4; g > 1; --g)
+        if (nb_total % g == 0) return g;
+    return 1;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const FfnWorkspace& ws, int K, int Nout,
                         hipStream_t st) {
     ProfileScope prof(SWIGLU ? MOE_KERNEL_FFN_GATE_UP : MOE_KERNEL_FFN_DOWN, st);
-    const int ncols = SWIGLU ? BN / 2 : BN;
-    const size_t lds = (size_t)2 * (BM + BN) * BK * 2;
-    auto kern = grouped_gemm_bf16_kernel<BM, BN, BK, SWIGLU>;
+    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;
+    const size_t lds = (size_t)2 * (BM + BN) * 128;
+    auto kern = ffn_gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, SWIGLU>;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((Nout / ncols) * ws.max_tiles), dim3(256), lds, st, (const uint16_t*)A,
+    const int nb_total = Nout / NCOLS;
+    const long long grid = (long long)nb_total * ws.max_tiles + 8;  // + 8: every XCD gets a whole chunk
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), lds, st, (const uint16_t*)A,
                        (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, ws.tile_expert, ws.tile_row0,
-                       ws.tile_rows, ws.n_tiles, K, Nout);
+                       ws.tile_rows, ws.n_tiles, K, Nout, column_group(nb_total));
 }
 
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
@@ -286,15 +315,15 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
                            ws.tile_expert, ws.tile_row0, ws.tile_rows, ws.n_tiles, ws.max_tiles);
     }
     if (d.dtype == MOE_DTYPE_BF16) {
-        launch_bf16<kFfnTileM, 128, 64, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-        launch_bf16<kFfnTileM, 128, 64, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+        launch_bf16<kFfnTileM, 256, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+        launch_bf16<kFfnTileM, 128, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
     } else {
         const dim3 g1(((d.d_hidden + 15) / 16) * ws.max_tiles), g2(((d.d_model + 15) / 16) * ws.max_tiles);
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), g1, dim3(256), 0, st, (const float*)xp,
-                           (const float*)w_gate, (const float*)w_up, (float*)ws.hidden, ws.tile_expert, ws.tile_row0,
-                           ws.tile_rows, ws.n_tiles, d.d_model, d.d_hidden);
+                               (const float*)w_gate, (const float*)w_up, (float*)ws.hidden, ws.tile_expert,
+                               ws.tile_row0, ws.tile_rows, ws.n_tiles, d.d_model, d.d_hidden);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), g2, dim3(256), 0, st, (const float*)ws.hidden,
