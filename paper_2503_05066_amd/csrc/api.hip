@@ -138,7 +138,8 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
     if (workspace_bytes) {
         const size_t a = drop_workspace(*desc, s, nullptr).bytes;
         const size_t b = ffn_workspace(*desc, s, nullptr).bytes;
-        *workspace_bytes = a > b ? a : b;
+        const size_t c = route_workspace(*desc, nullptr).bytes;
+        *workspace_bytes = a > b ? (a > c ? a : c) : (b > c ? b : c);
     }
     return MOE_OK;
 }
@@ -146,18 +147,31 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
 int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
                    int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
                    void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     const int v = validate(desc);
     if (v != MOE_OK) return v;
     if (desc->n_tokens == 0) return MOE_OK;  // nothing to route; empty arrays may be null
     if (!logits || !scores || !topk_idx || !topk_score) return MOE_ERR_INVALID_ARG;
     if (!use_given_logits && (!x || !w_router)) return MOE_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
+    const float* partial = nullptr;
+    int ksplit = 1;
     if (!use_given_logits) {
-        if (launch_router_logits(*desc, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
+        const RouteWorkspace ws = route_workspace(*desc, workspace);
+        if (ws.use_mfma) {
+            if (!workspace) return MOE_ERR_INVALID_ARG;
+            if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+            if (((uintptr_t)workspace & 255) != 0 || misaligned16(x)) return MOE_ERR_INVALID_ARG;
+            if (launch_router_mfma(*desc, ws, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
+            if (ws.ksplit > 1) {
+                partial = ws.partial;
+                ksplit = ws.ksplit;
+            }
+        } else if (launch_router_logits(*desc, x, w_router, bias, logits, st) != hipSuccess) {
+            return MOE_ERR_HIP;
+        }
     }
-    if (launch_softmax_topk(*desc, logits, scores, topk_idx, topk_score, st) != hipSuccess) return MOE_ERR_HIP;
+    if (launch_softmax_topk(*desc, logits, partial, ksplit, bias, scores, topk_idx, topk_score, st) != hipSuccess)
+        return MOE_ERR_HIP;
     return MOE_OK;
 }
 

@@ -44,6 +44,16 @@ struct DropWorkspace {
 };
 DropWorkspace drop_workspace(const moe_desc_t& d, const Sizes& s, void* base);
 
+// Workspace layout of moe_route_topk (bf16 activations: router GEMM on the matrix cores).
+struct RouteWorkspace {
+    bool use_mfma;    // false: fp32 activations or an unsupported width, plain fp32 kernel, no workspace
+    int ksplit;       // K slices; > 1: partial sums go to `partial` and the softmax kernel adds them
+    uint16_t* w3;     // [3,E,d] bf16 planes of the router weight
+    float* partial;   // [ksplit,N,E]
+    size_t bytes;
+};
+RouteWorkspace route_workspace(const moe_desc_t& d, void* base);
+
 // Workspace layout of moe_grouped_ffn.
 struct FfnWorkspace {
     void* hidden;         // [P_max, h] activations silu(gate)*up in desc->dtype
@@ -76,8 +86,11 @@ struct ProfileScope {
 // Launchers (each returns a hipError_t from hipGetLastError after its launches).
 hipError_t launch_router_logits(const moe_desc_t& d, const void* x, const float* w, const float* bias, float* logits,
                                 hipStream_t st);
-hipError_t launch_softmax_topk(const moe_desc_t& d, const float* logits, float* scores, int32_t* topk_idx,
-                               float* topk_score, hipStream_t st);
+hipError_t launch_router_mfma(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* w,
+                              const float* bias, float* logits, hipStream_t st);
+// partial != nullptr: logits[t,e] = bias[e] + sum over the ksplit slices of partial, written before use
+hipError_t launch_softmax_topk(const moe_desc_t& d, float* logits, const float* partial, int ksplit, const float* bias,
+                               float* scores, int32_t* topk_idx, float* topk_score, hipStream_t st);
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
                                 const int32_t* topk_idx, int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,

@@ -129,17 +129,22 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
             if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
         }
         __syncthreads();
-        if (tid == 0) {
-            int acc = 0, dsel = 0;
-            for (int dg = 255; dg >= 0; --dg) {
-                if (acc + hist[dg] >= rem) {
-                    dsel = dg;
-                    break;
-                }
-                acc += hist[dg];
-            }
-            sh_prefix = prefix | ((uint32_t)dsel << shift);
-            sh_rem = rem - acc;
+        // thread i owns digit 255 - i: an inclusive scan over threads counts the keys with a digit
+        // at least as large; the digit where that count first reaches `rem` holds the cap-th key
+        const int mine_d = 255 - tid;
+        const int h = hist[mine_d];
+        int incl = h;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int o = __shfl_up(incl, off, kWave);
+            if ((tid & 63) >= off) incl += o;
+        }
+        if ((tid & 63) == 63) red[tid >> 6] = incl;
+        __syncthreads();
+        for (int w = 0; w < (tid >> 6); ++w) incl += red[w];
+        if (incl >= rem && incl - h < rem) {  // exactly one thread
+            sh_prefix = prefix | ((uint32_t)mine_d << shift);
+            sh_rem = rem - (incl - h);
         }
         __syncthreads();
         prefix = sh_prefix;

@@ -11,6 +11,9 @@
 // XOR swizzle, multiplied on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
 // The weight rows feed the MFMA's first operand and the activation rows the second, so a lane
 // ends up with 4 consecutive output columns of one row and stores them as one 8-byte piece.
+#include <cstdlib>
+#include <type_traits>
+
 #include "common.h"
 
 namespace capmoe {
@@ -109,13 +112,183 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// Block tile: BM activation rows x BN weight rows, K slab of 64; WAVES_M x WAVES_N wavefronts.
+// s_waitcnt immediate for "at most n vector-memory operations outstanding, LDS/scalar counter
+// at zero" (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at 7, lgkmcnt 11:8).
+__host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | ((n >> 4) << 14); }
+
+// K loop of one wave.  A ring of STAGES LDS stages: while stage kt is multiplied, the fills of
+// the next STAGES-1 slabs are in flight (asynchronous, straight from global memory into LDS); one
+// barrier per slab separates the readers of a stage from its next fill.
+// LIVE = number of 32-row activation sub-tiles that are multiplied (the rest lie past the expert's
+// last row).
+template <int BM, int BN, int BK, int STAGES, int NW, int TM, int TN, int LOADS>
+struct MainLoop {
+    static constexpr int ROW_BYTES = BK * 2;
+    static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
+    static constexpr int CPR = BK / 8;  // 16-byte pieces per row
+    uint8_t* smem;
+    const uint16_t* const* src;
+    const int* a_off;
+    const int* a_sw;
+    const int* b_off;
+    const int* b_sw;
+    int KT, wv, lk;
+
+    __device__ __forceinline__ void fill(int kt) const {
+        uint8_t* dst = smem + (kt % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BK), (lptr_t)(dst + (wv + NW * i) * 1024),
+                                             16, 0, 0);
+    }
+
+    template <int LIVE>
+    __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
+#pragma unroll
+        for (int p = 0; p < STAGES - 1; ++p)
+            if (p < KT) fill(p);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // this wave's pieces of the first slabs have landed
+        __builtin_amdgcn_s_barrier();
+        for (int kt = 0; kt < KT; ++kt) {
+            const bool more = kt + STAGES - 1 < KT;
+            if (more) fill(kt + STAGES - 1);
+            const uint8_t* s = smem + (kt % STAGES) * STAGE_BYTES;
+            if (LIVE > 0) {
+#pragma unroll
+                for (int ks = 0; ks < BK / 16; ++ks) {
+                    const int kc = ks * 2 + lk;
+                    bf16x8 xa[LIVE > 0 ? LIVE : 1], wb[TN];
+#pragma unroll
+                    for (int j = 0; j < LIVE; ++j) xa[j] = *(const bf16x8*)(s + a_off[j] + ((kc ^ a_sw[j]) << 4));
+#pragma unroll
+                    for (int i = 0; i < TN; ++i) wb[i] = *(const bf16x8*)(s + b_off[i] + ((kc ^ b_sw[i]) << 4));
+#pragma unroll
+                    for (int i = 0; i < TN; ++i)
+#pragma unroll
+                        for (int j = 0; j < LIVE; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
+                }
+            }
+            // slab kt+1 must have landed; younger fills may stay in flight (loads complete in order)
+            if (more)
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm((STAGES - 2) * LOADS));
+            else
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            __builtin_amdgcn_s_barrier();
+        }
+    }
+};
+
+// Software-pipelined K loop (two LDS stages of 64-wide slabs).  MFMAs lag the operand reads by one
+// 16-wide k-step and the two are interleaved one by one, so that LDS reads and the fills of the
+// next slab issue in the shadow of the matrix instructions (an MFMA occupies the matrix pipe for 32
+// cycles but the wave's issue port only for a few):
+//     k-step 0..2 of slab kt:  MFMAs of the step  |  operand reads of the next step
+//     barrier (slab kt+1 landed, slab kt no longer read)
+//     k-step 3 of slab kt:     MFMAs              |  fills of slab kt+2, operand reads of slab kt+1 step 0
+// __builtin_amdgcn_sched_barrier(0) pins the order written here.
+template <int BM, int BN, int NW, int TM, int TN, int LOADS>
+struct PipelinedLoop {
+    static constexpr int BK = 64;
+    static constexpr int STAGE_BYTES = (BM + BN) * 128;
+    uint8_t* smem;
+    const uint16_t* const* src;
+    const int* a_off;
+    const int* a_sw;
+    const int* b_off;
+    const int* b_sw;
+    int KT, wv, lk;
+
+    template <int LIVE>
+    __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
+        if (LIVE == 0) {  // nothing to multiply in this wave: only keep the barriers of the block
+            for (int kt = 0; kt <= KT; ++kt) {
+                // other waves fill their own pieces; this wave still fills its share
+                if (kt < KT) fill(kt, src);
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                __builtin_amdgcn_s_barrier();
+            }
+            return;
+        }
+        constexpr int NL = LIVE > 0 ? LIVE : 1;
+        constexpr int NMFMA = TN * NL, NREAD = NL + TN;
+        bf16x8 xa[2][NL], wb[2][TN];
+        // lane's operand addresses for k-step 0 of stage 0; step ks flips piece bits 1-2 (byte bits 5-6)
+        int ra[NL], rb[TN];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) ra[j] = a_off[j] + ((lk ^ a_sw[j]) << 4);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) rb[i] = b_off[i] + ((lk ^ b_sw[i]) << 4);
+
+        fill(0, src);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_barrier();
+        if (1 < KT) fill(1, src);
+        // operand reads of slab 0, k-step 0
+#pragma unroll
+        for (int j = 0; j < NL; ++j) xa[0][j] = *(const bf16x8*)(smem + ra[j]);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) wb[0][i] = *(const bf16x8*)(smem + rb[i]);
+
+        for (int kt = 0; kt < KT; ++kt) {
+            const uint8_t* s = smem + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < 3; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1, flip = (ks + 1) << 5;
+#pragma unroll
+                for (int q = 0; q < (NMFMA > NREAD ? NMFMA : NREAD); ++q) {
+                    if (q < NMFMA) {
+                        const int j = q / TN, i = q % TN;
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
+                    }
+                    if (q < NL)
+                        xa[nxt][q] = *(const bf16x8*)(s + (ra[q] ^ flip));
+                    else if (q < NREAD)
+                        wb[nxt][q - NL] = *(const bf16x8*)(s + (rb[q - NL] ^ flip));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // slab kt+1 has landed for this wave and this wave no longer reads slab kt
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0) & ~(15 << 8));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 2 < KT) fill(kt + 2, src);
+            const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE_BYTES;
+            const bool more = kt + 1 < KT;
+#pragma unroll
+            for (int q = 0; q < (NMFMA > NREAD ? NMFMA : NREAD); ++q) {
+                if (q < NMFMA) {
+                    const int j = q / TN, i = q % TN;
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
+                }
+                if (more) {
+                    if (q < NL)
+                        xa[0][q] = *(const bf16x8*)(sn + ra[q]);
+                    else if (q < NREAD)
+                        wb[0][q - NL] = *(const bf16x8*)(sn + rb[q - NL]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void fill(int kt, const uint16_t* const* p) const {
+        uint8_t* dst = smem + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(p[i] + (size_t)kt * BK), (lptr_t)(dst + (wv + NW * i) * 1024), 16,
+                                             0, 0);
+    }
+};
+
+// Block tile: BM activation rows x BN weight rows, K slab BK (32 or 64); WAVES_M x WAVES_N waves.
 //
-// LDS holds two stages; a stage is (BM + BN) rows of 128 bytes.  Rows are filled by direct
-// global->LDS loads: one wave-wide load writes 8 rows (64 lanes x 16 bytes, contiguous in LDS), and
-// each lane chooses WHICH 16-byte piece of its row it fetches, so that piece kc of row r lands at
-// position kc ^ ((r >> 1) & 7): with 64 LDS banks a 16-lane group of a 16-byte read then touches
-// 16 different bank groups, for the fill as well as for the MFMA operand reads.
+// An LDS stage is (BM + BN) rows of BK bf16.  Rows are filled by direct global->LDS loads: one
+// wave-wide load writes 1 KB of consecutive LDS (64 lanes x 16 bytes = 8 or 16 rows), and each lane
+// chooses WHICH 16-byte piece of its row it fetches, so that piece kc of row r lands at position
+// kc ^ swz(r), swz(r) = (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows: with the 64
+// LDS banks of this chip, the 16 lanes that a 16-byte read serves per cycle then fall into 16
+// different bank groups, for the fill as well as for the MFMA operand reads.
 //
 // SWIGLU: weight rows [0,BN/2) of the tile come from W_gate, [BN/2,BN) from W_up, for the same
 // BN/2 hidden columns; a wave holds matching gate and up columns and applies silu(g)*u itself.
@@ -123,22 +296,25 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // Blocks are numbered so that each XCD (block id mod 8) walks a contiguous range of tiles, ordered
 // [column group][row tile][column in group]: blocks that run together share row and weight tiles in
 // their XCD's L2.
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
+template <int BM, int BN, int BK, int STAGES, int WAVES_M, int WAVES_N, bool SWIGLU>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
     uint16_t* __restrict__ C, const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ tile_row0,
     const int32_t* __restrict__ tile_rows, const int32_t* __restrict__ n_tiles, int K, int Nout, int col_group) {
-    constexpr int BK = 64;
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int A_GROUPS = BM / 8, GROUPS = (BM + BN) / 8;  // 8-row groups of a stage
-    constexpr int LOADS = GROUPS / NW;                         // wave-wide loads per wave per stage
-    constexpr int STAGE_BYTES = (BM + BN) * 128;
-    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;  // output columns per block
+    constexpr int ROW_BYTES = BK * 2, CPR = BK / 8;
+    constexpr int RPL = 1024 / ROW_BYTES;                         // rows per wave-wide load
+    constexpr int A_GROUPS = BM / RPL, GROUPS = (BM + BN) / RPL;  // row groups of a stage
+    constexpr int LOADS = GROUPS / NW;                            // wave-wide loads per wave per stage
+    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;                   // output columns per block
+    static_assert(BK == 32 || BK == 64, "K slab");
     static_assert(GROUPS % NW == 0, "loads must divide evenly over the waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
     static_assert(!SWIGLU || TN % 2 == 0, "a wave needs matching gate and up columns");
+    static_assert((STAGES - 2) * LOADS < 64, "vmcnt range");
+    static_assert(STAGES != 0 || BK == 64, "the pipelined loop is written for 64-wide slabs");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
@@ -163,9 +339,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
     const uint16_t* src[LOADS];
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-        const int g = wv + NW * i;           // row group inside the stage (wave-uniform)
-        const int r = g * 8 + (lane >> 3);   // row inside the stage: A rows first, then weight rows
-        const int kc = (lane & 7) ^ ((r >> 1) & 7);
+        const int g = wv + NW * i;               // row group inside the stage (wave-uniform)
+        const int r = g * RPL + lane / CPR;      // row inside the stage: A rows first, then weight rows
+        const int kc = (lane % CPR) ^ (CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3);
         if (g < A_GROUPS) {
             const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
             src[i] = A + (size_t)(row0 + rr) * K + kc * 8;
@@ -178,16 +354,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
         }
     }
 
-    // ---- LDS offsets of this lane's operand pieces (k-step 0; later steps flip piece bits) ----
+    // ---- LDS offsets of this lane's operand pieces ----
     const int lr = lane & 31, lk = lane >> 5;
     int a_off[TM], a_sw[TM], b_off[TN], b_sw[TN];
-    bool m_live[TM];
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         const int r = wm * WTM + j * 32 + lr;
-        a_off[j] = r * 128;
-        a_sw[j] = (r >> 1) & 7;
-        m_live[j] = wm * WTM + j * 32 < rows;  // wave-uniform: skip sub-tiles past the expert's end
+        a_off[j] = r * ROW_BYTES;
+        a_sw[j] = CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3;
     }
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
@@ -198,8 +372,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
         } else {
             r = wn * WTN + i * 32 + lr;
         }
-        b_off[i] = BM * 128 + r * 128;
-        b_sw[i] = (r >> 1) & 7;
+        b_off[i] = (BM + r) * ROW_BYTES;
+        b_sw[i] = CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3;
     }
 
     f32x16 acc[TN][TM];
@@ -210,42 +384,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int KT = K / BK;
-    // prologue: stage 0
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)src[i], (lptr_t)(smem + (wv + NW * i) * 1024), 16, 0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's pieces have landed
-    __syncthreads();
+    // 32-row sub-tiles of this wave that hold rows of the expert (wave-uniform); the main loop is
+    // specialised on it so that the common full tile carries no conditionals
+    int live = (rows - wm * WTM + 31) / 32;
+    live = __builtin_amdgcn_readfirstlane(live < 0 ? 0 : (live > TM ? TM : live));
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) {
-            uint8_t* dst = smem + (cur ^ 1) * STAGE_BYTES;
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)(kt + 1) * BK),
-                                                 (lptr_t)(dst + (wv + NW * i) * 1024), 16, 0, 0);
-        }
-        const uint8_t* s = smem + cur * STAGE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int kc = ks * 2 + lk;
-            bf16x8 xa[TM], wb[TN];
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                if (m_live[j]) xa[j] = *(const bf16x8*)(s + a_off[j] + ((kc ^ a_sw[j]) << 4));
-#pragma unroll
-            for (int i = 0; i < TN; ++i) wb[i] = *(const bf16x8*)(s + b_off[i] + ((kc ^ b_sw[i]) << 4));
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    if (m_live[j]) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
-    }
+    using Loop = typename std::conditional<STAGES == 0, PipelinedLoop<BM, BN, NW, TM, TN, LOADS>,
+                                           MainLoop<BM, BN, BK, (STAGES == 0 ? 2 : STAGES), NW, TM, TN, LOADS>>::type;
+    Loop loop{smem, src, a_off, a_sw, b_off, b_sw, K / BK, wv, lk};
+    if (live == TM)
+        loop.template run<TM>(acc);
+    else if (TM > 2 && live == 3)
+        loop.template run<(TM > 2 ? 3 : TM)>(acc);
+    else if (TM > 1 && live == 2)
+        loop.template run<(TM > 1 ? 2 : TM)>(acc);
+    else if (live == 1)
+        loop.template run<1>(acc);
+    else
+        loop.template run<0>(acc);
 
     // ---- epilogue: a lane holds, for activation row (lane & 31) of each 32-row sub-tile, output
     // columns 8*q + 4*(lane/32) + v (q, v = 0..3) of each 32-column sub-tile ----
@@ -286,13 +442,13 @@ static int column_group(int nb_total) {
     return 1;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
+template <int BM, int BN, int BK, int STAGES, int WAVES_M, int WAVES_N, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const FfnWorkspace& ws, int K, int Nout,
                         hipStream_t st) {
     ProfileScope prof(SWIGLU ? MOE_KERNEL_FFN_GATE_UP : MOE_KERNEL_FFN_DOWN, st);
     constexpr int NCOLS = SWIGLU ? BN / 2 : BN;
-    const size_t lds = (size_t)2 * (BM + BN) * 128;
-    auto kern = ffn_gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, SWIGLU>;
+    const size_t lds = (size_t)(STAGES == 0 ? 2 : STAGES) * (BM + BN) * BK * 2;
+    auto kern = ffn_gemm_bf16_kernel<BM, BN, BK, STAGES, WAVES_M, WAVES_N, SWIGLU>;
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -305,6 +461,15 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
                        ws.tile_rows, ws.n_tiles, K, Nout, column_group(nb_total));
 }
 
+static int tuning_variant() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("CAPMOE_FFN_VARIANT");  // kernel-tuning switch, not a documented interface
+        v = e ? atoi(e) : 0;
+    }
+    return v;
+}
+
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
                               const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
                               void* yp, hipStream_t st) {
@@ -315,8 +480,30 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
                            ws.tile_expert, ws.tile_row0, ws.tile_rows, ws.n_tiles, ws.max_tiles);
     }
     if (d.dtype == MOE_DTYPE_BF16) {
-        launch_bf16<kFfnTileM, 256, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-        launch_bf16<kFfnTileM, 128, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+        switch (tuning_variant()) {
+            case 1:
+                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+                break;
+            case 2:
+                launch_bf16<kFfnTileM, 256, 64, 0, 2, 2, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+                launch_bf16<kFfnTileM, 256, 64, 0, 2, 2, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+                break;
+            case 3:
+                launch_bf16<kFfnTileM, 256, 64, 2, 4, 2, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+                launch_bf16<kFfnTileM, 128, 64, 3, 4, 2, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+                break;
+            case 4:
+                launch_bf16<kFfnTileM, 256, 64, 2, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+                launch_bf16<kFfnTileM, 256, 64, 2, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+                break;
+            default:
+                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
+                if (d.d_model % 256 == 0)
+                    launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+                else  // d is a multiple of 128 only: 128 output columns per block
+                    launch_bf16<kFfnTileM, 128, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+        }
     } else {
         const dim3 g1(((d.d_hidden + 15) / 16) * ws.max_tiles), g2(((d.d_model + 15) / 16) * ws.max_tiles);
         {

@@ -151,8 +151,9 @@ __device__ inline float wave_max(float v) {
 }
 
 template <int EPL>
-__global__ __launch_bounds__(256) void softmax_topk_kernel(const float* __restrict__ logits,
-                                                           float* __restrict__ scores,
+__global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ logits,
+                                                           const float* __restrict__ partial, int ksplit,
+                                                           const float* __restrict__ bias, float* __restrict__ scores,
                                                            int32_t* __restrict__ topk_idx,
                                                            float* __restrict__ topk_score, int N, int E, int k) {
     __shared__ float numer[4][EPL * kWave];
@@ -161,13 +162,22 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(const float* __restri
     for (int base = blockIdx.x * 4; base < N; base += gridDim.x * 4) {
         const int t = base + wv;
         const bool live = t < N;
-        const float* l = logits + (size_t)(live ? t : 0) * E;
+        float* l = logits + (size_t)(live ? t : 0) * E;
         float v[EPL];
         float m = -INFINITY;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
             const int e = lane + kWave * i;
-            v[i] = e < E ? l[e] : -INFINITY;
+            if (e < E && partial) {
+                // the router GEMM left one partial sum per K slice: add them in slice order
+                float sum = bias ? bias[e] : 0.0f;
+                for (int sl = 0; sl < ksplit; ++sl)
+                    sum = __fadd_rn(sum, partial[((size_t)sl * N + (live ? t : 0)) * E + e]);
+                v[i] = sum;
+                if (live) l[e] = sum;
+            } else {
+                v[i] = e < E ? l[e] : -INFINITY;
+            }
             m = fmaxf(m, v[i]);
         }
         m = wave_max(m);
@@ -224,25 +234,25 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(const float* __restri
     }
 }
 
-hipError_t launch_softmax_topk(const moe_desc_t& d, const float* logits, float* scores, int32_t* topk_idx,
-                               float* topk_score, hipStream_t st) {
+hipError_t launch_softmax_topk(const moe_desc_t& d, float* logits, const float* partial, int ksplit, const float* bias,
+                               float* scores, int32_t* topk_idx, float* topk_score, hipStream_t st) {
     ProfileScope prof(MOE_KERNEL_SOFTMAX_TOPK, st);
     const int N = d.n_tokens, E = d.n_experts, k = d.top_k;
     int grid = (N + 3) / 4;
     if (grid > 2048) grid = 2048;
     const int epl = (E + kWave - 1) / kWave;
     if (epl <= 1)
-        hipLaunchKernelGGL((softmax_topk_kernel<1>), dim3(grid), dim3(256), 0, st, logits, scores, topk_idx, topk_score,
-                           N, E, k);
+        hipLaunchKernelGGL((softmax_topk_kernel<1>), dim3(grid), dim3(256), 0, st, logits, partial, ksplit, bias, scores,
+                           topk_idx, topk_score, N, E, k);
     else if (epl <= 2)
-        hipLaunchKernelGGL((softmax_topk_kernel<2>), dim3(grid), dim3(256), 0, st, logits, scores, topk_idx, topk_score,
-                           N, E, k);
+        hipLaunchKernelGGL((softmax_topk_kernel<2>), dim3(grid), dim3(256), 0, st, logits, partial, ksplit, bias, scores,
+                           topk_idx, topk_score, N, E, k);
     else if (epl <= 4)
-        hipLaunchKernelGGL((softmax_topk_kernel<4>), dim3(grid), dim3(256), 0, st, logits, scores, topk_idx, topk_score,
-                           N, E, k);
+        hipLaunchKernelGGL((softmax_topk_kernel<4>), dim3(grid), dim3(256), 0, st, logits, partial, ksplit, bias, scores,
+                           topk_idx, topk_score, N, E, k);
     else
-        hipLaunchKernelGGL((softmax_topk_kernel<8>), dim3(grid), dim3(256), 0, st, logits, scores, topk_idx, topk_score,
-                           N, E, k);
+        hipLaunchKernelGGL((softmax_topk_kernel<8>), dim3(grid), dim3(256), 0, st, logits, partial, ksplit, bias, scores,
+                           topk_idx, topk_score, N, E, k);
     return hipGetLastError();
 }
 

@@ -1,0 +1,219 @@
+// Router logits for bf16 activations on the matrix cores, at fp32 accuracy.
+//
+// The router weight is fp32.  It is split exactly into three bf16 planes, w = hi + mid + lo
+// (8 + 8 + 8 significand bits); x is bf16 already, so every product x*plane is exact in fp32 and
+// the three MFMAs of a k-step accumulate into one fp32 accumulator: the result is an fp32-accurate
+// dot product computed at bf16 matrix rate (3 MFMAs instead of one fp32-rate GEMM).
+//
+// Work split: a block owns 128 tokens (4 waves x 32) and one slice of K; the slices' partial sums
+// are added, in slice order, by the softmax kernel (deterministic: no floating-point atomics).
+// The weight planes of a 32-wide k-slab go through LDS (shared by the 4 waves, filled by direct
+// global->LDS loads, two stages); each wave reads its own 32 token rows straight from global memory.
+#include "common.h"
+
+namespace capmoe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+__device__ inline uint16_t bf16_rne_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// w [E,d] fp32 -> w3 [3,E,d] bf16 with w = w3[0] + w3[1] + w3[2]
+__global__ __launch_bounds__(256) void router_split_kernel(const float* __restrict__ w, uint16_t* __restrict__ w3,
+                                                           int count) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const float v = w[i];
+    const uint16_t hi = bf16_rne_bits(v);
+    const float r1 = v - __uint_as_float((uint32_t)hi << 16);
+    const uint16_t mid = bf16_rne_bits(r1);
+    const float r2 = r1 - __uint_as_float((uint32_t)mid << 16);
+    const uint16_t lo = bf16_rne_bits(r2);
+    w3[i] = hi;
+    w3[(size_t)count + i] = mid;
+    w3[2 * (size_t)count + i] = lo;
+}
+
+constexpr int kRmTokens = 128;  // tokens per block
+constexpr int kRmSlab = 32;     // k per LDS stage
+
+// TN = 32-expert tiles (E padded to 32*TN).  out: [ksplit, N, E] partial sums (or the logits
+// themselves, with the bias added, when there is a single slice).
+template <int TN>
+__global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __restrict__ x,
+                                                          const uint16_t* __restrict__ w3,
+                                                          const float* __restrict__ bias, float* __restrict__ out,
+                                                          int N, int d, int E, int k_per_slice, int add_bias) {
+    constexpr int EP = 32 * TN;          // padded expert count
+    constexpr int ROWS = 3 * EP;         // plane rows of a stage, 64 bytes each
+    constexpr int GROUPS = ROWS / 16;    // 1 KB row groups (one wave-wide load each)
+    constexpr int STAGE_BYTES = ROWS * 64;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int lr = lane & 31, lk = lane >> 5;
+    const int t0 = blockIdx.x * kRmTokens + wv * 32;
+    const int slice = blockIdx.y;
+    const int k_begin = slice * k_per_slice;
+    const int n_slabs = k_per_slice / kRmSlab;
+
+    // this lane's token row (clamped: rows past N repeat the last token and are not stored)
+    const int tr = t0 + lr < N ? t0 + lr : N - 1;
+    const uint16_t* xrow = x + (size_t)tr * d + k_begin + lk * 8;
+
+    // sources of the weight pieces this lane stages: group g covers rows 16g..16g+15
+    constexpr int LOADS = (GROUPS + 3) / 4;
+    const uint16_t* src[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int g = wv + 4 * i;
+        const int R = g * 16 + (lane >> 2);
+        const int kc = (lane & 3) ^ ((R >> 2) & 3);
+        const int plane = R / EP;
+        int e = R - plane * EP;
+        e = e < E ? e : E - 1;  // padding rows repeat the last expert; their outputs are not stored
+        src[i] = w3 + ((size_t)(plane < 3 ? plane : 2) * E + e) * d + k_begin + kc * 8;
+    }
+    auto fill = [&](int slab) {
+        uint8_t* dst = smem + (slab & 1) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int g = wv + 4 * i;
+            if (g < GROUPS)
+                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)slab * kRmSlab), (lptr_t)(dst + g * 1024), 16,
+                                                 0, 0);
+        }
+    };
+
+    f32x16 acc[TN];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    // LDS offsets of this lane's weight pieces for k-step 0 (piece lk) and 1 (piece 2 + lk)
+    int w_off[3][TN];
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int R = p * EP + i * 32 + lr;
+            w_off[p][i] = R * 64 + ((lk ^ ((R >> 2) & 3)) << 4);
+        }
+
+    fill(0);
+    bf16x8 xa[2], xn[2];
+    xa[0] = *(const bf16x8*)(xrow);
+    xa[1] = *(const bf16x8*)(xrow + 16);
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+    for (int s = 0; s < n_slabs; ++s) {
+        if (s + 1 < n_slabs) {
+            fill(s + 1);
+            xn[0] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab);
+            xn[1] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab + 16);
+        }
+        const uint8_t* st = smem + (s & 1) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+                // smallest plane first
+#pragma unroll
+                for (int p = 2; p >= 0; --p) {
+                    const bf16x8 wf = *(const bf16x8*)(st + (w_off[p][i] ^ (ks << 5)));
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa[ks], acc[i], 0, 0, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        __syncthreads();
+        xa[0] = xn[0];
+        xa[1] = xn[1];
+    }
+
+    // lane holds token (lane & 31) and experts 8q + 4*(lane/32) + v of each 32-expert tile
+    const int t = t0 + lr;
+    if (t < N) {
+        float* orow = out + ((size_t)slice * N + t) * E;
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int e = i * 32 + q * 8 + lk * 4 + v;
+                    if (e < E) orow[e] = acc[i][q * 4 + v] + (add_bias && bias ? bias[e] : 0.f);
+                }
+    }
+}
+
+RouteWorkspace route_workspace(const moe_desc_t& d, void* base) {
+    RouteWorkspace w;
+    w.use_mfma = d.dtype == MOE_DTYPE_BF16 && d.d_model % 32 == 0 && d.n_tokens > 0;
+    w.ksplit = 1;
+    w.w3 = nullptr;
+    w.partial = nullptr;
+    w.bytes = 0;
+    if (!w.use_mfma) return w;
+    const int blocks_m = (d.n_tokens + kRmTokens - 1) / kRmTokens;
+    int want = (256 + blocks_m - 1) / blocks_m;  // aim at one block per compute unit or more
+    if (want > 32) want = 32;
+    int ks = 1;
+    for (int c = 1; c <= want; ++c)
+        if (d.d_model % (c * kRmSlab) == 0) ks = c;
+    w.ksplit = ks;
+    char* p = (char*)base;
+    size_t off = 0;
+    w.w3 = (uint16_t*)(p + off);
+    off += align256((size_t)3 * d.n_experts * d.d_model * 2);
+    if (ks > 1) {
+        w.partial = (float*)(p + off);
+        off += align256((size_t)ks * d.n_tokens * d.n_experts * 4);
+    }
+    w.bytes = off;
+    return w;
+}
+
+template <int TN>
+static void launch_rm(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* bias, float* out,
+                      hipStream_t st) {
+    const size_t lds = (size_t)2 * 3 * 32 * TN * 64;
+    auto kern = router_mfma_kernel<TN>;
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        configured = true;
+    }
+    const dim3 grid((d.n_tokens + kRmTokens - 1) / kRmTokens, ws.ksplit);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const uint16_t*)x, ws.w3, bias, out, d.n_tokens, d.d_model,
+                       d.n_experts, d.d_model / ws.ksplit, ws.ksplit == 1 ? 1 : 0);
+}
+
+// Writes either the logits (single K slice) or ws.partial (several slices, summed later).
+hipError_t launch_router_mfma(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* w,
+                              const float* bias, float* logits, hipStream_t st) {
+    ProfileScope prof(MOE_KERNEL_ROUTER_LOGITS, st);
+    const int count = d.n_experts * d.d_model;
+    hipLaunchKernelGGL(router_split_kernel, dim3((count + 255) / 256), dim3(256), 0, st, w, ws.w3, count);
+    float* out = ws.ksplit == 1 ? logits : ws.partial;
+    const int tn = (d.n_experts + 31) / 32;
+    switch (tn) {
+        case 1: launch_rm<1>(d, ws, x, bias, out, st); break;
+        case 2: launch_rm<2>(d, ws, x, bias, out, st); break;
+        case 3: launch_rm<3>(d, ws, x, bias, out, st); break;
+        case 4: launch_rm<4>(d, ws, x, bias, out, st); break;
+        case 5: launch_rm<5>(d, ws, x, bias, out, st); break;
+        case 6: launch_rm<6>(d, ws, x, bias, out, st); break;
+        case 7: launch_rm<7>(d, ws, x, bias, out, st); break;
+        default: launch_rm<8>(d, ws, x, bias, out, st); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace capmoe
