@@ -76,18 +76,25 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
     FfnWorkspace w;
     char* p = (char*)base;
     size_t off = 0;
-    w.tile_m = d.dtype == MOE_DTYPE_BF16 ? kFfnTileM : kFfnTileMF32;
-    w.max_tiles = (int)(s.max_rows / w.tile_m) + d.n_experts;
+    const bool bf16 = d.dtype == MOE_DTYPE_BF16;
+    w.big.tile_m = bf16 ? kFfnTileM : kFfnTileMF32;
+    w.big.max_tiles = (int)(s.max_rows / w.big.tile_m) + d.n_experts;
+    w.small.tile_m = kFfnTileSmall;
+    w.small_max = bf16 ? kFfnSmallMax : 0;
+    w.small.max_tiles = bf16 ? d.n_experts * (kFfnSmallMax / kFfnTileSmall) : 0;
     w.hidden = p + off;
     off += align256((size_t)(s.max_rows > 0 ? s.max_rows : 1) * d.d_hidden * s.elem);
-    w.tile_expert = (int32_t*)(p + off);
-    off += align256((size_t)w.max_tiles * 4);
-    w.tile_row0 = (int32_t*)(p + off);
-    off += align256((size_t)w.max_tiles * 4);
-    w.tile_rows = (int32_t*)(p + off);
-    off += align256((size_t)w.max_tiles * 4);
-    w.n_tiles = (int32_t*)(p + off);
-    off += 256;
+    for (TileList* t : {&w.big, &w.small}) {
+        const size_t n = align256((size_t)(t->max_tiles > 0 ? t->max_tiles : 1) * 4);
+        t->expert = (int32_t*)(p + off);
+        off += n;
+        t->row0 = (int32_t*)(p + off);
+        off += n;
+        t->rows = (int32_t*)(p + off);
+        off += n;
+        t->count = (int32_t*)(p + off);
+        off += 256;
+    }
     w.bytes = off;
     return w;
 }

@@ -14,8 +14,10 @@ constexpr int kMaxTopK = 64;
 constexpr int kWave = 64;
 
 // Tile heights of the expert GEMMs; the tile schedule in the workspace is built for these.
-constexpr int kFfnTileM = 256;     // bf16 MFMA kernels
-constexpr int kFfnTileMF32 = 16;   // fp32 fallback kernels (tiny layers)
+constexpr int kFfnTileM = 256;      // bf16 MFMA kernels, compute-bound tiles
+constexpr int kFfnTileSmall = 64;   // bf16 MFMA kernels, tail of an expert with at most 128 rows left
+constexpr int kFfnSmallMax = 128;   // remainders up to this many rows are cut into small tiles
+constexpr int kFfnTileMF32 = 16;    // fp32 fallback kernels (tiny layers)
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 
@@ -55,14 +57,19 @@ struct RouteWorkspace {
 RouteWorkspace route_workspace(const moe_desc_t& d, void* base);
 
 // Workspace layout of moe_grouped_ffn.
-struct FfnWorkspace {
-    void* hidden;         // [P_max, h] activations silu(gate)*up in desc->dtype
-    int32_t* tile_expert; // [max_tiles]
-    int32_t* tile_row0;   // [max_tiles] first row of the tile
-    int32_t* tile_rows;   // [max_tiles] valid rows in the tile
-    int32_t* n_tiles;     // [1]
+struct TileList {
+    int32_t* expert;  // [max_tiles]
+    int32_t* row0;    // [max_tiles] first row of the tile
+    int32_t* rows;    // [max_tiles] valid rows in the tile
+    int32_t* count;   // [1]
     int max_tiles;
     int tile_m;
+};
+struct FfnWorkspace {
+    void* hidden;    // [P_max, h] activations silu(gate)*up in desc->dtype
+    TileList big;    // full-height row tiles, and remainders above small_max rows
+    TileList small;  // short row tiles covering remainders of at most small_max rows (bf16 only)
+    int small_max;
     size_t bytes;
 };
 FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base);

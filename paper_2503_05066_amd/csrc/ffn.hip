@@ -24,37 +24,61 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // ---------------------------------------------------------------------------------------------
 // tile schedule
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int tile_m,
-                                                          int32_t* __restrict__ tile_expert,
-                                                          int32_t* __restrict__ tile_row0,
-                                                          int32_t* __restrict__ tile_rows,
-                                                          int32_t* __restrict__ n_tiles, int max_tiles) {
+// Expert e with c rows gets floor(c / big) full tiles; a remainder above small_max rows becomes one
+// more (partly filled) big tile, a smaller one is cut into ceil(remainder / small) short tiles, which
+// a kernel with a deeper load pipeline serves (few rows per weight byte: memory-bound work).
+__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E,
+                                                          int big, int small, int small_max,
+                                                          int32_t* __restrict__ b_expert, int32_t* __restrict__ b_row0,
+                                                          int32_t* __restrict__ b_rows, int32_t* __restrict__ b_count,
+                                                          int b_max, int32_t* __restrict__ s_expert,
+                                                          int32_t* __restrict__ s_row0, int32_t* __restrict__ s_rows,
+                                                          int32_t* __restrict__ s_count, int s_max) {
     const int lane = threadIdx.x;
-    int base = 0;
+    int base_b = 0, base_s = 0;
     for (int e0 = 0; e0 < E; e0 += kWave) {
         const int e = e0 + lane;
         const int lo = e < E ? expert_offset[e] : 0;
         const int hi = e < E ? expert_offset[e + 1] : 0;
-        const int nt = (hi - lo + tile_m - 1) / tile_m;
-        int incl = nt;  // inclusive scan over the wave
+        const int c = hi - lo;
+        const int full = c / big, rem = c - full * big;
+        const bool rem_small = rem > 0 && rem <= small_max;
+        const int nb = full + (rem > 0 && !rem_small ? 1 : 0);
+        const int ns = rem_small ? (rem + small - 1) / small : 0;
+        int incl_b = nb, incl_s = ns;  // inclusive scans over the wave
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
-            const int o = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += o;
-        }
-        const int first = base + incl - nt;
-        for (int i = 0; i < nt; ++i) {
-            const int idx = first + i;
-            if (idx < max_tiles) {
-                tile_expert[idx] = e;
-                tile_row0[idx] = lo + i * tile_m;
-                const int left = hi - (lo + i * tile_m);
-                tile_rows[idx] = left < tile_m ? left : tile_m;
+            const int ob = __shfl_up(incl_b, off, kWave), os = __shfl_up(incl_s, off, kWave);
+            if (lane >= off) {
+                incl_b += ob;
+                incl_s += os;
             }
         }
-        base += __shfl(incl, kWave - 1, kWave);
+        for (int i = 0; i < nb; ++i) {
+            const int idx = base_b + incl_b - nb + i;
+            if (idx < b_max) {
+                b_expert[idx] = e;
+                b_row0[idx] = lo + i * big;
+                const int left = c - i * big;
+                b_rows[idx] = left < big ? left : big;
+            }
+        }
+        for (int i = 0; i < ns; ++i) {
+            const int idx = base_s + incl_s - ns + i;
+            if (idx < s_max) {
+                s_expert[idx] = e;
+                s_row0[idx] = lo + full * big + i * small;
+                const int left = rem - i * small;
+                s_rows[idx] = left < small ? left : small;
+            }
+        }
+        base_b += __shfl(incl_b, kWave - 1, kWave);
+        base_s += __shfl(incl_s, kWave - 1, kWave);
     }
-    if (lane == 0) *n_tiles = base < max_tiles ? base : max_tiles;
+    if (lane == 0) {
+        *b_count = base_b < b_max ? base_b : b_max;
+        *s_count = base_s < s_max ? base_s : s_max;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -296,11 +320,17 @@ struct PipelinedLoop {
 // Blocks are numbered so that each XCD (block id mod 8) walks a contiguous range of tiles, ordered
 // [column group][row tile][column in group]: blocks that run together share row and weight tiles in
 // their XCD's L2.
+// One output tile: rows [row0, row0+rows) of expert e times NCOLS output columns from n0.
 template <int BM, int BN, int BK, int STAGES, int WAVES_M, int WAVES_N, bool SWIGLU>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
-    uint16_t* __restrict__ C, const int32_t* __restrict__ tile_expert, const int32_t* __restrict__ tile_row0,
-    const int32_t* __restrict__ tile_rows, const int32_t* __restrict__ n_tiles, int K, int Nout, int col_group) {
+struct TileConfig {
+    static constexpr int kBM = BM, kBN = BN;
+    static constexpr int kNCols = SWIGLU ? BN / 2 : BN;
+    static constexpr int kThreads = 64 * WAVES_M * WAVES_N;
+    static constexpr int kLdsBytes = (STAGES == 0 ? 2 : STAGES) * (BM + BN) * BK * 2;
+
+    static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+                                               const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int e,
+                                               int row0, int rows, int n0, int K, int Nout, uint8_t* smem) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -308,29 +338,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
     constexpr int RPL = 1024 / ROW_BYTES;                         // rows per wave-wide load
     constexpr int A_GROUPS = BM / RPL, GROUPS = (BM + BN) / RPL;  // row groups of a stage
     constexpr int LOADS = GROUPS / NW;                            // wave-wide loads per wave per stage
-    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;                   // output columns per block
     static_assert(BK == 32 || BK == 64, "K slab");
     static_assert(GROUPS % NW == 0, "loads must divide evenly over the waves");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
     static_assert(!SWIGLU || TN % 2 == 0, "a wave needs matching gate and up columns");
     static_assert((STAGES - 2) * LOADS < 64, "vmcnt range");
     static_assert(STAGES != 0 || BK == 64, "the pipelined loop is written for 64-wide slabs");
-
-    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-
-    // ---- which tile ----
-    const int nt = *n_tiles;
-    const int nb_total = Nout / NCOLS;
-    const int total = nt * nb_total;
-    const int chunk = (total + 7) >> 3;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int logical = xcd * chunk + slot;
-    if (slot >= chunk || logical >= total) return;
-    const int per_group = nt * col_group;
-    const int cg = logical / per_group, rem = logical - cg * per_group;
-    const int tile = rem / col_group, nb = cg * col_group + (rem - tile * col_group);
-    const int e = tile_expert[tile], row0 = tile_row0[tile], rows = tile_rows[tile];
-    const int n0 = nb * NCOLS;
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv % WAVES_M, wn = wv / WAVES_M;
@@ -435,6 +448,46 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void ffn_gemm_bf16_kernel(
         }
     }
 }
+};
+
+// Decode a block's position in a list of `total` = tiles x column blocks work items, ordered
+// [column group][row tile][column in group].
+__device__ inline void decode_item(int logical, int nt, int col_group, int& tile, int& nb) {
+    const int per_group = nt * col_group;
+    const int cg = logical / per_group, rem = logical - cg * per_group;
+    tile = rem / col_group;
+    nb = cg * col_group + (rem - tile * col_group);
+}
+
+// One launch serves both tile lists.  Every XCD (block id mod 8) gets a contiguous eighth of the
+// big tiles, then a contiguous eighth of the small tiles: long blocks first, short ones fill the
+// tail, and blocks that run together on an XCD share row and weight tiles in its L2.
+template <class Big, class Small, bool SWIGLU>
+__global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
+    uint16_t* __restrict__ C, const int32_t* __restrict__ b_expert, const int32_t* __restrict__ b_row0,
+    const int32_t* __restrict__ b_rows, const int32_t* __restrict__ b_count, const int32_t* __restrict__ s_expert,
+    const int32_t* __restrict__ s_row0, const int32_t* __restrict__ s_rows, const int32_t* __restrict__ s_count, int K,
+    int Nout, int col_group_big, int col_group_small) {
+    static_assert(Big::kThreads == Small::kThreads, "one block size");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const int nt_b = *b_count, nt_s = *s_count;
+    const int total_b = nt_b * (Nout / Big::kNCols), total_s = nt_s * (Nout / Small::kNCols);
+    const int chunk_b = (total_b + 7) >> 3, chunk_s = (total_s + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int tile, nb;
+    if (slot < chunk_b) {
+        const int logical = xcd * chunk_b + slot;
+        if (logical >= total_b) return;
+        decode_item(logical, nt_b, col_group_big, tile, nb);
+        Big::run(A, B0, B1, C, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem);
+    } else if (slot - chunk_b < chunk_s) {
+        const int logical = xcd * chunk_s + (slot - chunk_b);
+        if (logical >= total_s) return;
+        decode_item(logical, nt_s, col_group_small, tile, nb);
+        Small::run(A, B0, B1, C, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem);
+    }
+}
 
 static int column_group(int nb_total) {
     for (int g = 4; g > 1; --g)
@@ -442,32 +495,23 @@ static int column_group(int nb_total) {
     return 1;
 }
 
-template <int BM, int BN, int BK, int STAGES, int WAVES_M, int WAVES_N, bool SWIGLU>
+template <class Big, class Small, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const FfnWorkspace& ws, int K, int Nout,
                         hipStream_t st) {
-    ProfileScope prof(SWIGLU ? MOE_KERNEL_FFN_GATE_UP : MOE_KERNEL_FFN_DOWN, st);
-    constexpr int NCOLS = SWIGLU ? BN / 2 : BN;
-    const size_t lds = (size_t)(STAGES == 0 ? 2 : STAGES) * (BM + BN) * BK * 2;
-    auto kern = ffn_gemm_bf16_kernel<BM, BN, BK, STAGES, WAVES_M, WAVES_N, SWIGLU>;
+    constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
+    auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
     static bool configured = false;
     if (!configured) {
-        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         configured = true;
     }
-    const int nb_total = Nout / NCOLS;
-    const long long grid = (long long)nb_total * ws.max_tiles + 8;  // + 8: every XCD gets a whole chunk
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WAVES_M * WAVES_N), lds, st, (const uint16_t*)A,
-                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, ws.tile_expert, ws.tile_row0,
-                       ws.tile_rows, ws.n_tiles, K, Nout, column_group(nb_total));
-}
-
-static int tuning_variant() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("CAPMOE_FFN_VARIANT");  // kernel-tuning switch, not a documented interface
-        v = e ? atoi(e) : 0;
-    }
-    return v;
+    const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
+    // + 16: both lists are cut into eight whole chunks
+    const long long grid = (long long)nb_b * ws.big.max_tiles + (long long)nb_s * ws.small.max_tiles + 16;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
+                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, ws.big.expert, ws.big.row0, ws.big.rows,
+                       ws.big.count, ws.small.expert, ws.small.row0, ws.small.rows, ws.small.count, K, Nout,
+                       column_group(nb_b), column_group(nb_s));
 }
 
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
@@ -476,46 +520,40 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
     (void)s;
     {
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts, ws.tile_m,
-                           ws.tile_expert, ws.tile_row0, ws.tile_rows, ws.n_tiles, ws.max_tiles);
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts, ws.big.tile_m,
+                           ws.small.tile_m, ws.small_max, ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count,
+                           ws.big.max_tiles, ws.small.expert, ws.small.row0, ws.small.rows, ws.small.count,
+                           ws.small.max_tiles);
     }
+    const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
     if (d.dtype == MOE_DTYPE_BF16) {
-        switch (tuning_variant()) {
-            case 1:
-                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
-                break;
-            case 2:
-                launch_bf16<kFfnTileM, 256, 64, 0, 2, 2, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-                launch_bf16<kFfnTileM, 256, 64, 0, 2, 2, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
-                break;
-            case 3:
-                launch_bf16<kFfnTileM, 256, 64, 2, 4, 2, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-                launch_bf16<kFfnTileM, 128, 64, 3, 4, 2, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
-                break;
-            case 4:
-                launch_bf16<kFfnTileM, 256, 64, 2, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-                launch_bf16<kFfnTileM, 256, 64, 2, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
-                break;
-            default:
-                launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, true>(xp, w_gate, w_up, ws.hidden, ws, d.d_model, d.d_hidden, st);
-                if (d.d_model % 256 == 0)
-                    launch_bf16<kFfnTileM, 256, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
-                else  // d is a multiple of 128 only: 128 output columns per block
-                    launch_bf16<kFfnTileM, 128, 64, 0, 2, 4, false>(ws.hidden, w_down, nullptr, yp, ws, d.d_hidden, d.d_model, st);
+        // big tiles: 256 x 256 x 64, two stages, software-pipelined; small tiles: 64 x 256 x 64, four stages
+        {
+            ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
+            launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, true>,
+                        true>(xp, w_gate, w_up, ws.hidden, ws, K1, N1, st);
         }
+        ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
+        if (N2 % 256 == 0)
+            launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, false>,
+                        TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, ws, K2,
+                                                                                    N2, st);
+        else  // d is a multiple of 128 only: 128 output columns per block
+            launch_bf16<TileConfig<kFfnTileM, 128, 64, 0, 2, 4, false>,
+                        TileConfig<kFfnTileSmall, 128, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, ws, K2,
+                                                                                    N2, st);
     } else {
-        const dim3 g1(((d.d_hidden + 15) / 16) * ws.max_tiles), g2(((d.d_model + 15) / 16) * ws.max_tiles);
+        const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), g1, dim3(256), 0, st, (const float*)xp,
-                               (const float*)w_gate, (const float*)w_up, (float*)ws.hidden, ws.tile_expert,
-                               ws.tile_row0, ws.tile_rows, ws.n_tiles, d.d_model, d.d_hidden);
+                               (const float*)w_gate, (const float*)w_up, (float*)ws.hidden, ws.big.expert, ws.big.row0,
+                               ws.big.rows, ws.big.count, K1, N1);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), g2, dim3(256), 0, st, (const float*)ws.hidden,
-                           (const float*)w_down, (const float*)nullptr, (float*)yp, ws.tile_expert, ws.tile_row0,
-                           ws.tile_rows, ws.n_tiles, d.d_hidden, d.d_model);
+                           (const float*)w_down, (const float*)nullptr, (float*)yp, ws.big.expert, ws.big.row0,
+                           ws.big.rows, ws.big.count, K2, N2);
     }
     return hipGetLastError();
 }
