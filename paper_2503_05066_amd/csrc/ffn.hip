@@ -11,7 +11,6 @@
 // XOR swizzle, multiplied on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
 // The weight rows feed the MFMA's first operand and the activation rows the second, so a lane
 // ends up with 4 consecutive output columns of one row and stores them as one 8-byte piece.
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
