@@ -78,10 +78,12 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
     size_t off = 0;
     const bool bf16 = d.dtype == MOE_DTYPE_BF16;
     w.big.tile_m = bf16 ? kFfnTileM : kFfnTileMF32;
+
     w.big.max_tiles = (int)(s.max_rows / w.big.tile_m) + d.n_experts;
     w.small.tile_m = kFfnTileSmall;
     w.small_max = bf16 ? kFfnSmallMax : 0;
     w.small.max_tiles = bf16 ? d.n_experts * (kFfnSmallMax / kFfnTileSmall) : 0;
+
     w.hidden = p + off;
     off += align256((size_t)(s.max_rows > 0 ? s.max_rows : 1) * d.d_hidden * s.elem);
     for (TileList* t : {&w.big, &w.small}) {

@@ -7,9 +7,10 @@
 //                     written expert-major so that a capacity segment is one contiguous run.
 //   2. drop_select    per segment: the cap-th largest key by a 4-pass radix select over LDS
 //                     histograms (the threshold tau of Eq. 8) and how many keys equal to it survive.
-//   3. drop_emit      per segment: ordered compaction of the survivors (ballot + prefix counts),
-//                     which yields rows in ascending token order and gives ties at the threshold
-//                     to the lower token index.
+//   3. drop_emit      per segment: ordered compaction of the survivors, which yields rows in
+//                     ascending token order and gives ties at the threshold to the lower token index.
+// Every kernel first pulls what it needs from global memory in one batch of independent loads
+// (these kernels are latency-bound: a dependent load per loop iteration costs a microsecond each).
 #include "common.h"
 
 namespace capmoe {
@@ -25,41 +26,40 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
                                                            int32_t* __restrict__ pair_row, int N, int E, int k, int S,
                                                            int expanded, int group_tokens, int group_experts) {
     extern __shared__ uint32_t lds[];
-    const int ld = E | 1;                                     // odd row pitch: conflict-free transposed reads
-    uint32_t* key_s = lds;                                    // [64][ld]
-    uint8_t* slot_s = (uint8_t*)(lds + kPrepTokens * ld);     // [64][ld]
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int ld = E | 1;                                  // odd row pitch: conflict-free transposed reads
+    uint32_t* key_s = lds;                                 // [64][ld] score bits, then keys
+    uint8_t* slot_s = (uint8_t*)(lds + kPrepTokens * ld);  // [64][ld] candidate flags, then slots
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int t0 = blockIdx.x * kPrepTokens;
+    const int nt = N - t0 < kPrepTokens ? N - t0 : kPrepTokens;  // tokens of this block
 
-    // candidate flags: a wave walks 16 tokens, lanes walk experts
-    for (int i = 0; i < 16; ++i) {
-        const int tl = wv * 16 + i;
-        for (int e = lane; e < E; e += kWave) key_s[tl * ld + e] = 0;
+    for (int i = tid; i < kPrepTokens * ld; i += 256) slot_s[i] = 0;
+    // the block's scores are one contiguous run of nt*E floats
+    for (int i = tid; i < nt * E; i += 256) {
+        const int tl = i / E, e = i - tl * E;
+        key_s[tl * ld + e] = __float_as_uint(scores[(size_t)t0 * E + i]);
     }
     __syncthreads();
-    for (int i = 0; i < 16; ++i) {
-        const int tl = wv * 16 + i, t = t0 + tl;
-        if (t >= N) break;
-        if (lane < k) key_s[tl * ld + topk_idx[(size_t)t * k + lane]] = 1;
-        if (expanded) {
-            const int e0 = (t / group_tokens) * group_experts;
-            for (int e = lane; e < group_experts; e += kWave) key_s[tl * ld + e0 + e] = 1;
+    for (int i = tid; i < nt * k; i += 256) slot_s[(i / k) * ld + topk_idx[(size_t)t0 * k + i]] = 1;
+    if (expanded) {
+        for (int i = tid; i < nt * group_experts; i += 256) {
+            const int tl = i / group_experts, j = i - tl * group_experts;
+            slot_s[tl * ld + ((t0 + tl) / group_tokens) * group_experts + j] = 1;
         }
     }
     __syncthreads();
-    // flags -> keys and slots (slot = number of candidate experts with a lower id)
+    // flags -> keys and slots (slot = number of candidate experts with a lower id); a wave walks 16 tokens
     for (int i = 0; i < 16; ++i) {
         const int tl = wv * 16 + i, t = t0 + tl;
-        if (t >= N) break;
+        if (tl >= nt) break;
         int base = 0;
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
-            const bool c = e < E && key_s[tl * ld + e] != 0;
+            const bool c = e < E && slot_s[tl * ld + e] != 0;
             const uint64_t mask = __ballot(c);
-            const int slot = base + __popcll(mask & ((1ull << lane) - 1ull));
             if (e < E) {
-                key_s[tl * ld + e] = c ? __float_as_uint(scores[(size_t)t * E + e]) + 1u : 0u;
-                slot_s[tl * ld + e] = (uint8_t)slot;
+                key_s[tl * ld + e] = c ? key_s[tl * ld + e] + 1u : 0u;
+                slot_s[tl * ld + e] = (uint8_t)(base + __popcll(mask & ((1ull << lane) - 1ull)));
             }
             base += __popcll(mask);
         }
@@ -69,19 +69,17 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
     __syncthreads();
     // transposed write: 64 consecutive tokens of one expert per wave
     for (int e = wv; e < E; e += 4) {
-        const int t = t0 + lane;
-        if (t < N) {
-            key_t[(size_t)e * N + t] = key_s[lane * ld + e];
-            slot_t[(size_t)e * N + t] = slot_s[lane * ld + e];
+        if (lane < nt) {
+            key_t[(size_t)e * N + t0 + lane] = key_s[lane * ld + e];
+            slot_t[(size_t)e * N + t0 + lane] = slot_s[lane * ld + e];
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// 2. threshold per segment
+// block-wide helpers (256 threads)
 // ---------------------------------------------------------------------------------------------
 __device__ inline int block_sum_256(int v, int* red) {
-    // red: 4 ints of LDS
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
     __syncthreads();
@@ -90,11 +88,35 @@ __device__ inline int block_sum_256(int v, int* red) {
     return red[0] + red[1] + red[2] + red[3];
 }
 
+// exclusive prefix sum of v over the block's threads; *total gets the block sum
+__device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int o = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) red[wv] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wv; ++w) before += red[w];
+    *total = red[0] + red[1] + red[2] + red[3];
+    return before + incl - v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// 2. threshold per segment
+// ---------------------------------------------------------------------------------------------
+constexpr int kSelectCache = 16384;  // keys of a segment kept in LDS (64 KB); longer segments re-read L2
+
 __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __restrict__ key_t,
                                                           uint32_t* __restrict__ seg_tau,
                                                           int32_t* __restrict__ seg_need,
                                                           int32_t* __restrict__ seg_count, int N, int E, int seg_tokens,
                                                           int cap) {
+    extern __shared__ uint32_t cache[];
     __shared__ int hist[256];
     __shared__ int red[4];
     __shared__ uint32_t sh_prefix;
@@ -103,10 +125,15 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
     const int b = seg / E, e = seg - b * E;
     const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
     const int tid = threadIdx.x;
+    const bool cached = seg_tokens <= kSelectCache;
 
     int mine = 0;
-    for (int i = tid; i < seg_tokens; i += 256) mine += keys[i] != 0u;
-    const int n_cand = block_sum_256(mine, red);
+    for (int i = tid; i < seg_tokens; i += 256) {
+        const uint32_t kx = keys[i];
+        if (cached) cache[i] = kx;
+        mine += kx != 0u;
+    }
+    const int n_cand = block_sum_256(mine, red);  // its barriers also order the cache writes before the reads
 
     if (n_cand <= cap || cap == 0) {
         if (tid == 0) {
@@ -125,26 +152,19 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         __syncthreads();
         const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
         for (int i = tid; i < seg_tokens; i += 256) {
-            const uint32_t kx = keys[i];
+            const uint32_t kx = cached ? cache[i] : keys[i];
             if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
         }
         __syncthreads();
-        // thread i owns digit 255 - i: an inclusive scan over threads counts the keys with a digit
-        // at least as large; the digit where that count first reaches `rem` holds the cap-th key
+        // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
+        // digit; the digit where that count first reaches `rem` holds the cap-th key
         const int mine_d = 255 - tid;
         const int h = hist[mine_d];
-        int incl = h;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int o = __shfl_up(incl, off, kWave);
-            if ((tid & 63) >= off) incl += o;
-        }
-        if ((tid & 63) == 63) red[tid >> 6] = incl;
-        __syncthreads();
-        for (int w = 0; w < (tid >> 6); ++w) incl += red[w];
-        if (incl >= rem && incl - h < rem) {  // exactly one thread
+        int total;
+        const int above = block_exclusive_scan_256(h, red, &total);
+        if (above + h >= rem && above < rem) {  // exactly one thread
             sh_prefix = prefix | ((uint32_t)mine_d << shift);
-            sh_rem = rem - (incl - h);
+            sh_rem = rem - above;
         }
         __syncthreads();
         prefix = sh_prefix;
@@ -160,6 +180,9 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
 // ---------------------------------------------------------------------------------------------
 // 3. ordered compaction
 // ---------------------------------------------------------------------------------------------
+constexpr int kEmitRun = 16;                // consecutive tokens per thread
+constexpr int kEmitChunk = 256 * kEmitRun;  // tokens per pass of the block
+
 __global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restrict__ key_t,
                                                         const uint8_t* __restrict__ slot_t,
                                                         const uint32_t* __restrict__ seg_tau,
@@ -170,12 +193,25 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restri
                                                         int32_t* __restrict__ row_token, float* __restrict__ row_weight,
                                                         int32_t* __restrict__ pair_row, int N, int E, int n_blocks,
                                                         int seg_tokens, int S) {
+    // a thread owns a run of 16 consecutive tokens; one padding word per run keeps the runs of
+    // neighbouring threads on different LDS banks
+    __shared__ uint32_t key_s[kEmitChunk + 256];
+    __shared__ uint8_t slot_s[kEmitChunk];
     __shared__ int red[4];
-    __shared__ int wave_kept[4], wave_eq[4];
     const int seg = blockIdx.x;
     const int b = seg / E, e = seg - b * E;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x;
 
+    const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
+    const uint8_t* slots = slot_t + (size_t)e * N + (size_t)b * seg_tokens;
+    // first chunk of keys and slots: issued before anything waits
+    {
+        const int n = seg_tokens < kEmitChunk ? seg_tokens : kEmitChunk;
+        for (int i = tid; i < n; i += 256) {
+            key_s[i + i / kEmitRun] = keys[i];
+            slot_s[i] = slots[i];
+        }
+    }
     // first row of this segment: all segments of lower experts, then lower blocks of this expert
     int before = 0, own = 0;
     for (int i = tid; i < n_blocks * E; i += 256) {
@@ -191,40 +227,57 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restri
         expert_offset[e] = row0;
         if (e == E - 1) expert_offset[E] = row0 + own_total;
     }
-
     const uint32_t tau = seg_tau[seg];
     const int need = seg_need[seg];
-    const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
-    const uint8_t* slots = slot_t + (size_t)e * N + (size_t)b * seg_tokens;
-    int kept_before = 0, eq_before = 0;  // running counts over the chunks already done
-    for (int c0 = 0; c0 < seg_tokens; c0 += 256) {
-        const int i = c0 + tid;
-        const uint32_t kx = i < seg_tokens ? keys[i] : 0u;
-        const bool cand = kx != 0u;
-        const bool eq = cand && kx == tau;
-        const uint64_t eq_mask = __ballot(eq);
-        if (lane == 0) wave_eq[wv] = __popcll(eq_mask);
-        __syncthreads();
-        int eq_rank = eq_before + __popcll(eq_mask & ((1ull << lane) - 1ull));
-        for (int w = 0; w < wv; ++w) eq_rank += wave_eq[w];
-        const bool keep = cand && (kx > tau || (eq && eq_rank < need));
-        const uint64_t keep_mask = __ballot(keep);
-        if (lane == 0) wave_kept[wv] = __popcll(keep_mask);
-        __syncthreads();
-        int pos = kept_before + __popcll(keep_mask & ((1ull << lane) - 1ull));
-        for (int w = 0; w < wv; ++w) pos += wave_kept[w];
-        if (cand) {
-            const int t = b * seg_tokens + i;
-            const int row = row0 + pos;
-            if (keep) {
-                row_token[row] = t;
-                row_weight[row] = __uint_as_float(kx - 1u);
+
+    int kept_base = 0, eq_base = 0;  // counts over the chunks already done
+    for (int c0 = 0; c0 < seg_tokens; c0 += kEmitChunk) {
+        const int n = seg_tokens - c0 < kEmitChunk ? seg_tokens - c0 : kEmitChunk;
+        if (c0 > 0) {
+            __syncthreads();
+            for (int i = tid; i < n; i += 256) {
+                key_s[i + i / kEmitRun] = keys[c0 + i];
+                slot_s[i] = slots[c0 + i];
             }
-            pair_row[(size_t)t * S + slots[i]] = keep ? row : -1;
         }
-        kept_before += wave_kept[0] + wave_kept[1] + wave_kept[2] + wave_kept[3];
-        eq_before += wave_eq[0] + wave_eq[1] + wave_eq[2] + wave_eq[3];
         __syncthreads();
+        uint32_t kx[kEmitRun];
+        int eq_cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kEmitRun; ++j) {
+            const int i = tid * kEmitRun + j;
+            kx[j] = i < n ? key_s[tid * (kEmitRun + 1) + j] : 0u;
+            eq_cnt += kx[j] != 0u && kx[j] == tau;
+        }
+        int eq_total, keep_total;
+        int eq_rank = eq_base + block_exclusive_scan_256(eq_cnt, red, &eq_total);
+        uint32_t keep_bits = 0;
+        int keep_cnt = 0;
+#pragma unroll
+        for (int j = 0; j < kEmitRun; ++j) {
+            const bool cand = kx[j] != 0u;
+            const bool eq = cand && kx[j] == tau;
+            const bool keep = cand && (kx[j] > tau || (eq && eq_rank < need));
+            eq_rank += eq;
+            keep_cnt += keep;
+            keep_bits |= (uint32_t)keep << j;
+        }
+        int pos = row0 + kept_base + block_exclusive_scan_256(keep_cnt, red, &keep_total);
+#pragma unroll
+        for (int j = 0; j < kEmitRun; ++j) {
+            if (kx[j] == 0u) continue;
+            const int i = tid * kEmitRun + j;
+            const int t = b * seg_tokens + c0 + i;
+            const bool keep = (keep_bits >> j) & 1u;
+            if (keep) {
+                row_token[pos] = t;
+                row_weight[pos] = __uint_as_float(kx[j] - 1u);
+            }
+            pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
+            pos += keep;
+        }
+        kept_base += keep_total;
+        eq_base += eq_total;
     }
 }
 
@@ -247,7 +300,14 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     const int segs = s.n_blocks * E;
     {
         ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
-        hipLaunchKernelGGL(drop_select_kernel, dim3(segs), dim3(256), 0, st, ws.key_t, ws.seg_tau, ws.seg_need,
+        const size_t lds = (size_t)(s.seg_tokens <= kSelectCache ? s.seg_tokens : 0) * 4;
+        static bool configured = false;
+        if (!configured) {  // 64 KB of keys plus the kernel's own few hundred bytes
+            (void)hipFuncSetAttribute((const void*)drop_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kSelectCache * 4);
+            configured = true;
+        }
+        hipLaunchKernelGGL(drop_select_kernel, dim3(segs), dim3(256), lds, st, ws.key_t, ws.seg_tau, ws.seg_need,
                            seg_count, N, E, s.seg_tokens, s.cap);
     }
     {

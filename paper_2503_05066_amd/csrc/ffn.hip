@@ -208,8 +208,9 @@ struct MainLoop {
 // cycles but the wave's issue port only for a few):
 //     k-step 0..2 of slab kt:  MFMAs of the step  |  operand reads of the next step
 //     barrier (slab kt+1 landed, slab kt no longer read)
-//     k-step 3 of slab kt:     MFMAs              |  fills of slab kt+2, operand reads of slab kt+1 step 0
-// __builtin_amdgcn_sched_barrier(0) pins the order written here.
+//     k-step 3 of slab kt:     MFMAs              |  operand reads of slab kt+1 step 0, fills of slab kt+2
+// Operands are read in the order the next step's MFMAs need them, so every read has a full k-step
+// of matrix work to hide behind.  __builtin_amdgcn_sched_barrier(0) pins the order written here.
 template <int BM, int BN, int NW, int TM, int TN, int LOADS>
 struct PipelinedLoop {
     static constexpr int BK = 64;
@@ -222,12 +223,20 @@ struct PipelinedLoop {
     const int* b_sw;
     int KT, wv, lk;
 
+    __device__ __forceinline__ void fill_one(int i, int kt) const {
+        __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BK),
+                                         (lptr_t)(smem + (kt & 1) * STAGE_BYTES + (wv + NW * i) * 1024), 16, 0, 0);
+    }
+    __device__ __forceinline__ void fill(int kt) const {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) fill_one(i, kt);
+    }
+
     template <int LIVE>
     __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
-        if (LIVE == 0) {  // nothing to multiply in this wave: only keep the barriers of the block
+        if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
             for (int kt = 0; kt <= KT; ++kt) {
-                // other waves fill their own pieces; this wave still fills its share
-                if (kt < KT) fill(kt, src);
+                if (kt < KT) fill(kt);
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 __builtin_amdgcn_s_barrier();
             }
@@ -235,6 +244,8 @@ struct PipelinedLoop {
         }
         constexpr int NL = LIVE > 0 ? LIVE : 1;
         constexpr int NMFMA = TN * NL, NREAD = NL + TN;
+        constexpr int NSTEP = NMFMA > NREAD ? NMFMA : NREAD;
+        constexpr int NSTEP3 = NSTEP > LOADS ? NSTEP : LOADS;
         bf16x8 xa[2][NL], wb[2][TN];
         // lane's operand addresses for k-step 0 of stage 0; step ks flips piece bits 1-2 (byte bits 5-6)
         int ra[NL], rb[TN];
@@ -243,15 +254,25 @@ struct PipelinedLoop {
 #pragma unroll
         for (int i = 0; i < TN; ++i) rb[i] = b_off[i] + ((lk ^ b_sw[i]) << 4);
 
-        fill(0, src);
+        // r-th operand read of a k-step, in the order the MFMAs (activation sub-tile major) need them:
+        // weight 0, activation 0, weights 1.., activations 1..
+        auto read_item = [&](int r, int set, const uint8_t* s, int flip) {
+            if (r == 0)
+                wb[set][0] = *(const bf16x8*)(s + (rb[0] ^ flip));
+            else if (r == 1)
+                xa[set][0] = *(const bf16x8*)(s + (ra[0] ^ flip));
+            else if (r <= TN)
+                wb[set][r - 1] = *(const bf16x8*)(s + (rb[r - 1] ^ flip));
+            else
+                xa[set][r - TN] = *(const bf16x8*)(s + (ra[r - TN] ^ flip));
+        };
+
+        fill(0);
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         __builtin_amdgcn_s_barrier();
-        if (1 < KT) fill(1, src);
-        // operand reads of slab 0, k-step 0
+        if (1 < KT) fill(1);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) xa[0][j] = *(const bf16x8*)(smem + ra[j]);
-#pragma unroll
-        for (int i = 0; i < TN; ++i) wb[0][i] = *(const bf16x8*)(smem + rb[i]);
+        for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, 0);
 
         for (int kt = 0; kt < KT; ++kt) {
             const uint8_t* s = smem + (kt & 1) * STAGE_BYTES;
@@ -259,15 +280,12 @@ struct PipelinedLoop {
             for (int ks = 0; ks < 3; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1, flip = (ks + 1) << 5;
 #pragma unroll
-                for (int q = 0; q < (NMFMA > NREAD ? NMFMA : NREAD); ++q) {
+                for (int q = 0; q < NSTEP; ++q) {
                     if (q < NMFMA) {
                         const int j = q / TN, i = q % TN;
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
                     }
-                    if (q < NL)
-                        xa[nxt][q] = *(const bf16x8*)(s + (ra[q] ^ flip));
-                    else if (q < NREAD)
-                        wb[nxt][q - NL] = *(const bf16x8*)(s + (rb[q - NL] ^ flip));
+                    if (q < NREAD) read_item(q, nxt, s, flip);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -275,32 +293,19 @@ struct PipelinedLoop {
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0) & ~(15 << 8));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            if (kt + 2 < KT) fill(kt + 2, src);
             const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE_BYTES;
-            const bool more = kt + 1 < KT;
+            const bool more = kt + 1 < KT, refill = kt + 2 < KT;
 #pragma unroll
-            for (int q = 0; q < (NMFMA > NREAD ? NMFMA : NREAD); ++q) {
+            for (int q = 0; q < NSTEP3; ++q) {
                 if (q < NMFMA) {
                     const int j = q / TN, i = q % TN;
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
                 }
-                if (more) {
-                    if (q < NL)
-                        xa[0][q] = *(const bf16x8*)(sn + ra[q]);
-                    else if (q < NREAD)
-                        wb[0][q - NL] = *(const bf16x8*)(sn + rb[q - NL]);
-                }
+                if (q < NREAD && more) read_item(q, 0, sn, 0);
+                if (q < LOADS && refill) fill_one(q, kt + 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
-
-    __device__ __forceinline__ void fill(int kt, const uint16_t* const* p) const {
-        uint8_t* dst = smem + (kt & 1) * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(p[i] + (size_t)kt * BK), (lptr_t)(dst + (wv + NW * i) * 1024), 16,
-                                             0, 0);
     }
 };
 
