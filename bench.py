@@ -38,6 +38,8 @@ def parse():
     p.add_argument("--scope", default="local", choices=list(SCOPES))
     p.add_argument("--gamma", type=float, default=1.0)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--unfused", action="store_true",
+                   help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
     p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none",
                    help="comma list of workload:mode measured after the main line ('' for none)")
     return p.parse_args()
@@ -85,7 +87,7 @@ def algorithmic_work(w, S, rows, active, elem):
     }
 
 
-def measure(w, mode, scope, gamma, steps, warmup):
+def measure(w, mode, scope, gamma, steps, warmup, fused=True):
     import torch
 
     from paper_2503_05066_amd import capmoe, synth
@@ -97,7 +99,8 @@ def measure(w, mode, scope, gamma, steps, warmup):
     K_GU = capmoe.KERNELS.index("ffn_gate_up")
 
     def step():
-        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"])
+        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
+                             fused_dispatch=fused)
 
     for _ in range(warmup):
         step()
@@ -137,6 +140,9 @@ def measure(w, mode, scope, gamma, steps, warmup):
     active = int((counts > 0).sum())
     elem = 2 if w.dtype == synth.DTYPE_BF16 else 4
     work = algorithmic_work(w, buf.slots, rows, active, elem)
+    if fused:   # the permuted copy is never written: the first GEMM reads x through row_token
+        work["dispatch"]["bytes"] = 0
+        kernel_ms["dispatch"] = 0.0
     nbar = w.n_tokens * w.top_k / w.n_experts
     res = {
         "wall_s": wall, "ms_per_step": 1e3 * wall / steps, "tokens_per_s": w.n_tokens * steps / wall,
@@ -214,7 +220,7 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[a.workload]
     mode, scope = MODES[a.mode], SCOPES[a.scope]
-    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup)
+    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused)
     primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
     primary["kernel"] = other["kernel"] = "grouped_gemm_bf16_kernel<SWIGLU> (gate/up GEMM + SwiGLU)"
     stages = {}
@@ -224,6 +230,9 @@ def main():
                      ("dispatch", km["dispatch"]), ("ffn_gate_up", km["ffn_gate_up"]), ("ffn_down", km["ffn_down"]),
                      ("combine", km["combine"])]:
         wk = r["work"][name]
+        if ms <= 0.0:
+            stages[name] = {"ms": 0.0, "note": "fused into ffn_gate_up"}
+            continue
         stages[name] = {"ms": round(ms, 4), "GB/s": round(wk["bytes"] / ms / 1e6, 1),
                         "hbm_frac": round(wk["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4)}
         if wk["flops"]:
@@ -237,7 +246,9 @@ def main():
                                f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity",
                    "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
                    "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
-                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3)},
+                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3),
+                   "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
+                            "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"},
         "roofline": primary, "roofline_other_roof": other, "stages": stages,
     }
     if not a.no_cpu_baseline:
@@ -248,7 +259,7 @@ def main():
         if name == a.workload and m == a.mode:
             continue
         ow = synth.WORKLOADS[name]
-        o = measure(ow, MODES[m], scope, a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5))
+        o = measure(ow, MODES[m], scope, a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5), fused=not a.unfused)
         p1, p2 = roofline_of(o["work"]["ffn_gate_up"], o["gate_up_ms"])
         d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
         others.append({"workload": name, "mode": m, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],

@@ -134,6 +134,15 @@ int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* exper
                     void* stream);
 
 /*
+ * moe_dispatch followed by moe_grouped_ffn in one call, without materialising xp: the first GEMM
+ * fetches row r of the plan from x[row_token[r],:] directly (same arithmetic, bit-identical yp).
+ *   x [N,d] in desc->dtype, row_token [P_max] and expert_offset [E+1] from moe_capacity_drop.
+ */
+int moe_dispatch_ffn(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
+                     const void* w_gate, const void* w_up, const void* w_down, void* yp, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/*
  * Weighted sum of Eq. (2) over the surviving pairs: y[t,:] = sum_slots row_weight[r] * yp[r,:],
  * r = pair_row[t,slot] >= 0, slots in ascending order (= ascending expert id), accumulated in
  * fp32.  A token with no surviving pair gets y[t,:] = 0.  y is [N,d].

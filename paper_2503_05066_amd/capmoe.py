@@ -57,11 +57,12 @@ def load():
         lib.moe_capacity_drop.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_dispatch_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_profile_attach.argtypes = [i32, vp, vp]
         lib.moe_profile_attach.restype = i32
         for f in ("moe_query", "moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn",
-                  "moe_combine"):
+                  "moe_dispatch_ffn", "moe_combine"):
             getattr(lib, f).restype = i32
         _lib = lib
     return _lib
@@ -130,6 +131,12 @@ def moe_grouped_ffn(desc, xp, expert_offset, w_gate, w_up, w_down, yp, workspace
                                   workspace.numel() * workspace.element_size(), _stream(stream)), "moe_grouped_ffn")
 
 
+def moe_dispatch_ffn(desc, x, expert_offset, row_token, w_gate, w_up, w_down, yp, workspace, stream=None):
+    _check(load().moe_dispatch_ffn(ctypes.byref(desc), _ptr(x), _ptr(expert_offset), _ptr(row_token), _ptr(w_gate),
+                                   _ptr(w_up), _ptr(w_down), _ptr(yp), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "moe_dispatch_ffn")
+
+
 def moe_combine(desc, yp, row_weight, pair_row, y, stream=None):
     _check(load().moe_combine(ctypes.byref(desc), _ptr(yp), _ptr(row_weight), _ptr(pair_row), _ptr(y),
                               _stream(stream)), "moe_combine")
@@ -175,8 +182,13 @@ class LayerBuffers:
         self.workspace = mk((max(self.workspace_bytes, 256),), torch.uint8)
 
 
-def layer_forward(buf: LayerBuffers, x, w_router, bias, w_gate, w_up, w_down, given_logits=None, stream=None):
-    """The five calls of one layer, enqueued back to back on one stream; returns buf.y."""
+def layer_forward(buf: LayerBuffers, x, w_router, bias, w_gate, w_up, w_down, given_logits=None, stream=None,
+                  fused_dispatch=False):
+    """The calls of one layer, enqueued back to back on one stream; returns buf.y.
+
+    fused_dispatch=False: the five calls route_topk, capacity_drop, dispatch, grouped_ffn, combine.
+    fused_dispatch=True: dispatch and grouped_ffn are replaced by moe_dispatch_ffn (xp is not written).
+    """
     d = buf.desc
     if given_logits is not None:
         buf.logits.copy_(given_logits)
@@ -184,8 +196,11 @@ def layer_forward(buf: LayerBuffers, x, w_router, bias, w_gate, w_up, w_down, gi
                    buf.topk_score, buf.workspace, stream)
     moe_capacity_drop(d, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
                       buf.row_token, buf.row_weight, buf.pair_row, buf.workspace, stream)
-    moe_dispatch(d, x, buf.expert_offset, buf.row_token, buf.xp, stream)
-    moe_grouped_ffn(d, buf.xp, buf.expert_offset, w_gate, w_up, w_down, buf.yp, buf.workspace, stream)
+    if fused_dispatch:
+        moe_dispatch_ffn(d, x, buf.expert_offset, buf.row_token, w_gate, w_up, w_down, buf.yp, buf.workspace, stream)
+    else:
+        moe_dispatch(d, x, buf.expert_offset, buf.row_token, buf.xp, stream)
+        moe_grouped_ffn(d, buf.xp, buf.expert_offset, w_gate, w_up, w_down, buf.yp, buf.workspace, stream)
     moe_combine(d, buf.yp, buf.row_weight, buf.pair_row, buf.y, stream)
     return buf.y
 

@@ -167,9 +167,12 @@ int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router,
     if (!use_given_logits) {
         const RouteWorkspace ws = route_workspace(*desc, workspace);
         if (ws.use_mfma) {
-            if (!workspace) return MOE_ERR_INVALID_ARG;
-            if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
-            if (((uintptr_t)workspace & 255) != 0 || misaligned16(x)) return MOE_ERR_INVALID_ARG;
+            if (ws.bytes > 0) {
+                if (!workspace) return MOE_ERR_INVALID_ARG;
+                if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+                if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+            }
+            if (misaligned16(x) || misaligned16(w_router)) return MOE_ERR_INVALID_ARG;
             if (launch_router_mfma(*desc, ws, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
             if (ws.ksplit > 1) {
                 partial = ws.partial;
@@ -217,13 +220,13 @@ int moe_dispatch(const moe_desc_t* desc, const void* x, const int32_t* expert_of
     return MOE_OK;
 }
 
-int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* expert_offset, const void* w_gate,
-                    const void* w_up, const void* w_down, void* yp, void* workspace, size_t workspace_bytes,
-                    void* stream) {
+static int grouped_ffn_impl(const moe_desc_t* desc, const void* a, const int32_t* row_token,
+                            const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
+                            void* yp, void* workspace, size_t workspace_bytes, void* stream) {
     const int v = validate(desc);
     if (v != MOE_OK) return v;
-    if (!xp || !expert_offset || !w_gate || !w_up || !w_down || !yp || !workspace) return MOE_ERR_INVALID_ARG;
-    if (misaligned16(xp) || misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
+    if (!a || !expert_offset || !w_gate || !w_up || !w_down || !yp || !workspace) return MOE_ERR_INVALID_ARG;
+    if (misaligned16(a) || misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
         return MOE_ERR_INVALID_ARG;
     const int sh = ffn_shape_supported(*desc);
     if (sh != MOE_OK) return sh;
@@ -232,10 +235,25 @@ int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* exper
     if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
     if (s.max_rows == 0) return MOE_OK;
-    if (launch_grouped_ffn(*desc, s, ws, xp, expert_offset, w_gate, w_up, w_down, yp, (hipStream_t)stream) !=
+    if (launch_grouped_ffn(*desc, s, ws, a, row_token, expert_offset, w_gate, w_up, w_down, yp, (hipStream_t)stream) !=
         hipSuccess)
         return MOE_ERR_HIP;
     return MOE_OK;
+}
+
+int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* expert_offset, const void* w_gate,
+                    const void* w_up, const void* w_down, void* yp, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    return grouped_ffn_impl(desc, xp, nullptr, expert_offset, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
+                            stream);
+}
+
+int moe_dispatch_ffn(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
+                     const void* w_gate, const void* w_up, const void* w_down, void* yp, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    if (!row_token) return MOE_ERR_INVALID_ARG;
+    return grouped_ffn_impl(desc, x, row_token, expert_offset, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
+                            stream);
 }
 
 int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight, const int32_t* pair_row, void* y,

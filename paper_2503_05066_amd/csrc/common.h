@@ -46,11 +46,10 @@ struct DropWorkspace {
 };
 DropWorkspace drop_workspace(const moe_desc_t& d, const Sizes& s, void* base);
 
-// Workspace layout of moe_route_topk (bf16 activations: router GEMM on the matrix cores).
+// Workspace layout of moe_route_topk (bf16 activations: router GEMM on the matrix cores, split over K).
 struct RouteWorkspace {
     bool use_mfma;    // false: fp32 activations or an unsupported width, plain fp32 kernel, no workspace
     int ksplit;       // K slices; > 1: partial sums go to `partial` and the softmax kernel adds them
-    uint16_t* w3;     // [3,E,d] bf16 planes of the router weight
     float* partial;   // [ksplit,N,E]
     size_t bytes;
 };
@@ -107,7 +106,7 @@ hipError_t launch_dispatch(const moe_desc_t& d, const Sizes& s, const void* x, c
 hipError_t launch_combine(const moe_desc_t& d, const Sizes& s, const void* yp, const float* row_weight,
                           const int32_t* pair_row, void* y, hipStream_t st);
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
-                              const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
-                              void* yp, hipStream_t st);
+                              const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
+                              const void* w_up, const void* w_down, void* yp, hipStream_t st);
 
 }  // namespace capmoe

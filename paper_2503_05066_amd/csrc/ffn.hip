@@ -90,7 +90,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
                                                                const int32_t* __restrict__ tile_expert,
                                                                const int32_t* __restrict__ tile_row0,
                                                                const int32_t* __restrict__ tile_rows,
-                                                               const int32_t* __restrict__ n_tiles, int K, int Nout) {
+                                                               const int32_t* __restrict__ n_tiles,
+                                                               const int32_t* __restrict__ gather, int K, int Nout) {
     __shared__ float as[16][17], b0s[16][17], b1s[16][17];
     const int nt = *n_tiles;
     if (nt == 0) return;
@@ -102,9 +103,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
     const float* b0 = B0 + (size_t)e * Nout * K;
     const float* b1 = SWIGLU ? B1 + (size_t)e * Nout * K : nullptr;
     float acc0 = 0.f, acc1 = 0.f;
+    const int arow = ty < rows ? (gather ? gather[row0 + ty] : row0 + ty) : 0;
     for (int k0 = 0; k0 < K; k0 += 16) {
         const int kk = k0 + tx;
-        as[ty][tx] = (ty < rows && kk < K) ? A[(size_t)(row0 + ty) * K + kk] : 0.f;
+        as[ty][tx] = (ty < rows && kk < K) ? A[(size_t)arow * K + kk] : 0.f;
         b0s[ty][tx] = (n0 + ty < Nout && kk < K) ? b0[(size_t)(n0 + ty) * K + kk] : 0.f;
         if (SWIGLU) b1s[ty][tx] = (n0 + ty < Nout && kk < K) ? b1[(size_t)(n0 + ty) * K + kk] : 0.f;
         __syncthreads();
@@ -333,8 +335,9 @@ struct TileConfig {
     static constexpr int kLdsBytes = (STAGES == 0 ? 2 : STAGES) * (BM + BN) * BK * 2;
 
     static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
-                                               const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int e,
-                                               int row0, int rows, int n0, int K, int Nout, uint8_t* smem) {
+                                               const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+                                               const int32_t* __restrict__ gather, int e, int row0, int rows, int n0,
+                                               int K, int Nout, uint8_t* smem) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -361,7 +364,9 @@ struct TileConfig {
         const int kc = (lane % CPR) ^ (CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3);
         if (g < A_GROUPS) {
             const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
-            src[i] = A + (size_t)(row0 + rr) * K + kc * 8;
+            // with a gather list the activation rows are fetched from the unpermuted input
+            const int arow = gather ? gather[row0 + rr] : row0 + rr;
+            src[i] = A + (size_t)arow * K + kc * 8;
         } else {
             const int rb = r - BM;
             if (SWIGLU && rb >= BN / 2)
@@ -469,7 +474,8 @@ __device__ inline void decode_item(int logical, int nt, int col_group, int& tile
 template <class Big, class Small, bool SWIGLU>
 __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
-    uint16_t* __restrict__ C, const int32_t* __restrict__ b_expert, const int32_t* __restrict__ b_row0,
+    uint16_t* __restrict__ C, const int32_t* __restrict__ gather, const int32_t* __restrict__ b_expert,
+    const int32_t* __restrict__ b_row0,
     const int32_t* __restrict__ b_rows, const int32_t* __restrict__ b_count, const int32_t* __restrict__ s_expert,
     const int32_t* __restrict__ s_row0, const int32_t* __restrict__ s_rows, const int32_t* __restrict__ s_count, int K,
     int Nout, int col_group_big, int col_group_small) {
@@ -484,12 +490,12 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
         const int logical = xcd * chunk_b + slot;
         if (logical >= total_b) return;
         decode_item(logical, nt_b, col_group_big, tile, nb);
-        Big::run(A, B0, B1, C, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem);
+        Big::run(A, B0, B1, C, gather, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem);
     } else if (slot - chunk_b < chunk_s) {
         const int logical = xcd * chunk_s + (slot - chunk_b);
         if (logical >= total_s) return;
         decode_item(logical, nt_s, col_group_small, tile, nb);
-        Small::run(A, B0, B1, C, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem);
+        Small::run(A, B0, B1, C, gather, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem);
     }
 }
 
@@ -500,8 +506,8 @@ static int column_group(int nb_total) {
 }
 
 template <class Big, class Small, bool SWIGLU>
-static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const FfnWorkspace& ws, int K, int Nout,
-                        hipStream_t st) {
+static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const int32_t* gather,
+                        const FfnWorkspace& ws, int K, int Nout, hipStream_t st) {
     constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
     auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
     static bool configured = false;
@@ -513,14 +519,16 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
     // + 16: both lists are cut into eight whole chunks
     const long long grid = (long long)nb_b * ws.big.max_tiles + (long long)nb_s * ws.small.max_tiles + 16;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
-                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, ws.big.expert, ws.big.row0, ws.big.rows,
+                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, ws.big.expert, ws.big.row0, ws.big.rows,
                        ws.big.count, ws.small.expert, ws.small.row0, ws.small.rows, ws.small.count, K, Nout,
                        column_group(nb_b), column_group(nb_s));
 }
 
+// row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
+// plan is fetched from x[row_token[r]] (dispatch fused into the first GEMM's operand fetch).
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
-                              const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
-                              void* yp, hipStream_t st) {
+                              const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
+                              const void* w_up, const void* w_down, void* yp, hipStream_t st) {
     (void)s;
     {
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
@@ -535,29 +543,29 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, true>,
-                        true>(xp, w_gate, w_up, ws.hidden, ws, K1, N1, st);
+                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws, K1, N1, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         if (N2 % 256 == 0)
             launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, false>,
-                        TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, ws, K2,
-                                                                                    N2, st);
+                        TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
+                                                                                    K2, N2, st);
         else  // d is a multiple of 128 only: 128 output columns per block
             launch_bf16<TileConfig<kFfnTileM, 128, 64, 0, 2, 4, false>,
-                        TileConfig<kFfnTileSmall, 128, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, ws, K2,
-                                                                                    N2, st);
+                        TileConfig<kFfnTileSmall, 128, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
+                                                                                    K2, N2, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             hipLaunchKernelGGL((grouped_gemm_f32_kernel<true>), g1, dim3(256), 0, st, (const float*)xp,
                                (const float*)w_gate, (const float*)w_up, (float*)ws.hidden, ws.big.expert, ws.big.row0,
-                               ws.big.rows, ws.big.count, K1, N1);
+                               ws.big.rows, ws.big.count, row_token, K1, N1);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         hipLaunchKernelGGL((grouped_gemm_f32_kernel<false>), g2, dim3(256), 0, st, (const float*)ws.hidden,
                            (const float*)w_down, (const float*)nullptr, (float*)yp, ws.big.expert, ws.big.row0,
-                           ws.big.rows, ws.big.count, K2, N2);
+                           ws.big.rows, ws.big.count, (const int32_t*)nullptr, K2, N2);
     }
     return hipGetLastError();
 }

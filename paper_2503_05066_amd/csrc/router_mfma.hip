@@ -7,8 +7,9 @@
 //
 // Work split: a block owns 128 tokens (4 waves x 32) and one slice of K; the slices' partial sums
 // are added, in slice order, by the softmax kernel (deterministic: no floating-point atomics).
-// The weight planes of a 32-wide k-slab go through LDS (shared by the 4 waves, filled by direct
-// global->LDS loads, two stages); each wave reads its own 32 token rows straight from global memory.
+// The fp32 weights of a 32-wide k-slab are split in registers and the three planes go to LDS
+// (shared by the 4 waves, two stages); each wave reads its own 32 token rows straight from global
+// memory.
 #include "common.h"
 
 namespace capmoe {
@@ -23,36 +24,35 @@ __device__ inline uint16_t bf16_rne_bits(float f) {
     return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
-// w [E,d] fp32 -> w3 [3,E,d] bf16 with w = w3[0] + w3[1] + w3[2]
-__global__ __launch_bounds__(256) void router_split_kernel(const float* __restrict__ w, uint16_t* __restrict__ w3,
-                                                           int count) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
-    const float v = w[i];
-    const uint16_t hi = bf16_rne_bits(v);
-    const float r1 = v - __uint_as_float((uint32_t)hi << 16);
-    const uint16_t mid = bf16_rne_bits(r1);
-    const float r2 = r1 - __uint_as_float((uint32_t)mid << 16);
-    const uint16_t lo = bf16_rne_bits(r2);
-    w3[i] = hi;
-    w3[(size_t)count + i] = mid;
-    w3[2 * (size_t)count + i] = lo;
-}
-
 constexpr int kRmTokens = 128;  // tokens per block
 constexpr int kRmSlab = 32;     // k per LDS stage
+
+// 8 fp32 router weights -> the three bf16 planes (w = hi + mid + lo exactly), 16 bytes each
+__device__ inline void split_planes(const float4& a, const float4& b, uint4& hi, uint4& mid, uint4& lo) {
+    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t h[8], m[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        h[i] = bf16_rne_bits(v[i]);
+        const float r1 = v[i] - __uint_as_float(h[i] << 16);
+        m[i] = bf16_rne_bits(r1);
+        const float r2 = r1 - __uint_as_float(m[i] << 16);
+        l[i] = bf16_rne_bits(r2);
+    }
+    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    mid = make_uint4(m[0] | (m[1] << 16), m[2] | (m[3] << 16), m[4] | (m[5] << 16), m[6] | (m[7] << 16));
+    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+}
 
 // TN = 32-expert tiles (E padded to 32*TN).  out: [ksplit, N, E] partial sums (or the logits
 // themselves, with the bias added, when there is a single slice).
 template <int TN>
-__global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __restrict__ x,
-                                                          const uint16_t* __restrict__ w3,
+__global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __restrict__ x, const float* __restrict__ w,
                                                           const float* __restrict__ bias, float* __restrict__ out,
                                                           int N, int d, int E, int k_per_slice, int add_bias) {
-    constexpr int EP = 32 * TN;          // padded expert count
-    constexpr int ROWS = 3 * EP;         // plane rows of a stage, 64 bytes each
-    constexpr int GROUPS = ROWS / 16;    // 1 KB row groups (one wave-wide load each)
-    constexpr int STAGE_BYTES = ROWS * 64;
+    constexpr int EP = 32 * TN;                  // padded expert count
+    constexpr int STAGE_BYTES = 3 * EP * 64;     // three planes of EP rows, 32 bf16 (64 bytes) each
+    constexpr int NP = (EP * 4 + 255) / 256;     // 16-byte pieces of a plane that a thread stages
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -66,28 +66,38 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
     const int tr = t0 + lr < N ? t0 + lr : N - 1;
     const uint16_t* xrow = x + (size_t)tr * d + k_begin + lk * 8;
 
-    // sources of the weight pieces this lane stages: group g covers rows 16g..16g+15
-    constexpr int LOADS = (GROUPS + 3) / 4;
-    const uint16_t* src[LOADS];
+    // weight pieces this thread stages: piece p = row p/4 (expert), 8 consecutive k at (p%4)*8
+    const float* wsrc[NP];
+    int wdst[NP];
+    bool wlive[NP];
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int g = wv + 4 * i;
-        const int R = g * 16 + (lane >> 2);
-        const int kc = (lane & 3) ^ ((R >> 2) & 3);
-        const int plane = R / EP;
-        int e = R - plane * EP;
-        e = e < E ? e : E - 1;  // padding rows repeat the last expert; their outputs are not stored
-        src[i] = w3 + ((size_t)(plane < 3 ? plane : 2) * E + e) * d + k_begin + kc * 8;
+    for (int i = 0; i < NP; ++i) {
+        const int p = tid + 256 * i;
+        const int e = p >> 2, kc = p & 3;
+        wlive[i] = p < EP * 4;
+        wsrc[i] = w + (size_t)(e < E ? e : E - 1) * d + k_begin + kc * 8;  // padding rows repeat the last expert
+        wdst[i] = e * 64 + ((kc ^ ((e >> 2) & 3)) << 4);                   // EP is a multiple of 4: same swizzle per plane
     }
-    auto fill = [&](int slab) {
+    float4 wreg[NP][2];
+    auto load_w = [&](int slab) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+            if (wlive[i]) {
+                wreg[i][0] = *(const float4*)(wsrc[i] + slab * kRmSlab);
+                wreg[i][1] = *(const float4*)(wsrc[i] + slab * kRmSlab + 4);
+            }
+    };
+    auto store_w = [&](int slab) {
         uint8_t* dst = smem + (slab & 1) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int g = wv + 4 * i;
-            if (g < GROUPS)
-                __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)slab * kRmSlab), (lptr_t)(dst + g * 1024), 16,
-                                                 0, 0);
-        }
+        for (int i = 0; i < NP; ++i)
+            if (wlive[i]) {
+                uint4 hi, mid, lo;
+                split_planes(wreg[i][0], wreg[i][1], hi, mid, lo);
+                *(uint4*)(dst + wdst[i]) = hi;
+                *(uint4*)(dst + EP * 64 + wdst[i]) = mid;
+                *(uint4*)(dst + 2 * EP * 64 + wdst[i]) = lo;
+            }
     };
 
     f32x16 acc[TN];
@@ -96,25 +106,25 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-    // LDS offsets of this lane's weight pieces for k-step 0 (piece lk) and 1 (piece 2 + lk)
+    // LDS offsets of this lane's weight pieces for k-step 0 (piece lk); k-step 1 flips piece bit 1
     int w_off[3][TN];
 #pragma unroll
     for (int p = 0; p < 3; ++p)
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
-            const int R = p * EP + i * 32 + lr;
-            w_off[p][i] = R * 64 + ((lk ^ ((R >> 2) & 3)) << 4);
+            const int R = i * 32 + lr;
+            w_off[p][i] = p * EP * 64 + R * 64 + ((lk ^ ((R >> 2) & 3)) << 4);
         }
 
-    fill(0);
+    load_w(0);
     bf16x8 xa[2], xn[2];
     xa[0] = *(const bf16x8*)(xrow);
     xa[1] = *(const bf16x8*)(xrow + 16);
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+    store_w(0);
     __syncthreads();
     for (int s = 0; s < n_slabs; ++s) {
         if (s + 1 < n_slabs) {
-            fill(s + 1);
+            load_w(s + 1);
             xn[0] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab);
             xn[1] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab + 16);
         }
@@ -131,7 +141,7 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
                 }
             }
         }
-        __builtin_amdgcn_s_waitcnt(0x0f70);
+        if (s + 1 < n_slabs) store_w(s + 1);  // the other stage: last read before the previous barrier
         __syncthreads();
         xa[0] = xn[0];
         xa[1] = xn[1];
@@ -157,7 +167,6 @@ RouteWorkspace route_workspace(const moe_desc_t& d, void* base) {
     RouteWorkspace w;
     w.use_mfma = d.dtype == MOE_DTYPE_BF16 && d.d_model % 32 == 0 && d.n_tokens > 0;
     w.ksplit = 1;
-    w.w3 = nullptr;
     w.partial = nullptr;
     w.bytes = 0;
     if (!w.use_mfma) return w;
@@ -170,8 +179,6 @@ RouteWorkspace route_workspace(const moe_desc_t& d, void* base) {
     w.ksplit = ks;
     char* p = (char*)base;
     size_t off = 0;
-    w.w3 = (uint16_t*)(p + off);
-    off += align256((size_t)3 * d.n_experts * d.d_model * 2);
     if (ks > 1) {
         w.partial = (float*)(p + off);
         off += align256((size_t)ks * d.n_tokens * d.n_experts * 4);
@@ -181,8 +188,9 @@ RouteWorkspace route_workspace(const moe_desc_t& d, void* base) {
 }
 
 template <int TN>
-static void launch_rm(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* bias, float* out,
-                      hipStream_t st) {
+static void launch_rm(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* w, const float* bias,
+                      float* out, hipStream_t st) {
+    (void)ws;
     const size_t lds = (size_t)2 * 3 * 32 * TN * 64;
     auto kern = router_mfma_kernel<TN>;
     static bool configured = false;
@@ -191,7 +199,7 @@ static void launch_rm(const moe_desc_t& d, const RouteWorkspace& ws, const void*
         configured = true;
     }
     const dim3 grid((d.n_tokens + kRmTokens - 1) / kRmTokens, ws.ksplit);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const uint16_t*)x, ws.w3, bias, out, d.n_tokens, d.d_model,
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const uint16_t*)x, w, bias, out, d.n_tokens, d.d_model,
                        d.n_experts, d.d_model / ws.ksplit, ws.ksplit == 1 ? 1 : 0);
 }
 
@@ -199,19 +207,17 @@ static void launch_rm(const moe_desc_t& d, const RouteWorkspace& ws, const void*
 hipError_t launch_router_mfma(const moe_desc_t& d, const RouteWorkspace& ws, const void* x, const float* w,
                               const float* bias, float* logits, hipStream_t st) {
     ProfileScope prof(MOE_KERNEL_ROUTER_LOGITS, st);
-    const int count = d.n_experts * d.d_model;
-    hipLaunchKernelGGL(router_split_kernel, dim3((count + 255) / 256), dim3(256), 0, st, w, ws.w3, count);
     float* out = ws.ksplit == 1 ? logits : ws.partial;
     const int tn = (d.n_experts + 31) / 32;
     switch (tn) {
-        case 1: launch_rm<1>(d, ws, x, bias, out, st); break;
-        case 2: launch_rm<2>(d, ws, x, bias, out, st); break;
-        case 3: launch_rm<3>(d, ws, x, bias, out, st); break;
-        case 4: launch_rm<4>(d, ws, x, bias, out, st); break;
-        case 5: launch_rm<5>(d, ws, x, bias, out, st); break;
-        case 6: launch_rm<6>(d, ws, x, bias, out, st); break;
-        case 7: launch_rm<7>(d, ws, x, bias, out, st); break;
-        default: launch_rm<8>(d, ws, x, bias, out, st); break;
+        case 1: launch_rm<1>(d, ws, x, w, bias, out, st); break;
+        case 2: launch_rm<2>(d, ws, x, w, bias, out, st); break;
+        case 3: launch_rm<3>(d, ws, x, w, bias, out, st); break;
+        case 4: launch_rm<4>(d, ws, x, w, bias, out, st); break;
+        case 5: launch_rm<5>(d, ws, x, w, bias, out, st); break;
+        case 6: launch_rm<6>(d, ws, x, w, bias, out, st); break;
+        case 7: launch_rm<7>(d, ws, x, w, bias, out, st); break;
+        default: launch_rm<8>(d, ws, x, w, bias, out, st); break;
     }
     return hipGetLastError();
 }

@@ -24,7 +24,8 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = capmoe.load()
     names = declared_functions()
-    assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_combine", "moe_query",
+    assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_dispatch_ffn", "moe_combine",
+            "moe_query", "moe_profile_attach",
             "moe_status_string"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
@@ -88,5 +89,6 @@ def test_bad_arguments_are_refused_on_the_host():
     assert lib.moe_capacity_drop(ctypes.byref(ok), z, z, z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_dispatch(ctypes.byref(ok), z, z, z, z, z) == 1
     assert lib.moe_grouped_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, 0, z) == 1
+    assert lib.moe_dispatch_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_combine(ctypes.byref(ok), z, z, z, z, z) == 1
     assert lib.moe_query(None, None, None, None, None) == 1

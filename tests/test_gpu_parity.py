@@ -210,6 +210,12 @@ def check_layer(orc, layer, mode, scope, gamma, tokens=None, what=""):
         y = y[tokens]
     assert np.all(np.isfinite(to_host_f64(buf.y)))
     assert_output_close(y, y_ref, TOL[w.dtype], what)
+    # dispatch fused into the first GEMM (moe_dispatch_ffn): same bits as the two separate calls
+    fused = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(fused, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         torch.from_numpy(logits).cuda(), fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.yp[:rows], buf.yp[:rows]) and torch.equal(fused.y, buf.y)
     return buf, ref
 
 
