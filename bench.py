@@ -24,6 +24,10 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 matrix peak
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
+# HBM bytes per launch of the gate/up GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# 1 GiB device copy (profiles/olmoe_token_drop_gamma1_layer.md); keyed by (workload, mode, scope, gamma)
+MEASURED_TRAFFIC = {("olmoe", "token", "local", 1.0): 716.7e6 + 32.5e6}
+
 MODES = {"none": 0, "token": 1, "expanded": 2}
 SCOPES = {"local": 0, "global": 1}
 
@@ -40,6 +44,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--unfused", action="store_true",
                    help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
+    p.add_argument("--calibration-copy", action="store_true",
+                   help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
     p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none",
                    help="comma list of workload:mode measured after the main line ('' for none)")
     return p.parse_args()
@@ -222,7 +228,8 @@ def main():
     mode, scope = MODES[a.mode], SCOPES[a.scope]
     r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused)
     primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
-    primary["kernel"] = other["kernel"] = "grouped_gemm_bf16_kernel<SWIGLU> (gate/up GEMM + SwiGLU)"
+    primary["kernel"] = other["kernel"] = "ffn_gemm_bf16_kernel<..., SWIGLU> (gate/up GEMM + SwiGLU epilogue)"
+    primary["traffic"] = other["traffic"] = MEASURED_TRAFFIC.get((a.workload, a.mode, a.scope, a.gamma))
     stages = {}
     km = r["kernel_ms"]
     drop_ms = km["drop_prepare"] + km["drop_select"] + km["drop_emit"]
@@ -268,6 +275,13 @@ def main():
                        "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
     if others:
         out["other_workloads"] = others
+    if a.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = 1 << 30
     print(json.dumps(out))
 
 
