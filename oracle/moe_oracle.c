@@ -17,7 +17,9 @@
  *     to the lower token index, and exactly `cap` candidates are kept,
  *   - rows of the dispatch plan are expert-major, ascending token inside an expert,
  *   - token t lives on simulated device t / (N/G), which hosts experts
- *     [b*E/G, (b+1)*E/G).
+ *     [b*E/G, (b+1)*E/G),
+ *   - the generator behind the Random metric (orc_pair_hash) and the encoding of the
+ *     multimodal strategies as a class per token.
  *
  * All matrices are row-major host arrays.
  */
@@ -162,28 +164,58 @@ void orc_candidates(const int32_t* topk_idx, int N, int E, int k, int G, int mod
 }
 
 /* ---------------------------------------------------------------------------
- * Score-ranked drop, Eqs. (8)-(10) (threshold tau, kept set T_J, mask M_J) and the
+ * Ranked drop, Eqs. (8)-(10) (threshold tau, kept set T_J, mask M_J) and the
  * column-wise topk(cap) of Alg. 1 / Alg. 2.
  *
  * A capacity segment is one expert over the tokens the constraint ranges over:
  * scope GLOBAL - all N tokens; scope LOCAL - the N/G tokens of one device (Sec. 3:
  * constraints are applied to the tokens within each local device).  In every segment
- * the candidates are sorted by (score descending, token ascending) and the first
- * `cap` are kept.  Mode NONE keeps every candidate.
+ * the candidates are sorted by importance and the first `cap` are kept.  Mode NONE
+ * keeps every candidate.
+ *
+ * Importance of a candidate (token t, expert e), Sec. 3 "metrics":
+ *   SCORE          its gating score s[t,e] (higher is kept first)
+ *   ORDER          earlier tokens are kept first (later ones are discarded once the
+ *                  capacity is filled)
+ *   REVERSE_ORDER  later tokens are kept first
+ *   RANDOM         an independent uniform draw per pair: the 30 high bits of a 32-bit
+ *                  integer hash of (seed, t*E + e) - a counter-based generator, so that
+ *                  any implementation draws the same numbers
+ * Multimodal strategies (Sec. "Extension to Multimodal Mixture of Experts": "Image First",
+ * "Text First", "Uniform"): an optional
+ * class per token (0..3) ranks before the metric - a candidate of a lower class is
+ * dropped before any candidate of a higher class.  Image First = image tokens class 0,
+ * text tokens class 1; Uniform = no classes.
+ * Equal importance goes to the lower token index.
  * keep is a dense [N,E] 0/1 matrix.  Returns the number of kept pairs.
  * ------------------------------------------------------------------------- */
-typedef struct { float score; int32_t token; } orc_cand_t;
+enum { ORC_METRIC_SCORE = 0, ORC_METRIC_ORDER = 1, ORC_METRIC_REVERSE_ORDER = 2, ORC_METRIC_RANDOM = 3 };
+
+/* 32-bit integer hash (two multiply-xorshift rounds); the counter is offset by the seed */
+uint32_t orc_pair_hash(uint32_t seed, uint32_t counter) {
+    uint32_t x = counter + seed * 0x9E3779B9u;
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+typedef struct { int cls; double value; int32_t token; } orc_cand_t;
 
 static int orc_cand_cmp(const void* a, const void* b) {
     const orc_cand_t* p = (const orc_cand_t*)a;
     const orc_cand_t* q = (const orc_cand_t*)b;
-    if (p->score > q->score) return -1;
-    if (p->score < q->score) return 1;
+    if (p->cls != q->cls) return p->cls > q->cls ? -1 : 1;
+    if (p->value > q->value) return -1;
+    if (p->value < q->value) return 1;
     return (p->token > q->token) - (p->token < q->token);
 }
 
 int64_t orc_capacity_drop(const float* scores, const uint8_t* cand, int N, int E, int k, int G, int mode,
-                          int scope, double gamma, uint8_t* keep) {
+                          int scope, double gamma, int metric, const uint8_t* token_class, uint32_t seed,
+                          uint8_t* keep) {
     const int n_blocks = (scope == ORC_SCOPE_LOCAL) ? G : 1;
     const int seg_tokens = N / n_blocks;
     const int cap = (mode == ORC_MODE_NONE) ? seg_tokens : orc_capacity(gamma, seg_tokens, k, E);
@@ -194,11 +226,18 @@ int64_t orc_capacity_drop(const float* scores, const uint8_t* cand, int N, int E
         for (int e = 0; e < E; ++e) {
             int n = 0;
             for (int t = b * seg_tokens; t < (b + 1) * seg_tokens; ++t) {
-                if (cand[(size_t)t * E + e]) {
-                    list[n].score = scores[(size_t)t * E + e];
-                    list[n].token = t;
-                    ++n;
+                if (!cand[(size_t)t * E + e]) continue;
+                list[n].cls = token_class ? (token_class[t] & 3) : 0;
+                list[n].token = t;
+                switch (metric) {
+                    case ORC_METRIC_ORDER: list[n].value = -(double)t; break;
+                    case ORC_METRIC_REVERSE_ORDER: list[n].value = (double)t; break;
+                    case ORC_METRIC_RANDOM:
+                        list[n].value = (double)(orc_pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2);
+                        break;
+                    default: list[n].value = (double)scores[(size_t)t * E + e]; break;
                 }
+                ++n;
             }
             qsort(list, (size_t)n, sizeof(orc_cand_t), orc_cand_cmp);
             const int n_keep = n < cap ? n : cap;

@@ -49,7 +49,9 @@ def _load():
         lib.orc_capacity.restype = i32
         lib.orc_candidates.argtypes = [vp, i32, i32, i32, i32, i32, vp]
         lib.orc_candidates.restype = None
-        lib.orc_capacity_drop.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp]
+        lib.orc_capacity_drop.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, dbl, i32, vp, ctypes.c_uint32, vp]
+        lib.orc_pair_hash.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
+        lib.orc_pair_hash.restype = ctypes.c_uint32
         lib.orc_capacity_drop.restype = i64
         lib.orc_build_plan.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.orc_build_plan.restype = i64
@@ -113,12 +115,22 @@ def candidates(topk_idx, n_experts, device_groups, mode):
     return cand
 
 
-def capacity_drop(scores, cand, k, device_groups, mode, scope, gamma):
+METRIC_SCORE, METRIC_ORDER, METRIC_REVERSE_ORDER, METRIC_RANDOM = 0, 1, 2, 3
+
+
+def pair_hash(seed, counter) -> int:
+    return int(_load().orc_pair_hash(seed & 0xFFFFFFFF, counter & 0xFFFFFFFF))
+
+
+def capacity_drop(scores, cand, k, device_groups, mode, scope, gamma, metric=METRIC_SCORE, token_class=None, seed=0):
     s, c = _c(scores, np.float32), _c(cand, np.uint8)
     n, e = s.shape
     assert c.shape == (n, e) and n % device_groups == 0
     keep = np.empty((n, e), np.uint8)
-    kept = _load().orc_capacity_drop(_p(s), _p(c), n, e, k, device_groups, mode, scope, float(gamma), _p(keep))
+    tc = _c(token_class, np.uint8) if token_class is not None else None
+    assert tc is None or tc.shape == (n,)
+    kept = _load().orc_capacity_drop(_p(s), _p(c), n, e, k, device_groups, mode, scope, float(gamma), metric,
+                                     _p(tc) if tc is not None else None, seed & 0xFFFFFFFF, _p(keep))
     assert kept == int(keep.sum())
     return keep
 
@@ -151,13 +163,13 @@ def build_plan(scores, cand, keep, slots, n_blocks) -> Plan:
                 row_token=row_token[:p_max], row_weight=row_weight[:p_max], pair_row=pair_row)
 
 
-def route_and_drop(logits, k, device_groups, mode, scope, gamma):
+def route_and_drop(logits, k, device_groups, mode, scope, gamma, metric=METRIC_SCORE, token_class=None, seed=0):
     """softmax -> top-k -> candidates -> drop -> plan, from given fp32 logits."""
     scores = softmax_scores(logits)
     topk_idx, topk_score = topk(scores, k)
     n, e = scores.shape
     cand = candidates(topk_idx, e, device_groups, mode)
-    keep = capacity_drop(scores, cand, k, device_groups, mode, scope, gamma)
+    keep = capacity_drop(scores, cand, k, device_groups, mode, scope, gamma, metric, token_class, seed)
     n_blocks = device_groups if scope == SCOPE_LOCAL else 1
     plan = build_plan(scores, cand, keep, slots_per_token(k, e, device_groups, mode), n_blocks)
     seg_tokens = n // n_blocks

@@ -361,6 +361,112 @@ def test_score_metric_is_permutation_equivariant(orc):
 
 
 # ----------------------------------------------------------------------------
+# the other ranking metrics of Sec. 3 (Order, Reverse Order, Random) and the multimodal strategies
+# ----------------------------------------------------------------------------
+def segments(n, e, scope, g):
+    blocks = g if scope == LOCAL else 1
+    ns = n // blocks
+    for b in range(blocks):
+        for j in range(e):
+            yield np.arange(b * ns, (b + 1) * ns), j
+
+
+@pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (TD, LOCAL, 4), (ED, LOCAL, 4)])
+def test_order_and_reverse_order_metrics(orc, mode, scope, g):
+    n, e, k = 256, 8, 2
+    logits = small_logits(n, e, 21, 1.5)
+    first = orc.route_and_drop(logits, k, g, mode, scope, 1.0, metric=orc.METRIC_ORDER)
+    last = orc.route_and_drop(logits, k, g, mode, scope, 1.0, metric=orc.METRIC_REVERSE_ORDER)
+    overflowed = 0
+    for toks, j in segments(n, e, scope, g):
+        cand = toks[first.cand[toks, j] == 1]
+        # Order: the capacity is filled by the earliest tokens, later ones are discarded; Reverse Order: the latest stay
+        np.testing.assert_array_equal(toks[first.keep[toks, j] == 1], cand[:first.cap])
+        np.testing.assert_array_equal(toks[last.keep[toks, j] == 1], cand[max(0, len(cand) - last.cap):])
+        overflowed += len(cand) > first.cap
+    assert overflowed > 0
+    # unlike Score, Order depends on the position of a token in the batch (the paper calls it unstable)
+    perm = np.random.default_rng(22).permutation(n)
+    shuffled = orc.route_and_drop(logits[perm], k, 1, TD, GLOBAL, 1.0, metric=orc.METRIC_ORDER)
+    straight = orc.route_and_drop(logits, k, 1, TD, GLOBAL, 1.0, metric=orc.METRIC_ORDER)
+    assert (shuffled.keep != straight.keep[perm]).any()
+    assert shuffled.keep.sum() == straight.keep.sum()
+    # the combine weights stay the gating scores whatever ranks the tokens
+    tt, ee = np.nonzero(first.keep.T)[1], np.nonzero(first.keep.T)[0]
+    np.testing.assert_array_equal(first.plan.row_weight, first.scores[tt, ee])
+
+
+def py_pair_hash(seed, counter):
+    x = (counter + seed * 0x9E3779B9) & 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & 0xFFFFFFFF
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def test_random_metric(orc):
+    n, e, k, g = 512, 8, 2, 2
+    logits = small_logits(n, e, 23, 1.5)
+    a = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.5, metric=orc.METRIC_RANDOM, seed=7)
+    b = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.5, metric=orc.METRIC_RANDOM, seed=8)
+    assert (a.keep != b.keep).any() and a.keep.sum() == b.keep.sum()
+    for toks, j in segments(n, e, LOCAL, g):
+        cand = toks[a.cand[toks, j] == 1]
+        kept = toks[a.keep[toks, j] == 1]
+        assert len(kept) == min(len(cand), a.cap)
+        # brute force: the cap largest draws (ties to the lower token) among the candidates
+        draws = np.array([py_pair_hash(7, int(t) * e + j) >> 2 for t in cand])
+        order = np.lexsort((cand, -draws))
+        np.testing.assert_array_equal(np.sort(cand[order[:a.cap]]), kept)
+    # every token has the same chance: the kept share does not depend on position or score
+    big = orc.route_and_drop(small_logits(4096, 4, 24, 0.0), 2, 1, TD, GLOBAL, 0.5, metric=orc.METRIC_RANDOM, seed=1)
+    share = big.keep.sum(1).reshape(8, 512).sum(1) / big.cand.sum(1).reshape(8, 512).sum(1)
+    assert np.all(np.abs(share - share.mean()) < 0.06)
+    hi_score = big.scores > np.median(big.scores[big.cand == 1])
+    kept_hi = big.keep[(big.cand == 1) & hi_score].mean()
+    kept_lo = big.keep[(big.cand == 1) & ~hi_score].mean()
+    assert abs(kept_hi - kept_lo) < 0.05
+    # the generator is uniform on 32 bits (16 equal buckets over 2^16 consecutive counters)
+    draws = np.array([orc.pair_hash(3, c) for c in range(1 << 16)], dtype=np.uint64)
+    counts = np.bincount((draws >> 28).astype(np.int64), minlength=16)
+    assert np.all(np.abs(counts - 4096) < 5 * 64) and len(np.unique(draws)) > 65000
+    assert [orc.pair_hash(9, c) for c in (0, 1, 12345)] == [py_pair_hash(9, c) for c in (0, 1, 12345)]
+
+
+def test_modality_strategies(orc):
+    n, e, k, g = 384, 8, 2, 2
+    logits = small_logits(n, e, 25, 1.5)
+    image = (np.random.default_rng(26).random(n) < 0.7)
+    image_first = np.where(image, 0, 1).astype(np.uint8)   # image tokens are dropped before any text token
+    text_first = np.where(image, 1, 0).astype(np.uint8)
+    uniform = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.6)
+    same = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.6, token_class=np.full(n, 2, np.uint8))
+    np.testing.assert_array_equal(uniform.keep, same.keep)               # one class = no classes ("Uniform")
+    for cls, dropped_first in ((image_first, image), (text_first, ~image)):
+        r = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.6, token_class=cls)
+        np.testing.assert_array_equal(r.keep.sum(0), uniform.keep.sum(0))  # the loads do not change, only who stays
+        split = 0
+        for toks, j in segments(n, e, LOCAL, g):
+            cand = toks[r.cand[toks, j] == 1]
+            kept = toks[r.keep[toks, j] == 1]
+            dropped = np.setdiff1d(cand, kept)
+            low_kept, high_dropped = kept[dropped_first[kept]], dropped[~dropped_first[dropped]]
+            assert len(low_kept) == 0 or len(high_dropped) == 0      # never keep a low class over a higher one
+            for group in (dropped_first, ~dropped_first):              # inside a class: by score
+                kk, dd = kept[group[kept]], dropped[group[dropped]]
+                if len(kk) and len(dd):
+                    assert r.scores[kk, j].min() >= r.scores[dd, j].max()
+            split += len(dropped) > 0
+        assert split > 0
+        assert (r.keep != uniform.keep).any()
+    # image tokens are the first to go: fewer of them survive than under the uniform strategy
+    r = orc.route_and_drop(logits, k, g, TD, LOCAL, 0.6, token_class=image_first)
+    assert r.keep[image].sum() < uniform.keep[image].sum() and r.keep[~image].sum() > uniform.keep[~image].sum()
+
+
+# ----------------------------------------------------------------------------
 # dispatch plan
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (ED, LOCAL, 4), (ED, GLOBAL, 4), (NONE, LOCAL, 2)])
