@@ -44,6 +44,8 @@ typedef enum {
 enum { MOE_MODE_NONE = 0, MOE_MODE_TOKEN_DROP = 1, MOE_MODE_EXPANDED_DROP = 2 };
 enum { MOE_SCOPE_LOCAL = 0, MOE_SCOPE_GLOBAL = 1 };
 enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+/* What ranks the candidates of an overflowed expert (Sec. 3, list of metrics) */
+enum { MOE_METRIC_SCORE = 0, MOE_METRIC_ORDER = 1, MOE_METRIC_REVERSE_ORDER = 2, MOE_METRIC_RANDOM = 3 };
 
 /* Shape and policy of one layer call (host memory, plain data). */
 typedef struct {
@@ -60,7 +62,9 @@ typedef struct {
     double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 3)                           */
     int32_t dtype;          /* MOE_DTYPE_*: type of x, expert weights, xp, yp, y.  The router
                                (logits, softmax, scores) is always fp32.                             */
-    int32_t reserved;       /* set to 0                                                              */
+    int32_t metric;         /* MOE_METRIC_*: SCORE keeps the highest gating scores (the paper's choice),
+                               ORDER the earliest tokens, REVERSE_ORDER the latest, RANDOM a uniform
+                               draw per pair; 0 = SCORE                                              */
 } moe_desc_t;
 
 const char* moe_status_string(int status);
@@ -98,7 +102,8 @@ int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router,
  * Capacity enforcement: Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop (Alg. 2), or none.
  * Candidates of token t: its top-k experts; Expanded Drop adds the E/G experts of the token's own
  * device.  In every capacity segment (expert, or device-block x expert for LOCAL scope) the `cap`
- * candidates with the highest score are kept; equal scores go to the lower token index.
+ * candidates that rank highest under desc->metric (the gating score by default) are kept; equal rank
+ * goes to the lower token index.
  * Outputs (the dispatch plan; B = G for LOCAL scope, 1 for GLOBAL):
  *   expert_count  [E]     kept pairs per expert
  *   seg_count     [B,E]   kept pairs per (device block, expert)
@@ -113,6 +118,23 @@ int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t
                       int32_t* expert_count, int32_t* seg_count, int32_t* expert_offset, int32_t* row_token,
                       float* row_weight, int32_t* pair_row, void* workspace, size_t workspace_bytes,
                       void* stream);
+
+/*
+ * moe_capacity_drop with the two optional inputs of the other drop policies:
+ *   token_class [N] uint8 or NULL  the multimodal strategies (Sec. "Extension to Multimodal Mixture of
+ *              Experts"): a candidate of a lower class (0..3) is dropped before any candidate of a
+ *              higher class, whatever the metric says; "Image First" = image tokens 0, text tokens 1;
+ *              NULL = "Uniform" (one class).
+ *   seed       MOE_METRIC_RANDOM draws, for the pair (t, e), the 30 high bits of a 32-bit integer hash
+ *              of the counter t*E + e offset by seed * 0x9E3779B9 (x ^= x>>16; x *= 0x7FEB352D;
+ *              x ^= x>>15; x *= 0x846CA68B; x ^= x>>16): a counter-based generator, reproducible
+ *              anywhere.  Ignored by the other metrics.
+ * Equal rank goes to the lower token index.  row_weight is the gating score whatever ranks the tokens.
+ */
+int moe_capacity_drop_ranked(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,
+                             const uint8_t* token_class, uint32_t seed, int32_t* expert_count, int32_t* seg_count,
+                             int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
+                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Permutation (the "permutation" stage of the latency breakdown, Sec. 5.1):

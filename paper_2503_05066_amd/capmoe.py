@@ -17,6 +17,7 @@ MOE_OK = 0
 MODE_NONE, MODE_TOKEN_DROP, MODE_EXPANDED_DROP = 0, 1, 2
 SCOPE_LOCAL, SCOPE_GLOBAL = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
+METRIC_SCORE, METRIC_ORDER, METRIC_REVERSE_ORDER, METRIC_RANDOM = 0, 1, 2, 3
 
 
 class MoeDesc(ctypes.Structure):
@@ -26,7 +27,7 @@ class MoeDesc(ctypes.Structure):
         ("n_tokens", ctypes.c_int32), ("d_model", ctypes.c_int32), ("n_experts", ctypes.c_int32),
         ("top_k", ctypes.c_int32), ("d_hidden", ctypes.c_int32), ("device_groups", ctypes.c_int32),
         ("mode", ctypes.c_int32), ("capacity_scope", ctypes.c_int32), ("gamma", ctypes.c_double),
-        ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("metric", ctypes.c_int32),
     ]
 
 
@@ -55,13 +56,15 @@ def load():
                                   ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
         lib.moe_route_topk.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_capacity_drop.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_capacity_drop_ranked.argtypes = [dp, vp, vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_profile_attach.argtypes = [i32, vp, vp]
         lib.moe_profile_attach.restype = i32
-        for f in ("moe_query", "moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn",
+        for f in ("moe_query", "moe_route_topk", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
+                  "moe_grouped_ffn",
                   "moe_dispatch_ffn", "moe_combine"):
             getattr(lib, f).restype = i32
         _lib = lib
@@ -73,9 +76,9 @@ def status_string(status: int) -> str:
 
 
 def make_desc(n_tokens, d_model, n_experts, top_k, d_hidden, device_groups=1, mode=MODE_TOKEN_DROP,
-              capacity_scope=SCOPE_LOCAL, gamma=1.0, dtype=DTYPE_BF16) -> MoeDesc:
+              capacity_scope=SCOPE_LOCAL, gamma=1.0, dtype=DTYPE_BF16, metric=METRIC_SCORE) -> MoeDesc:
     return MoeDesc(n_tokens, d_model, n_experts, top_k, d_hidden, device_groups, mode, capacity_scope,
-                   float(gamma), dtype, 0)
+                   float(gamma), dtype, metric)
 
 
 def _ptr(t):
@@ -118,6 +121,15 @@ def moe_capacity_drop(desc, scores, topk_idx, expert_count, seg_count, expert_of
                                     _ptr(seg_count), _ptr(expert_offset), _ptr(row_token), _ptr(row_weight),
                                     _ptr(pair_row), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                     _stream(stream)), "moe_capacity_drop")
+
+
+def moe_capacity_drop_ranked(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
+                             row_token, row_weight, pair_row, workspace, stream=None):
+    _check(load().moe_capacity_drop_ranked(ctypes.byref(desc), _ptr(scores), _ptr(topk_idx), _ptr(token_class),
+                                           int(seed) & 0xFFFFFFFF, _ptr(expert_count), _ptr(seg_count),
+                                           _ptr(expert_offset), _ptr(row_token), _ptr(row_weight), _ptr(pair_row),
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                           _stream(stream)), "moe_capacity_drop_ranked")
 
 
 def moe_dispatch(desc, x, expert_offset, row_token, xp, stream=None):
@@ -183,7 +195,7 @@ class LayerBuffers:
 
 
 def layer_forward(buf: LayerBuffers, x, w_router, bias, w_gate, w_up, w_down, given_logits=None, stream=None,
-                  fused_dispatch=False):
+                  fused_dispatch=False, token_class=None, seed=0):
     """The calls of one layer, enqueued back to back on one stream; returns buf.y.
 
     fused_dispatch=False: the five calls route_topk, capacity_drop, dispatch, grouped_ffn, combine.
@@ -194,8 +206,12 @@ def layer_forward(buf: LayerBuffers, x, w_router, bias, w_gate, w_up, w_down, gi
         buf.logits.copy_(given_logits)
     moe_route_topk(d, x, w_router, bias, given_logits is not None, buf.logits, buf.scores, buf.topk_idx,
                    buf.topk_score, buf.workspace, stream)
-    moe_capacity_drop(d, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
-                      buf.row_token, buf.row_weight, buf.pair_row, buf.workspace, stream)
+    if token_class is None and seed == 0:
+        moe_capacity_drop(d, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
+                          buf.row_token, buf.row_weight, buf.pair_row, buf.workspace, stream)
+    else:
+        moe_capacity_drop_ranked(d, buf.scores, buf.topk_idx, token_class, seed, buf.expert_count, buf.seg_count,
+                                 buf.expert_offset, buf.row_token, buf.row_weight, buf.pair_row, buf.workspace, stream)
     if fused_dispatch:
         moe_dispatch_ffn(d, x, buf.expert_offset, buf.row_token, w_gate, w_up, w_down, buf.yp, buf.workspace, stream)
     else:

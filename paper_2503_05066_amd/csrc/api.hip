@@ -16,6 +16,7 @@ int validate(const moe_desc_t* d) {
     if (d->mode < MOE_MODE_NONE || d->mode > MOE_MODE_EXPANDED_DROP) return MOE_ERR_INVALID_ARG;
     if (d->capacity_scope != MOE_SCOPE_LOCAL && d->capacity_scope != MOE_SCOPE_GLOBAL) return MOE_ERR_INVALID_ARG;
     if (d->dtype != MOE_DTYPE_F32 && d->dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
+    if (d->metric < MOE_METRIC_SCORE || d->metric > MOE_METRIC_RANDOM) return MOE_ERR_INVALID_ARG;
     if (std::isnan(d->gamma) || d->gamma < 0.0) return MOE_ERR_INVALID_ARG;
     if (d->n_experts > kMaxExperts || d->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
     const int slots = d->top_k + (d->mode == MOE_MODE_EXPANDED_DROP ? d->n_experts / d->device_groups : 0);
@@ -187,9 +188,10 @@ int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router,
     return MOE_OK;
 }
 
-int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx, int32_t* expert_count,
-                      int32_t* seg_count, int32_t* expert_offset, int32_t* row_token, float* row_weight,
-                      int32_t* pair_row, void* workspace, size_t workspace_bytes, void* stream) {
+int moe_capacity_drop_ranked(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,
+                             const uint8_t* token_class, uint32_t seed, int32_t* expert_count, int32_t* seg_count,
+                             int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
+                             void* workspace, size_t workspace_bytes, void* stream) {
     const int v = validate(desc);
     if (v != MOE_OK) return v;
     if (!expert_count || !seg_count || !expert_offset || !workspace) return MOE_ERR_INVALID_ARG;
@@ -201,10 +203,17 @@ int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t
     const DropWorkspace ws = drop_workspace(*desc, s, workspace);
     if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
-    if (launch_capacity_drop(*desc, s, ws, scores, topk_idx, expert_count, seg_count, expert_offset, row_token,
-                             row_weight, pair_row, (hipStream_t)stream) != hipSuccess)
+    if (launch_capacity_drop(*desc, s, ws, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
+                             row_token, row_weight, pair_row, (hipStream_t)stream) != hipSuccess)
         return MOE_ERR_HIP;
     return MOE_OK;
+}
+
+int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx, int32_t* expert_count,
+                      int32_t* seg_count, int32_t* expert_offset, int32_t* row_token, float* row_weight,
+                      int32_t* pair_row, void* workspace, size_t workspace_bytes, void* stream) {
+    return moe_capacity_drop_ranked(desc, scores, topk_idx, nullptr, 0u, expert_count, seg_count, expert_offset,
+                                    row_token, row_weight, pair_row, workspace, workspace_bytes, stream);
 }
 
 int moe_dispatch(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,

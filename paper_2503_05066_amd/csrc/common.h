@@ -98,7 +98,8 @@ hipError_t launch_router_mfma(const moe_desc_t& d, const RouteWorkspace& ws, con
 hipError_t launch_softmax_topk(const moe_desc_t& d, float* logits, const float* partial, int ksplit, const float* bias,
                                float* scores, int32_t* topk_idx, float* topk_score, hipStream_t st);
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
-                                const int32_t* topk_idx, int32_t* expert_count, int32_t* seg_count,
+                                const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
+                                int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
                                 hipStream_t st);
 hipError_t launch_dispatch(const moe_desc_t& d, const Sizes& s, const void* x, const int32_t* expert_offset,

@@ -3,8 +3,10 @@
 // Three kernels, all integer work on score bit patterns (scores are >= +0, so the unsigned
 // order of the bits is the order of the values):
 //   1. drop_prepare   per token: candidate set (top-k, plus the experts of the token's own device
-//                     for Expanded Drop) -> key = score bits + 1 for candidates, 0 otherwise,
-//                     written expert-major so that a capacity segment is one contiguous run.
+//                     for Expanded Drop) -> key = rank + 1 for candidates, 0 otherwise, written
+//                     expert-major so that a capacity segment is one contiguous run.  The rank is
+//                     the score's bit pattern (Score metric), the token's position (Order, Reverse
+//                     Order) or a hashed draw (Random), below an optional 2-bit token class.
 //   2. drop_select    per segment: the cap-th largest key by a 4-pass radix select over LDS
 //                     histograms (the threshold tau of Eq. 8) and how many keys equal to it survive.
 //   3. drop_emit      per segment: ordered compaction of the survivors, which yields rows in
@@ -17,6 +19,18 @@ namespace capmoe {
 
 constexpr int kPrepTokens = 64;
 
+// The draw of MOE_METRIC_RANDOM: a 32-bit integer hash (two multiply-xorshift rounds) of the pair's
+// counter, offset by the seed; the header states the same formula.
+__device__ inline uint32_t pair_hash(uint32_t seed, uint32_t counter) {
+    uint32_t x = counter + seed * 0x9E3779B9u;
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
 // ---------------------------------------------------------------------------------------------
 // 1. candidate keys, transposed
 // ---------------------------------------------------------------------------------------------
@@ -24,7 +38,9 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
                                                            const int32_t* __restrict__ topk_idx,
                                                            uint32_t* __restrict__ key_t, uint8_t* __restrict__ slot_t,
                                                            int32_t* __restrict__ pair_row, int N, int E, int k, int S,
-                                                           int expanded, int group_tokens, int group_experts) {
+                                                           int expanded, int group_tokens, int group_experts,
+                                                           int metric, int seg_tokens,
+                                                           const uint8_t* __restrict__ token_class, uint32_t seed) {
     extern __shared__ uint32_t lds[];
     const int ld = E | 1;                                  // odd row pitch: conflict-free transposed reads
     uint32_t* key_s = lds;                                 // [64][ld] score bits, then keys
@@ -53,12 +69,24 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
         const int tl = wv * 16 + i, t = t0 + tl;
         if (tl >= nt) break;
         int base = 0;
+        const uint32_t cls = token_class ? (uint32_t)(token_class[t] & 3) << 30 : 0u;
+        const int local = t % seg_tokens;  // position inside the capacity segment
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
             const bool c = e < E && slot_s[tl * ld + e] != 0;
             const uint64_t mask = __ballot(c);
             if (e < E) {
-                key_s[tl * ld + e] = c ? key_s[tl * ld + e] + 1u : 0u;
+                // rank within the class, below 2^30: score bits (scores are in [0,1]), position, or a draw
+                uint32_t rank;
+                if (metric == MOE_METRIC_ORDER)
+                    rank = (uint32_t)(seg_tokens - 1 - local);
+                else if (metric == MOE_METRIC_REVERSE_ORDER)
+                    rank = (uint32_t)local;
+                else if (metric == MOE_METRIC_RANDOM)
+                    rank = pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2;
+                else
+                    rank = key_s[tl * ld + e];
+                key_s[tl * ld + e] = c ? cls + rank + 1u : 0u;
                 slot_s[tl * ld + e] = (uint8_t)(base + __popcll(mask & ((1ull << lane) - 1ull)));
             }
             base += __popcll(mask);
@@ -183,7 +211,8 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
 constexpr int kEmitRun = 16;                // consecutive tokens per thread
 constexpr int kEmitChunk = 256 * kEmitRun;  // tokens per pass of the block
 
-__global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restrict__ key_t,
+__global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict__ scores,
+                                                        const uint32_t* __restrict__ key_t,
                                                         const uint8_t* __restrict__ slot_t,
                                                         const uint32_t* __restrict__ seg_tau,
                                                         const int32_t* __restrict__ seg_need,
@@ -271,7 +300,7 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restri
             const bool keep = (keep_bits >> j) & 1u;
             if (keep) {
                 row_token[pos] = t;
-                row_weight[pos] = __uint_as_float(kx[j] - 1u);
+                row_weight[pos] = scores[(size_t)t * E + e];  // the gating score, whatever ranked the pair
             }
             pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
             pos += keep;
@@ -282,7 +311,8 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const uint32_t* __restri
 }
 
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
-                                const int32_t* topk_idx, int32_t* expert_count, int32_t* seg_count,
+                                const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
+                                int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
                                 hipStream_t st) {
     const int N = d.n_tokens, E = d.n_experts;
@@ -295,7 +325,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         ProfileScope prof(MOE_KERNEL_DROP_PREPARE, st);
         hipLaunchKernelGGL(drop_prepare_kernel, dim3(grid), dim3(256), lds, st, scores, topk_idx, ws.key_t, ws.slot_t,
                            pair_row, N, E, d.top_k, s.slots, d.mode == MOE_MODE_EXPANDED_DROP ? 1 : 0, s.group_tokens,
-                           s.group_experts);
+                           s.group_experts, d.metric, s.seg_tokens > 0 ? s.seg_tokens : 1, token_class, seed);
     }
     const int segs = s.n_blocks * E;
     {
@@ -312,7 +342,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     }
     {
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
-        hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, ws.key_t, ws.slot_t, ws.seg_tau,
+        hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
                            ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
                            s.n_blocks, s.seg_tokens, s.slots);
     }

@@ -75,6 +75,7 @@ def test_bad_arguments_are_refused_on_the_host():
         capmoe.make_desc(128, 64, 8, 2, 128, mode=7),
         capmoe.make_desc(128, 64, 8, 2, 128, dtype=5),
         capmoe.make_desc(128, 0, 8, 2, 128),
+        capmoe.make_desc(128, 64, 8, 2, 128, metric=4),
     ]
     for d in bad:
         with pytest.raises(capmoe.CapMoeError) as ei:
@@ -87,6 +88,7 @@ def test_bad_arguments_are_refused_on_the_host():
     z = ctypes.c_void_p(None)
     assert lib.moe_route_topk(ctypes.byref(ok), z, z, z, 0, z, z, z, z, z, 0, z) == 1
     assert lib.moe_capacity_drop(ctypes.byref(ok), z, z, z, z, z, z, z, z, z, 0, z) == 1
+    assert lib.moe_capacity_drop_ranked(ctypes.byref(ok), z, z, z, 0, z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_dispatch(ctypes.byref(ok), z, z, z, z, z) == 1
     assert lib.moe_grouped_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_dispatch_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, z, 0, z) == 1

@@ -26,24 +26,30 @@ def note(*a):
     print(*a, flush=True)
 
 
-def route_and_drop_gpu(desc, logits_host):
-    """moe_route_topk (given logits) + moe_capacity_drop; returns the buffers."""
+def route_and_drop_gpu(desc, logits_host, token_class=None, seed=0):
+    """moe_route_topk (given logits) + moe_capacity_drop[_ranked]; returns the buffers."""
     buf = capmoe.LayerBuffers(desc)
     if desc.n_tokens:
         buf.logits.copy_(torch.from_numpy(logits_host))
     capmoe.moe_route_topk(desc, None, None, None, 1, buf.logits, buf.scores, buf.topk_idx, buf.topk_score,
                           buf.workspace)
-    capmoe.moe_capacity_drop(desc, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
-                             buf.row_token, buf.row_weight, buf.pair_row, buf.workspace)
+    if token_class is None and seed == 0:
+        capmoe.moe_capacity_drop(desc, buf.scores, buf.topk_idx, buf.expert_count, buf.seg_count, buf.expert_offset,
+                                 buf.row_token, buf.row_weight, buf.pair_row, buf.workspace)
+    else:
+        tc = torch.from_numpy(token_class).cuda() if token_class is not None else None
+        capmoe.moe_capacity_drop_ranked(desc, buf.scores, buf.topk_idx, tc, seed, buf.expert_count, buf.seg_count,
+                                        buf.expert_offset, buf.row_token, buf.row_weight, buf.pair_row, buf.workspace)
     torch.cuda.synchronize()
     return buf
 
 
-def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what):
-    note("case", what, dict(n=n, e=e, k=k, g=g, mode=mode, scope=scope, gamma=gamma))
-    desc = capmoe.make_desc(n, 64, e, k, 128, g, mode, scope, gamma, synth.DTYPE_F32)
-    buf = route_and_drop_gpu(desc, logits)
-    ref = orc.route_and_drop(logits, k, g, mode, scope, gamma)
+def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what, metric=0, token_class=None, seed=0):
+    note("case", what, dict(n=n, e=e, k=k, g=g, mode=mode, scope=scope, gamma=gamma, metric=metric, seed=seed,
+                            classes=token_class is not None))
+    desc = capmoe.make_desc(n, 64, e, k, 128, g, mode, scope, gamma, synth.DTYPE_F32, metric)
+    buf = route_and_drop_gpu(desc, logits, token_class, seed)
+    ref = orc.route_and_drop(logits, k, g, mode, scope, gamma, metric, token_class, seed)
     assert buf.cap == ref.cap
     np.testing.assert_array_equal(buf.scores.cpu().numpy().view(np.uint32), ref.scores.view(np.uint32))
     np.testing.assert_array_equal(buf.topk_idx.cpu().numpy(), ref.topk_idx)
@@ -142,6 +148,36 @@ def test_plan_with_forced_ties(orc, mode, scope, g):
         dropped_scores = set(s[cd[:, j] & ~kp[:, j], j].tolist())
         partial += len(kept_scores & dropped_scores)
     assert partial > 0
+
+
+@pytest.mark.parametrize("name,mode,scope,gamma,metric,classes,seed", [
+    ("olmoe", TD, LOCAL, 1.0, 1, False, 0), ("olmoe", TD, LOCAL, 1.0, 2, False, 0), ("olmoe", TD, LOCAL, 1.5, 3, False, 11),
+    ("olmoe", TD, LOCAL, 0.5, 0, True, 0), ("olmoe", TD, LOCAL, 1.0, 3, True, 12),
+    ("finegrained", ED, LOCAL, 1.0, 1, False, 0), ("finegrained", ED, LOCAL, 1.0, 3, True, 13),
+    ("mixtral", ED, GLOBAL, 1.0, 2, True, 0), ("decode", ED, LOCAL, 1.0, 3, False, 14), ("tiny", TD, LOCAL, 1.0, 1, True, 0),
+])
+def test_plan_other_metrics_and_token_classes(orc, name, mode, scope, gamma, metric, classes, seed):
+    """Order / Reverse Order / Random (Sec. 3) and the multimodal class strategies, at full size."""
+    w = W[name]
+    if name not in _logit_cache:
+        _logit_cache[name] = oracle_logits(orc, w)
+    cls = None
+    if classes:   # about 70 % "image" tokens (class 0, dropped first), the rest "text" (class 1)
+        cls = (np.random.default_rng(w.seed(5)).random(w.n_tokens) >= 0.7).astype(np.uint8)
+    buf, ref = check_route_and_plan(orc, _logit_cache[name], w.n_tokens, w.n_experts, w.top_k, w.device_groups, mode,
+                                    scope, gamma, f"{name} metric {metric}", metric, cls, seed)
+    base = orc.route_and_drop(_logit_cache[name], w.top_k, w.device_groups, mode, scope, gamma)
+    np.testing.assert_array_equal(ref.plan.seg_count, base.plan.seg_count)   # loads depend on capacity only
+    if ref.cand.sum() > ref.keep.sum():
+        assert (ref.keep != base.keep).any()
+
+
+def test_random_metric_ties_and_seeds(orc):
+    n, e = 1024, 8
+    logits = np.zeros((n, e), np.float32)           # all scores equal: only the draws decide
+    a, _ = check_route_and_plan(orc, logits, n, e, 2, 1, TD, GLOBAL, 0.5, "random flat", 3, None, 1)
+    b, _ = check_route_and_plan(orc, logits, n, e, 2, 1, TD, GLOBAL, 0.5, "random flat", 3, None, 2)
+    assert not torch.equal(a.row_token, b.row_token)
 
 
 def test_peaked_logits_zero_scores(orc):
