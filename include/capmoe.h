@@ -3,8 +3,8 @@
  *
  * C ABI of the hot path of "Capacity-Aware Inference: Mitigating the Straggler Effect in
  * Mixture of Experts" (arXiv 2503.05066): router -> softmax -> top-k (Eq. 1), expert capacity
- * C = gamma * N_bar (Sec. 3), score-ranked Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop
- * (Sec. 3 "Expanded Drop", Alg. 2), permutation, expert FFNs and the weighted sum (Eq. 2).
+ * C = gamma * N_bar (Sec. 4), score-ranked Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop
+ * (Sec. 4 "Expanded Drop", Alg. 2), permutation, expert FFNs and the weighted sum (Eq. 2).
  *
  * Conventions shared by every call
  *   - All tensor pointers are DEVICE pointers (HIP global memory) unless marked "host".  The caller
@@ -44,7 +44,7 @@ typedef enum {
 enum { MOE_MODE_NONE = 0, MOE_MODE_TOKEN_DROP = 1, MOE_MODE_EXPANDED_DROP = 2 };
 enum { MOE_SCOPE_LOCAL = 0, MOE_SCOPE_GLOBAL = 1 };
 enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
-/* What ranks the candidates of an overflowed expert (Sec. 3, list of metrics) */
+/* What ranks the candidates of an overflowed expert (Sec. 4, list of metrics) */
 enum { MOE_METRIC_SCORE = 0, MOE_METRIC_ORDER = 1, MOE_METRIC_REVERSE_ORDER = 2, MOE_METRIC_RANDOM = 3 };
 
 /* Shape and policy of one layer call (host memory, plain data). */
@@ -57,9 +57,9 @@ typedef struct {
     int32_t device_groups;  /* G >= 1 simulated devices                                              */
     int32_t mode;           /* MOE_MODE_*: plain top-k, Token Drop (Alg. 1), Expanded Drop (Alg. 2)  */
     int32_t capacity_scope; /* MOE_SCOPE_LOCAL: capacity per (device's tokens, expert), with
-                               N/G tokens in the capacity formula (Sec. 3: constraints are applied
+                               N/G tokens in the capacity formula (Sec. 4: constraints are applied
                                within each local device).  MOE_SCOPE_GLOBAL: per expert over all N.  */
-    double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 3)                           */
+    double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 4)                           */
     int32_t dtype;          /* MOE_DTYPE_*: type of x, expert weights, xp, yp, y.  The router
                                (logits, softmax, scores) is always fp32.                             */
     int32_t metric;         /* MOE_METRIC_*: SCORE keeps the highest gating scores (the paper's choice),
@@ -72,8 +72,8 @@ const char* moe_status_string(int status);
 /*
  * Static sizes of a layer call (host-only, launches nothing).
  *   cap             capacity of one segment: min(Ns, trunc(gamma * (Ns*k) / E)), Ns = N (GLOBAL) or
- *                   N/G (LOCAL); Ns for MOE_MODE_NONE or gamma = +inf.  (Sec. 3; Alg. 1)
- *   slots_per_token S = k, or k + E/G for Expanded Drop (a token may keep up to k+m experts, Sec. 3)
+ *                   N/G (LOCAL); Ns for MOE_MODE_NONE or gamma = +inf.  (Sec. 4; Alg. 1)
+ *   slots_per_token S = k, or k + E/G for Expanded Drop (a token may keep up to k+m experts, Sec. 4)
  *   max_rows        P_max, an upper bound on surviving token-expert pairs: size xp, yp, row_token,
  *                   row_weight for this many rows
  *   workspace_bytes enough for any single call of this descriptor

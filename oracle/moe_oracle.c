@@ -32,7 +32,7 @@
 #endif
 
 enum { ORC_MODE_NONE = 0, ORC_MODE_TOKEN_DROP = 1, ORC_MODE_EXPANDED_DROP = 2 };
-enum { ORC_SCOPE_LOCAL = 0, ORC_SCOPE_GLOBAL = 1 };
+enum { ORC_SCOPE_LOCAL = 0, ORC_SCOPE_GLOBAL = 1, ORC_SCOPE_LOCAL_DEVICE = 2, ORC_SCOPE_GLOBAL_DEVICE = 3 };
 
 int orc_num_threads(void) {
 #ifdef _OPENMP
@@ -130,10 +130,10 @@ void orc_topk(const float* scores, int N, int E, int k, int32_t* topk_idx, float
 }
 
 /* ---------------------------------------------------------------------------
- * Expert capacity C = gamma * N_bar, N_bar = N*k/E (Sec. 2.1 and Sec. 3); as an
+ * Expert capacity C = gamma * N_bar, N_bar = N*k/E (Sec. 3.1 and Sec. 4); as an
  * integer it is evaluated as in Alg. 1: gamma times (N*k), divided by E, truncated.
  * `seg_tokens` is the number of tokens the constraint ranges over (all N, or the
- * N/G tokens of one device when capacity is enforced locally, Sec. 3).  The result is
+ * N/G tokens of one device when capacity is enforced locally, Sec. 4).  The result is
  * clamped to seg_tokens: an expert cannot hold more tokens than exist.
  * ------------------------------------------------------------------------- */
 int orc_capacity(double gamma, int seg_tokens, int k, int E) {
@@ -147,7 +147,7 @@ int orc_capacity(double gamma, int seg_tokens, int k, int E) {
 /* ---------------------------------------------------------------------------
  * Candidate set of every token.
  *   Token Drop (Alg. 1): the token's top-k experts.
- *   Expanded Drop (Alg. 2, Sec. 3 "Expanded Drop"): top-k plus all m = E/G experts
+ *   Expanded Drop (Alg. 2, Sec. 4 "Expanded Drop"): top-k plus all m = E/G experts
  *   hosted on the token's own device.  A set: an expert that is both counts once.
  * cand is a dense [N,E] 0/1 matrix.
  * ------------------------------------------------------------------------- */
@@ -168,12 +168,12 @@ void orc_candidates(const int32_t* topk_idx, int N, int E, int k, int G, int mod
  * column-wise topk(cap) of Alg. 1 / Alg. 2.
  *
  * A capacity segment is one expert over the tokens the constraint ranges over:
- * scope GLOBAL - all N tokens; scope LOCAL - the N/G tokens of one device (Sec. 3:
+ * scope GLOBAL - all N tokens; scope LOCAL - the N/G tokens of one device (Sec. 4:
  * constraints are applied to the tokens within each local device).  In every segment
  * the candidates are sorted by importance and the first `cap` are kept.  Mode NONE
  * keeps every candidate.
  *
- * Importance of a candidate (token t, expert e), Sec. 3 "metrics":
+ * Importance of a candidate (token t, expert e), Sec. 4 "metrics":
  *   SCORE          its gating score s[t,e] (higher is kept first)
  *   ORDER          earlier tokens are kept first (later ones are discarded once the
  *                  capacity is filled)
@@ -186,7 +186,14 @@ void orc_candidates(const int32_t* topk_idx, int N, int E, int k, int G, int mod
  * class per token (0..3) ranks before the metric - a candidate of a lower class is
  * dropped before any candidate of a higher class.  Image First = image tokens class 0,
  * text tokens class 1; Uniform = no classes.
- * Equal importance goes to the lower token index.
+ * Equal importance goes to the lower expert id (only relevant when several experts share a
+ * budget), then to the lower token index.
+ *
+ * Granularity (Sec. 5.2, "Advanced Variant: Device-Level Capacity-Aware Inference"): with a
+ * *_DEVICE scope the constraint bounds the aggregated load of the E/G experts of one device,
+ * N_1 + ... + N_nl <= n_l * gamma * N_bar, instead of each expert: all candidate pairs of
+ * the device's experts are ranked together and the best `budget` are kept.  (The paper gives
+ * the constraint, not the selection rule; ranking by the same metric is this build's reading.)
  * keep is a dense [N,E] 0/1 matrix.  Returns the number of kept pairs.
  * ------------------------------------------------------------------------- */
 enum { ORC_METRIC_SCORE = 0, ORC_METRIC_ORDER = 1, ORC_METRIC_REVERSE_ORDER = 2, ORC_METRIC_RANDOM = 3 };
@@ -202,7 +209,7 @@ uint32_t orc_pair_hash(uint32_t seed, uint32_t counter) {
     return x;
 }
 
-typedef struct { int cls; double value; int32_t token; } orc_cand_t;
+typedef struct { int cls; double value; int32_t expert; int32_t token; } orc_cand_t;
 
 static int orc_cand_cmp(const void* a, const void* b) {
     const orc_cand_t* p = (const orc_cand_t*)a;
@@ -210,38 +217,64 @@ static int orc_cand_cmp(const void* a, const void* b) {
     if (p->cls != q->cls) return p->cls > q->cls ? -1 : 1;
     if (p->value > q->value) return -1;
     if (p->value < q->value) return 1;
+    if (p->expert != q->expert) return p->expert < q->expert ? -1 : 1;
     return (p->token > q->token) - (p->token < q->token);
+}
+
+static double orc_importance(const float* scores, int E, int t, int e, int metric, uint32_t seed) {
+    switch (metric) {
+        case ORC_METRIC_ORDER: return -(double)t;
+        case ORC_METRIC_REVERSE_ORDER: return (double)t;
+        case ORC_METRIC_RANDOM: return (double)(orc_pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2);
+        default: return (double)scores[(size_t)t * E + e];
+    }
+}
+
+/* Device-level budget (Sec. 5.2 "Device-Level Capacity-Aware Inference"): the experts of one
+ * device together hold at most n_l * gamma * N_bar pairs, n_l = E/G; as an integer it is
+ * evaluated like the expert capacity: gamma times (N*k*n_l), divided by E, truncated. */
+int orc_device_budget(double gamma, int seg_tokens, int k, int E, int experts_per_device) {
+    const long long all_pairs = (long long)seg_tokens * (k < experts_per_device ? k : experts_per_device);
+    if (isinf(gamma) && gamma > 0) return (int)all_pairs;
+    double c = gamma * (double)((long long)seg_tokens * k * experts_per_device) / (double)E;
+    if (!(c > 0.0)) return 0;
+    if (c >= (double)seg_tokens * (double)experts_per_device) return seg_tokens * experts_per_device;
+    return (int)c;
 }
 
 int64_t orc_capacity_drop(const float* scores, const uint8_t* cand, int N, int E, int k, int G, int mode,
                           int scope, double gamma, int metric, const uint8_t* token_class, uint32_t seed,
                           uint8_t* keep) {
-    const int n_blocks = (scope == ORC_SCOPE_LOCAL) ? G : 1;
+    const int per_device = scope == ORC_SCOPE_LOCAL_DEVICE || scope == ORC_SCOPE_GLOBAL_DEVICE;
+    const int n_blocks = (scope == ORC_SCOPE_LOCAL || scope == ORC_SCOPE_LOCAL_DEVICE) ? G : 1;
     const int seg_tokens = N / n_blocks;
-    const int cap = (mode == ORC_MODE_NONE) ? seg_tokens : orc_capacity(gamma, seg_tokens, k, E);
+    const int span = per_device ? E / G : 1; /* experts that share one budget */
+    int cap;
+    if (mode == ORC_MODE_NONE)
+        cap = seg_tokens * span;
+    else
+        cap = per_device ? orc_device_budget(gamma, seg_tokens, k, E, span) : orc_capacity(gamma, seg_tokens, k, E);
     int64_t kept = 0;
-    orc_cand_t* list = (orc_cand_t*)malloc(sizeof(orc_cand_t) * (size_t)(seg_tokens > 0 ? seg_tokens : 1));
+    const size_t room = (size_t)(seg_tokens > 0 ? seg_tokens : 1) * (size_t)span;
+    orc_cand_t* list = (orc_cand_t*)malloc(sizeof(orc_cand_t) * room);
     memset(keep, 0, (size_t)N * E);
     for (int b = 0; b < n_blocks; ++b) {
-        for (int e = 0; e < E; ++e) {
+        for (int e0 = 0; e0 < E; e0 += span) {
+            /* the candidates that compete for this budget: one expert, or all experts of one device */
             int n = 0;
-            for (int t = b * seg_tokens; t < (b + 1) * seg_tokens; ++t) {
-                if (!cand[(size_t)t * E + e]) continue;
-                list[n].cls = token_class ? (token_class[t] & 3) : 0;
-                list[n].token = t;
-                switch (metric) {
-                    case ORC_METRIC_ORDER: list[n].value = -(double)t; break;
-                    case ORC_METRIC_REVERSE_ORDER: list[n].value = (double)t; break;
-                    case ORC_METRIC_RANDOM:
-                        list[n].value = (double)(orc_pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2);
-                        break;
-                    default: list[n].value = (double)scores[(size_t)t * E + e]; break;
+            for (int e = e0; e < e0 + span; ++e) {
+                for (int t = b * seg_tokens; t < (b + 1) * seg_tokens; ++t) {
+                    if (!cand[(size_t)t * E + e]) continue;
+                    list[n].cls = token_class ? (token_class[t] & 3) : 0;
+                    list[n].expert = e;
+                    list[n].token = t;
+                    list[n].value = orc_importance(scores, E, t, e, metric, seed);
+                    ++n;
                 }
-                ++n;
             }
             qsort(list, (size_t)n, sizeof(orc_cand_t), orc_cand_cmp);
             const int n_keep = n < cap ? n : cap;
-            for (int i = 0; i < n_keep; ++i) keep[(size_t)list[i].token * E + e] = 1;
+            for (int i = 0; i < n_keep; ++i) keep[(size_t)list[i].token * E + list[i].expert] = 1;
             kept += n_keep;
         }
     }

@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "moe_oracle.c")
 _LIB = os.path.join(_HERE, "libmoe_oracle.so")
 
 MODE_NONE, MODE_TOKEN_DROP, MODE_EXPANDED_DROP = 0, 1, 2
-SCOPE_LOCAL, SCOPE_GLOBAL = 0, 1
+SCOPE_LOCAL, SCOPE_GLOBAL, SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> str:
@@ -52,6 +52,8 @@ def _load():
         lib.orc_capacity_drop.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, dbl, i32, vp, ctypes.c_uint32, vp]
         lib.orc_pair_hash.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
         lib.orc_pair_hash.restype = ctypes.c_uint32
+        lib.orc_device_budget.argtypes = [dbl, i32, i32, i32, i32]
+        lib.orc_device_budget.restype = i32
         lib.orc_capacity_drop.restype = i64
         lib.orc_build_plan.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.orc_build_plan.restype = i64
@@ -104,6 +106,10 @@ def topk(scores, k):
 
 def capacity(gamma, seg_tokens, k, n_experts) -> int:
     return int(_load().orc_capacity(float(gamma), seg_tokens, k, n_experts))
+
+
+def device_budget(gamma, seg_tokens, k, n_experts, experts_per_device) -> int:
+    return int(_load().orc_device_budget(float(gamma), seg_tokens, k, n_experts, experts_per_device))
 
 
 def candidates(topk_idx, n_experts, device_groups, mode):
@@ -170,10 +176,16 @@ def route_and_drop(logits, k, device_groups, mode, scope, gamma, metric=METRIC_S
     n, e = scores.shape
     cand = candidates(topk_idx, e, device_groups, mode)
     keep = capacity_drop(scores, cand, k, device_groups, mode, scope, gamma, metric, token_class, seed)
-    n_blocks = device_groups if scope == SCOPE_LOCAL else 1
+    n_blocks = device_groups if scope in (SCOPE_LOCAL, SCOPE_LOCAL_DEVICE) else 1
     plan = build_plan(scores, cand, keep, slots_per_token(k, e, device_groups, mode), n_blocks)
     seg_tokens = n // n_blocks
-    cap = seg_tokens if mode == MODE_NONE else capacity(gamma, seg_tokens, k, e)
+    span = e // device_groups if scope in (SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE) else 1
+    if mode == MODE_NONE:
+        cap = seg_tokens * span
+    elif span > 1 or scope in (SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE):
+        cap = device_budget(gamma, seg_tokens, k, e, span)
+    else:
+        cap = capacity(gamma, seg_tokens, k, e)
     return Plan(scores=scores, topk_idx=topk_idx, topk_score=topk_score, cand=cand, keep=keep, cap=cap, plan=plan)
 
 

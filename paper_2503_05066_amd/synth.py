@@ -10,7 +10,7 @@ weights nor the datasets are available here.  These generators stand in for them
 shapes follow the model families the paper names (OLMoE-, Mixtral-, fine-grained-
 and decode-shaped layers) and the router bias is skewed so that the peak expert
 load reaches several times the mean, as the paper's test-time load analysis
-reports (Sec. 2.1, Fig. "expert_capacity"; App. "Layer-wise Expert Load").
+reports (Sec. 3.1, Fig. "expert_capacity"; App. "Layer-wise Expert Load").
 """
 from __future__ import annotations
 

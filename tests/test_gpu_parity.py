@@ -157,7 +157,7 @@ def test_plan_with_forced_ties(orc, mode, scope, g):
     ("mixtral", ED, GLOBAL, 1.0, 2, True, 0), ("decode", ED, LOCAL, 1.0, 3, False, 14), ("tiny", TD, LOCAL, 1.0, 1, True, 0),
 ])
 def test_plan_other_metrics_and_token_classes(orc, name, mode, scope, gamma, metric, classes, seed):
-    """Order / Reverse Order / Random (Sec. 3) and the multimodal class strategies, at full size."""
+    """Order / Reverse Order / Random (Sec. 4) and the multimodal class strategies, at full size."""
     w = W[name]
     if name not in _logit_cache:
         _logit_cache[name] = oracle_logits(orc, w)

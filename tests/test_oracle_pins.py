@@ -146,7 +146,7 @@ def test_topk_ties_go_to_lower_expert(orc):
 
 
 # ----------------------------------------------------------------------------
-# capacity, Sec. 3 (C = gamma * N_bar) and the integer form of Alg. 1
+# capacity, Sec. 4 (C = gamma * N_bar) and the integer form of Alg. 1
 # ----------------------------------------------------------------------------
 def test_capacity_values(orc):
     # the five workloads: N_bar = N k / E is an integer, C = gamma N_bar
@@ -237,7 +237,7 @@ def test_threshold_definition(orc, seed):
 
 
 # ----------------------------------------------------------------------------
-# load invariants: Sec. 2.2 (sum and range of loads), Sec. 3 (bound under gamma), Eq. (11)
+# load invariants: Sec. 3.2 (sum and range of loads), Sec. 4 (bound under gamma), Eq. (11)
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("gamma", [0.25, 0.5, 1.0, 1.5, 2.0])
 def test_load_invariants_and_dropped_ratio(orc, gamma):
@@ -275,7 +275,7 @@ def test_gamma_infinite_and_mode_none_reproduce_plain_topk(orc):
 
 
 # ----------------------------------------------------------------------------
-# Expanded Drop properties, Sec. 3 "Expanded Drop" and Alg. 2
+# Expanded Drop properties, Sec. 4 "Expanded Drop" and Alg. 2
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("scope", [LOCAL, GLOBAL])
 def test_expanded_drop_properties(orc, scope):
@@ -350,7 +350,7 @@ def test_zero_score_candidates_rank_above_non_candidates(orc):
 
 
 # ----------------------------------------------------------------------------
-# "Score" does not depend on the order of tokens in the batch (Sec. 3, metrics)
+# "Score" does not depend on the order of tokens in the batch (Sec. 4, metrics)
 # ----------------------------------------------------------------------------
 def test_score_metric_is_permutation_equivariant(orc):
     logits = small_logits(160, 8, 9, 1.5)
@@ -361,7 +361,7 @@ def test_score_metric_is_permutation_equivariant(orc):
 
 
 # ----------------------------------------------------------------------------
-# the other ranking metrics of Sec. 3 (Order, Reverse Order, Random) and the multimodal strategies
+# the other ranking metrics of Sec. 4 (Order, Reverse Order, Random) and the multimodal strategies
 # ----------------------------------------------------------------------------
 def segments(n, e, scope, g):
     blocks = g if scope == LOCAL else 1
@@ -467,6 +467,53 @@ def test_modality_strategies(orc):
 
 
 # ----------------------------------------------------------------------------
+# device-level capacity (Sec. 5.2, "Advanced Variant: Device-Level Capacity-Aware Inference")
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", [TD, ED])
+@pytest.mark.parametrize("scope_dev,scope_exp", [(2, LOCAL), (3, GLOBAL)])
+def test_device_level_capacity(orc, mode, scope_dev, scope_exp):
+    n, e, k, g, gamma = 512, 16, 2, 4, 1.0
+    m = e // g
+    logits = small_logits(n, e, 31, 2.0)
+    dev = orc.route_and_drop(logits, k, g, mode, scope_dev, gamma)
+    exp = orc.route_and_drop(logits, k, g, mode, scope_exp, gamma)
+    blocks = g if scope_dev == 2 else 1
+    ns = n // blocks
+    budget = int(gamma * (ns * k * m) / e)             # n_l * gamma * N_bar
+    assert dev.cap == budget == m * exp.cap
+    np.testing.assert_array_equal(dev.cand, exp.cand)
+    limited = 0
+    for b in range(blocks):
+        toks = np.arange(b * ns, (b + 1) * ns)
+        for dg in range(g):
+            cols = np.arange(dg * m, (dg + 1) * m)
+            cand = dev.cand[np.ix_(toks, cols)].astype(bool)
+            kept = dev.keep[np.ix_(toks, cols)].astype(bool)
+            assert kept.sum() == min(cand.sum(), budget)                    # N_1 + ... + N_nl <= n_l gamma N_bar
+            # brute force: rank all candidate pairs of the device together (score, then expert, then token)
+            tt, ee = np.nonzero(cand)
+            order = np.lexsort((toks[tt], cols[ee], -dev.scores[toks[tt], cols[ee]].astype(np.float64)))
+            expect = np.zeros_like(kept)
+            expect[tt[order[:budget]], ee[order[:budget]]] = True
+            np.testing.assert_array_equal(kept, expect)
+            # a single overloaded expert no longer forces drops while the device has spare room
+            kept_exp = exp.keep[np.ix_(toks, cols)].sum()
+            assert kept.sum() >= kept_exp
+            limited += cand.sum() > budget
+    assert limited > 0
+    assert dev.keep.sum() >= exp.keep.sum()
+    if mode == TD:   # (Expanded Drop can already fill every expert to its own capacity)
+        assert dev.keep.sum() > exp.keep.sum()
+        assert dev.keep.sum(0).max() > exp.cap * (blocks if scope_exp == LOCAL else 1)
+    # one expert per device: the two granularities coincide
+    one_d = orc.route_and_drop(logits, k, e, TD, 2, gamma)
+    one_e = orc.route_and_drop(logits, k, e, TD, LOCAL, gamma)
+    np.testing.assert_array_equal(one_d.keep, one_e.keep)
+    assert orc.device_budget(1.0, 2048, 8, 128, 16) == 16 * 128 and orc.device_budget(1.3, 128, 2, 8, 2) == 83
+    assert orc.device_budget(math.inf, 64, 2, 8, 4) == 128 and orc.device_budget(0.0, 64, 2, 8, 4) == 0
+
+
+# ----------------------------------------------------------------------------
 # dispatch plan
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (ED, LOCAL, 4), (ED, GLOBAL, 4), (NONE, LOCAL, 2)])
@@ -545,7 +592,7 @@ def test_layer_output_needs_the_weights_it_uses(orc):
 
 
 # ----------------------------------------------------------------------------
-# the synthetic workloads have the skew the paper reports (Sec. 2.1; App. layer-wise load)
+# the synthetic workloads have the skew the paper reports (Sec. 3.1; App. layer-wise load)
 # ----------------------------------------------------------------------------
 def test_workload_skew(orc):
     w = synth.WORKLOADS["olmoe"]
