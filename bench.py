@@ -29,7 +29,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 MEASURED_TRAFFIC = {("olmoe", "token", "local", 1.0): 716.7e6 + 32.5e6}
 
 MODES = {"none": 0, "token": 1, "expanded": 2}
-SCOPES = {"local": 0, "global": 1}
+SCOPES = {"local": 0, "global": 1, "local_device": 2, "global_device": 3}
+METRICS = {"score": 0, "order": 1, "reverse_order": 2, "random": 3}
 
 
 def parse():
@@ -41,13 +42,14 @@ def parse():
     p.add_argument("--mode", default="token", choices=list(MODES))
     p.add_argument("--scope", default="local", choices=list(SCOPES))
     p.add_argument("--gamma", type=float, default=1.0)
+    p.add_argument("--metric", default="score", choices=list(METRICS), help="what ranks the tokens of a full expert")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--unfused", action="store_true",
                    help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
-    p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none",
-                   help="comma list of workload:mode measured after the main line ('' for none)")
+    p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none,mixtral:token:local_device",
+                   help="comma list of workload:mode[:scope] measured after the main line ('' for none)")
     return p.parse_args()
 
 
@@ -93,14 +95,14 @@ def algorithmic_work(w, S, rows, active, elem):
     }
 
 
-def measure(w, mode, scope, gamma, steps, warmup, fused=True):
+def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
     import torch
 
     from paper_2503_05066_amd import capmoe, synth
 
     t = upload(w)
     desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
-                            gamma, w.dtype)
+                            gamma, w.dtype, metric)
     buf = capmoe.LayerBuffers(desc)
     K_GU = capmoe.KERNELS.index("ffn_gate_up")
 
@@ -226,7 +228,7 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[a.workload]
     mode, scope = MODES[a.mode], SCOPES[a.scope]
-    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused)
+    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused, metric=METRICS[a.metric])
     primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
     primary["kernel"] = other["kernel"] = "ffn_gemm_bf16_kernel<..., SWIGLU> (gate/up GEMM + SwiGLU epilogue)"
     primary["traffic"] = other["traffic"] = MEASURED_TRAFFIC.get((a.workload, a.mode, a.scope, a.gamma))
@@ -250,7 +252,8 @@ def main():
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n_tokens} d={w.d_model} E={w.n_experts} k={w.top_k} h={w.d_hidden} "
-                               f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity",
+                               f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity, "
+                               f"{a.metric} metric",
                    "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
                    "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
                    "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3),
@@ -262,14 +265,17 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, mode, scope, a.gamma)
     others = []
     for item in [s for s in a.others.split(",") if s]:
-        name, m = item.split(":")
-        if name == a.workload and m == a.mode:
+        parts = item.split(":")
+        name, m = parts[0], parts[1]
+        osc = parts[2] if len(parts) > 2 else a.scope
+        if name == a.workload and m == a.mode and osc == a.scope:
             continue
         ow = synth.WORKLOADS[name]
-        o = measure(ow, MODES[m], scope, a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5), fused=not a.unfused)
+        o = measure(ow, MODES[m], SCOPES[osc], a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5),
+                    fused=not a.unfused, metric=METRICS[a.metric])
         p1, p2 = roofline_of(o["work"]["ffn_gate_up"], o["gate_up_ms"])
         d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
-        others.append({"workload": name, "mode": m, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
+        others.append({"workload": name, "mode": m, "scope": osc, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
                        "ms_per_step": o["ms_per_step"], "surviving_pairs": o["rows"], "cap": o["cap"],
                        "max_segment_load": o["max_segment_load"], "ffn_gate_up": p1, "ffn_down": d1,
                        "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})

@@ -42,7 +42,9 @@ typedef enum {
 } moe_status_t;
 
 enum { MOE_MODE_NONE = 0, MOE_MODE_TOKEN_DROP = 1, MOE_MODE_EXPANDED_DROP = 2 };
-enum { MOE_SCOPE_LOCAL = 0, MOE_SCOPE_GLOBAL = 1 };
+/* Where a capacity constraint applies: per expert (Sec. 4) or per device (Sec. 5.2, "Advanced Variant:
+ * Device-Level Capacity-Aware Inference"), over the tokens of one device (LOCAL) or over all tokens */
+enum { MOE_SCOPE_LOCAL = 0, MOE_SCOPE_GLOBAL = 1, MOE_SCOPE_LOCAL_DEVICE = 2, MOE_SCOPE_GLOBAL_DEVICE = 3 };
 enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
 /* What ranks the candidates of an overflowed expert (Sec. 4, list of metrics) */
 enum { MOE_METRIC_SCORE = 0, MOE_METRIC_ORDER = 1, MOE_METRIC_REVERSE_ORDER = 2, MOE_METRIC_RANDOM = 3 };
@@ -58,7 +60,12 @@ typedef struct {
     int32_t mode;           /* MOE_MODE_*: plain top-k, Token Drop (Alg. 1), Expanded Drop (Alg. 2)  */
     int32_t capacity_scope; /* MOE_SCOPE_LOCAL: capacity per (device's tokens, expert), with
                                N/G tokens in the capacity formula (Sec. 4: constraints are applied
-                               within each local device).  MOE_SCOPE_GLOBAL: per expert over all N.  */
+                               within each local device).  MOE_SCOPE_GLOBAL: per expert over all N.
+                               MOE_SCOPE_LOCAL_DEVICE / MOE_SCOPE_GLOBAL_DEVICE: one budget for the E/G
+                               experts of a device, N_1 + ... + N_nl <= n_l * gamma * N_bar (Sec. 5.2): all
+                               candidate pairs of the device's experts are ranked together (equal rank:
+                               lower expert id, then lower token); the paper states the constraint, the
+                               ranking rule is this library's reading.                               */
     double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 4)                           */
     int32_t dtype;          /* MOE_DTYPE_*: type of x, expert weights, xp, yp, y.  The router
                                (logits, softmax, scores) is always fp32.                             */
@@ -73,6 +80,7 @@ const char* moe_status_string(int status);
  * Static sizes of a layer call (host-only, launches nothing).
  *   cap             capacity of one segment: min(Ns, trunc(gamma * (Ns*k) / E)), Ns = N (GLOBAL) or
  *                   N/G (LOCAL); Ns for MOE_MODE_NONE or gamma = +inf.  (Sec. 4; Alg. 1)
+ *                   Device scopes: the device budget min(Ns*E/G, trunc(gamma * (Ns*k*E/G) / E)).
  *   slots_per_token S = k, or k + E/G for Expanded Drop (a token may keep up to k+m experts, Sec. 4)
  *   max_rows        P_max, an upper bound on surviving token-expert pairs: size xp, yp, row_token,
  *                   row_weight for this many rows
@@ -104,7 +112,7 @@ int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router,
  * device.  In every capacity segment (expert, or device-block x expert for LOCAL scope) the `cap`
  * candidates that rank highest under desc->metric (the gating score by default) are kept; equal rank
  * goes to the lower token index.
- * Outputs (the dispatch plan; B = G for LOCAL scope, 1 for GLOBAL):
+ * Outputs (the dispatch plan; B = G for the LOCAL scopes, 1 for the GLOBAL ones):
  *   expert_count  [E]     kept pairs per expert
  *   seg_count     [B,E]   kept pairs per (device block, expert)
  *   expert_offset [E+1]   exclusive prefix sum of expert_count; expert_offset[E] = P

@@ -234,8 +234,7 @@ static double orc_importance(const float* scores, int E, int t, int e, int metri
  * device together hold at most n_l * gamma * N_bar pairs, n_l = E/G; as an integer it is
  * evaluated like the expert capacity: gamma times (N*k*n_l), divided by E, truncated. */
 int orc_device_budget(double gamma, int seg_tokens, int k, int E, int experts_per_device) {
-    const long long all_pairs = (long long)seg_tokens * (k < experts_per_device ? k : experts_per_device);
-    if (isinf(gamma) && gamma > 0) return (int)all_pairs;
+    if (isinf(gamma) && gamma > 0) return seg_tokens * experts_per_device; /* no limit: every possible pair */
     double c = gamma * (double)((long long)seg_tokens * k * experts_per_device) / (double)E;
     if (!(c > 0.0)) return 0;
     if (c >= (double)seg_tokens * (double)experts_per_device) return seg_tokens * experts_per_device;

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libcapmoe.so")
 
 MOE_OK = 0
 MODE_NONE, MODE_TOKEN_DROP, MODE_EXPANDED_DROP = 0, 1, 2
-SCOPE_LOCAL, SCOPE_GLOBAL = 0, 1
+SCOPE_LOCAL, SCOPE_GLOBAL, SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
 METRIC_SCORE, METRIC_ORDER, METRIC_REVERSE_ORDER, METRIC_RANDOM = 0, 1, 2, 3
 
@@ -178,7 +178,7 @@ class LayerBuffers:
         self.desc = desc
         self.cap, self.slots, self.max_rows, self.workspace_bytes = moe_query(desc)
         n, e, k, d = desc.n_tokens, desc.n_experts, desc.top_k, desc.d_model
-        blocks = desc.device_groups if desc.capacity_scope == SCOPE_LOCAL else 1
+        blocks = desc.device_groups if desc.capacity_scope in (SCOPE_LOCAL, SCOPE_LOCAL_DEVICE) else 1
         act = torch.bfloat16 if desc.dtype == DTYPE_BF16 else torch.float32
         rows = max(self.max_rows, 1)
         i32, f32 = torch.int32, torch.float32

@@ -14,14 +14,14 @@ int validate(const moe_desc_t* d) {
     if (d->top_k > d->n_experts) return MOE_ERR_INVALID_ARG;
     if (d->n_tokens % d->device_groups != 0 || d->n_experts % d->device_groups != 0) return MOE_ERR_INVALID_ARG;
     if (d->mode < MOE_MODE_NONE || d->mode > MOE_MODE_EXPANDED_DROP) return MOE_ERR_INVALID_ARG;
-    if (d->capacity_scope != MOE_SCOPE_LOCAL && d->capacity_scope != MOE_SCOPE_GLOBAL) return MOE_ERR_INVALID_ARG;
+    if (d->capacity_scope < MOE_SCOPE_LOCAL || d->capacity_scope > MOE_SCOPE_GLOBAL_DEVICE) return MOE_ERR_INVALID_ARG;
     if (d->dtype != MOE_DTYPE_F32 && d->dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
     if (d->metric < MOE_METRIC_SCORE || d->metric > MOE_METRIC_RANDOM) return MOE_ERR_INVALID_ARG;
     if (std::isnan(d->gamma) || d->gamma < 0.0) return MOE_ERR_INVALID_ARG;
     if (d->n_experts > kMaxExperts || d->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
     const int slots = d->top_k + (d->mode == MOE_MODE_EXPANDED_DROP ? d->n_experts / d->device_groups : 0);
     if (slots > 255) return MOE_ERR_UNSUPPORTED;
-    if ((int64_t)d->n_tokens * d->n_experts >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    if ((int64_t)d->n_tokens * d->n_experts >= (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
     if ((int64_t)d->n_tokens * slots >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
     // rows are moved in 16-byte pieces
     const int per16 = d->dtype == MOE_DTYPE_BF16 ? 8 : 4;
@@ -31,25 +31,31 @@ int validate(const moe_desc_t* d) {
 
 Sizes derive(const moe_desc_t& d) {
     Sizes s;
-    s.n_blocks = d.capacity_scope == MOE_SCOPE_LOCAL ? d.device_groups : 1;
+    const bool local = d.capacity_scope == MOE_SCOPE_LOCAL || d.capacity_scope == MOE_SCOPE_LOCAL_DEVICE;
+    const bool per_device = d.capacity_scope == MOE_SCOPE_LOCAL_DEVICE || d.capacity_scope == MOE_SCOPE_GLOBAL_DEVICE;
+    s.n_blocks = local ? d.device_groups : 1;
     s.seg_tokens = d.n_tokens / s.n_blocks;
     s.group_experts = d.n_experts / d.device_groups;
     s.group_tokens = d.n_tokens / d.device_groups;
+    s.span = per_device ? s.group_experts : 1;
+    const long long seg_pairs = (long long)s.seg_tokens * s.span;  // most pairs a segment can hold
     if (d.mode == MOE_MODE_NONE || (std::isinf(d.gamma) && d.gamma > 0)) {
-        s.cap = s.seg_tokens;
+        s.cap = (int)seg_pairs;
     } else {
-        // capacity as in Alg. 1: gamma times (N*k), divided by E, truncated; never above the segment size
-        const double c = d.gamma * (double)((long long)s.seg_tokens * (long long)d.top_k) / (double)d.n_experts;
+        // capacity as in Alg. 1: gamma times (N*k), divided by E, truncated; for a device budget the
+        // numerator carries the n_l experts of the device (Sec. 5.2); never above what the segment holds
+        const double c =
+            d.gamma * (double)((long long)s.seg_tokens * (long long)d.top_k * s.span) / (double)d.n_experts;
         if (!(c > 0.0))
             s.cap = 0;
-        else if (c >= (double)s.seg_tokens)
-            s.cap = s.seg_tokens;
+        else if (c >= (double)seg_pairs)
+            s.cap = (int)seg_pairs;
         else
             s.cap = (int)c;
     }
     s.slots = d.top_k + (d.mode == MOE_MODE_EXPANDED_DROP ? s.group_experts : 0);
     const int64_t by_tokens = (int64_t)d.n_tokens * (s.slots < d.n_experts ? s.slots : d.n_experts);
-    const int64_t by_capacity = (int64_t)s.n_blocks * d.n_experts * s.cap;
+    const int64_t by_capacity = (int64_t)s.n_blocks * (d.n_experts / s.span) * s.cap;
     s.max_rows = by_tokens < by_capacity ? by_tokens : by_capacity;
     s.elem = d.dtype == MOE_DTYPE_BF16 ? 2 : 4;
     return s;

@@ -25,7 +25,8 @@ inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 struct Sizes {
     int n_blocks;      // capacity blocks B
     int seg_tokens;    // tokens per capacity segment
-    int cap;           // capacity per segment
+    int cap;           // capacity per segment (per expert, or per device for the device scopes)
+    int span;          // experts that share one capacity: 1, or E/G for the device scopes
     int slots;         // S
     int64_t max_rows;  // P_max
     int group_experts; // m = E / G

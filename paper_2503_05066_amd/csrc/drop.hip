@@ -139,69 +139,108 @@ __device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
 // ---------------------------------------------------------------------------------------------
 constexpr int kSelectCache = 16384;  // keys of a segment kept in LDS (64 KB); longer segments re-read L2
 
+// One block per capacity segment: `span` experts (1, or the E/G experts of a device when the
+// capacity is a device budget) over seg_tokens tokens.  The keys of expert e0+r form run r.
+// Outputs, per (block, expert): the threshold, how many keys equal to it survive, the kept count.
+// Several experts under one budget share the threshold; the keys equal to it are granted to the
+// lower expert ids first (inside an expert, the emit kernel grants them to the lower tokens).
 __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __restrict__ key_t,
                                                           uint32_t* __restrict__ seg_tau,
                                                           int32_t* __restrict__ seg_need,
                                                           int32_t* __restrict__ seg_count, int N, int E, int seg_tokens,
-                                                          int cap) {
+                                                          int span, int cap) {
     extern __shared__ uint32_t cache[];
     __shared__ int hist[256];
+    __shared__ int gt_s[kMaxExperts], eq_s[kMaxExperts];
     __shared__ int red[4];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_rem;
-    const int seg = blockIdx.x;  // = b*E + e
-    const int b = seg / E, e = seg - b * E;
-    const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
+    const int groups = E / span;
+    const int b = blockIdx.x / groups, e0 = (blockIdx.x - b * groups) * span;
+    const uint32_t* keys = key_t + (size_t)e0 * N + (size_t)b * seg_tokens;  // run r starts at keys + r*N
     const int tid = threadIdx.x;
-    const bool cached = seg_tokens <= kSelectCache;
+    const int n_keys = span * seg_tokens;
+    const bool cached = n_keys <= kSelectCache;
 
     int mine = 0;
-    for (int i = tid; i < seg_tokens; i += 256) {
-        const uint32_t kx = keys[i];
+    for (int i = tid; i < n_keys; i += 256) {
+        const int r = i / seg_tokens;
+        const uint32_t kx = keys[(size_t)r * N + (i - r * seg_tokens)];
         if (cached) cache[i] = kx;
         mine += kx != 0u;
     }
-    const int n_cand = block_sum_256(mine, red);  // its barriers also order the cache writes before the reads
+    for (int r = tid; r < span; r += 256) gt_s[r] = eq_s[r] = 0;
+    const int n_cand = block_sum_256(mine, red);  // its barriers also order the LDS writes before the reads
 
-    if (n_cand <= cap || cap == 0) {
-        if (tid == 0) {
-            // cap == 0: nothing passes; otherwise every candidate (key >= 1) passes
-            seg_tau[seg] = cap == 0 ? 0xffffffffu : 0u;
-            seg_need[seg] = 0;
-            seg_count[seg] = cap == 0 ? 0 : n_cand;
+    // threshold: keys above tau are kept, `rem` of the keys equal to tau are kept
+    uint32_t tau = 0;  // every candidate (key >= 1) passes
+    int rem = 0;
+    if (cap == 0) {
+        tau = 0xffffffffu;  // nothing passes
+    } else if (n_cand > cap) {
+        // cap-th largest key, most significant byte first
+        uint32_t prefix = 0;
+        rem = cap;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            hist[tid] = 0;
+            __syncthreads();
+            const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+            for (int i = tid; i < n_keys; i += 256) {
+                uint32_t kx;
+                if (cached) {
+                    kx = cache[i];
+                } else {
+                    const int r = i / seg_tokens;
+                    kx = keys[(size_t)r * N + (i - r * seg_tokens)];
+                }
+                if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+            }
+            __syncthreads();
+            // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
+            // digit; the digit where that count first reaches `rem` holds the cap-th key
+            const int mine_d = 255 - tid;
+            const int h = hist[mine_d];
+            int total;
+            const int above = block_exclusive_scan_256(h, red, &total);
+            if (above + h >= rem && above < rem) {  // exactly one thread
+                sh_prefix = prefix | ((uint32_t)mine_d << shift);
+                sh_rem = rem - above;
+            }
+            __syncthreads();
+            prefix = sh_prefix;
+            rem = sh_rem;
         }
-        return;
+        tau = prefix;
     }
-    // cap-th largest key, most significant byte first
-    uint32_t prefix = 0;
-    int rem = cap;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        hist[tid] = 0;
-        __syncthreads();
-        const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
-        for (int i = tid; i < seg_tokens; i += 256) {
-            const uint32_t kx = cached ? cache[i] : keys[i];
-            if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+    // per expert: keys above the threshold and keys equal to it (a thread's keys change run rarely)
+    {
+        int run = -1, gt = 0, eq = 0;
+        for (int i = tid; i < n_keys; i += 256) {
+            const int r = i / seg_tokens;
+            const uint32_t kx = cached ? cache[i] : keys[(size_t)r * N + (i - r * seg_tokens)];
+            if (r != run) {
+                if (gt) atomicAdd(&gt_s[run], gt);
+                if (eq) atomicAdd(&eq_s[run], eq);
+                run = r;
+                gt = eq = 0;
+            }
+            gt += kx > tau;
+            eq += kx == tau && kx != 0u;
         }
-        __syncthreads();
-        // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
-        // digit; the digit where that count first reaches `rem` holds the cap-th key
-        const int mine_d = 255 - tid;
-        const int h = hist[mine_d];
-        int total;
-        const int above = block_exclusive_scan_256(h, red, &total);
-        if (above + h >= rem && above < rem) {  // exactly one thread
-            sh_prefix = prefix | ((uint32_t)mine_d << shift);
-            sh_rem = rem - above;
-        }
-        __syncthreads();
-        prefix = sh_prefix;
-        rem = sh_rem;
+        if (gt) atomicAdd(&gt_s[run], gt);
+        if (eq) atomicAdd(&eq_s[run], eq);
     }
+    __syncthreads();
     if (tid == 0) {
-        seg_tau[seg] = prefix;  // keys above it are all kept
-        seg_need[seg] = rem;    // and the first `rem` keys equal to it, in token order
-        seg_count[seg] = cap;
+        int left = rem;
+        for (int r = 0; r < span; ++r) {
+            const int take = eq_s[r] < left ? eq_s[r] : left;
+            left -= take;
+            const int seg = b * E + e0 + r;
+            seg_tau[seg] = tau;
+            seg_need[seg] = take;
+            seg_count[seg] = gt_s[r] + take;
+        }
     }
 }
 
@@ -330,15 +369,16 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     const int segs = s.n_blocks * E;
     {
         ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
-        const size_t lds = (size_t)(s.seg_tokens <= kSelectCache ? s.seg_tokens : 0) * 4;
+        const size_t n_keys = (size_t)s.seg_tokens * s.span;
+        const size_t lds = (n_keys <= (size_t)kSelectCache ? n_keys : 0) * 4;
         static bool configured = false;
         if (!configured) {  // 64 KB of keys plus the kernel's own few hundred bytes
             (void)hipFuncSetAttribute((const void*)drop_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       kSelectCache * 4);
             configured = true;
         }
-        hipLaunchKernelGGL(drop_select_kernel, dim3(segs), dim3(256), lds, st, ws.key_t, ws.seg_tau, ws.seg_need,
-                           seg_count, N, E, s.seg_tokens, s.cap);
+        hipLaunchKernelGGL(drop_select_kernel, dim3(segs / s.span), dim3(256), lds, st, ws.key_t, ws.seg_tau,
+                           ws.seg_need, seg_count, N, E, s.seg_tokens, s.span, s.cap);
     }
     {
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);

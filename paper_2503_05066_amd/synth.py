@@ -20,7 +20,7 @@ import math
 import numpy as np
 
 MODE_NONE, MODE_TOKEN_DROP, MODE_EXPANDED_DROP = 0, 1, 2
-SCOPE_LOCAL, SCOPE_GLOBAL = 0, 1
+SCOPE_LOCAL, SCOPE_GLOBAL, SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE = 0, 1, 2, 3
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 BASE_SEED = 20250305

@@ -43,6 +43,8 @@ def test_descriptor_layout_matches_header():
     ("mixtral", 1, 1, 1.0, 2048, 2, 16384), ("finegrained", 2, 0, 1.0, 128, 24, 131072),
     ("finegrained", 2, 1, 1.25, 1280, 24, 163840), ("decode", 2, 0, 1.0, 3, 14, 1536),
     ("olmoe", 0, 0, 1.0, 4096, 8, 32768), ("olmoe", 1, 0, math.inf, 4096, 8, 32768), ("olmoe", 1, 0, 0.0, 0, 8, 0),
+    ("mixtral", 1, 2, 1.0, 1024, 2, 16384), ("finegrained", 2, 2, 1.0, 2048, 24, 131072),
+    ("finegrained", 1, 3, 1.25, 20480, 8, 131072),
 ])
 def test_query_sizes(orc, name, mode, scope, gamma, cap, slots, rows):
     w = synth.WORKLOADS[name]
@@ -50,9 +52,12 @@ def test_query_sizes(orc, name, mode, scope, gamma, cap, slots, rows):
                          w.dtype)
     got = capmoe.moe_query(d)
     assert got[:3] == (cap, slots, rows)
-    blocks = w.device_groups if scope == 0 else 1
-    if mode != 0:
+    blocks = w.device_groups if scope in (0, 2) else 1
+    if mode != 0 and scope < 2:
         assert cap == orc.capacity(gamma, w.n_tokens // blocks, w.top_k, w.n_experts)
+    if mode != 0 and scope >= 2:
+        assert cap == orc.device_budget(gamma, w.n_tokens // blocks, w.top_k, w.n_experts,
+                                        w.n_experts // w.device_groups)
     assert got[3] > 0
 
 

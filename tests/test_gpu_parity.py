@@ -172,6 +172,41 @@ def test_plan_other_metrics_and_token_classes(orc, name, mode, scope, gamma, met
         assert (ref.keep != base.keep).any()
 
 
+LOCAL_DEV, GLOBAL_DEV = 2, 3
+
+
+@pytest.mark.parametrize("name,mode,scope,gamma,metric", [
+    ("mixtral", TD, LOCAL_DEV, 1.0, 0), ("mixtral", ED, LOCAL_DEV, 1.0, 0), ("mixtral", TD, GLOBAL_DEV, 1.5, 0),
+    ("finegrained", TD, LOCAL_DEV, 1.0, 0), ("finegrained", ED, LOCAL_DEV, 1.0, 0), ("finegrained", TD, GLOBAL_DEV, 1.0, 3),
+    ("decode", ED, LOCAL_DEV, 1.0, 0), ("decode", TD, LOCAL_DEV, 1.0, 1), ("olmoe", TD, LOCAL_DEV, 1.0, 0),
+])
+def test_plan_device_level_capacity(orc, name, mode, scope, gamma, metric):
+    """One budget per device's experts (Sec. 5.2 of the paper), full size."""
+    w = W[name]
+    if name not in _logit_cache:
+        _logit_cache[name] = oracle_logits(orc, w)
+    buf, ref = check_route_and_plan(orc, _logit_cache[name], w.n_tokens, w.n_experts, w.top_k, w.device_groups, mode,
+                                    scope, gamma, f"{name} device-level", metric, None, 5 if metric == 3 else 0)
+    m = w.n_experts // w.device_groups
+    per_device = ref.plan.seg_count.reshape(ref.plan.seg_count.shape[0], w.device_groups, m).sum(2)
+    assert per_device.max() <= ref.cap                                  # aggregated device load <= n_l gamma N_bar
+    if m > 1 and mode == TD:
+        expert_level = orc.route_and_drop(_logit_cache[name], w.top_k, w.device_groups, mode, scope - 2, gamma, metric,
+                                          None, 5 if metric == 3 else 0)
+        assert ref.plan.rows >= expert_level.plan.rows                  # less restrictive than per-expert limits
+
+
+def test_device_level_ties(orc):
+    w = synth.scaled(W["olmoe"], n_tokens=2048, n_experts=32, top_k=4, device_groups=4)
+    logits = synth.logits_with_ties(w)
+    for scope in (LOCAL_DEV, GLOBAL_DEV):
+        for mode in (TD, ED):
+            check_route_and_plan(orc, logits, w.n_tokens, w.n_experts, w.top_k, 4, mode, scope, 1.0, "device ties")
+    flat = np.zeros((512, 16), np.float32)     # every score equal: the tie rule alone decides
+    check_route_and_plan(orc, flat, 512, 16, 2, 4, TD, LOCAL_DEV, 0.5, "device ties flat")
+    check_route_and_plan(orc, flat, 512, 16, 2, 4, ED, GLOBAL_DEV, 0.5, "device ties flat")
+
+
 def test_random_metric_ties_and_seeds(orc):
     n, e = 1024, 8
     logits = np.zeros((n, e), np.float32)           # all scores equal: only the draws decide

@@ -510,7 +510,7 @@ def test_device_level_capacity(orc, mode, scope_dev, scope_exp):
     one_e = orc.route_and_drop(logits, k, e, TD, LOCAL, gamma)
     np.testing.assert_array_equal(one_d.keep, one_e.keep)
     assert orc.device_budget(1.0, 2048, 8, 128, 16) == 16 * 128 and orc.device_budget(1.3, 128, 2, 8, 2) == 83
-    assert orc.device_budget(math.inf, 64, 2, 8, 4) == 128 and orc.device_budget(0.0, 64, 2, 8, 4) == 0
+    assert orc.device_budget(math.inf, 64, 2, 8, 4) == 256 and orc.device_budget(0.0, 64, 2, 8, 4) == 0
 
 
 # ----------------------------------------------------------------------------
