@@ -53,10 +53,20 @@ def parse():
     return p.parse_args()
 
 
+_uploaded = {}
+
+
 def upload(w):
-    """Synthetic inputs of a workload as device tensors (storage type of the workload)."""
+    """Synthetic inputs of a workload as device tensors (storage type of the workload).
+
+    The last workload stays resident, so that several modes of one workload share one upload."""
     import numpy as np
     import torch
+
+    if w.name in _uploaded:
+        return _uploaded[w.name]
+    _uploaded.clear()
+    torch.cuda.empty_cache()
 
     from paper_2503_05066_amd import synth
 
@@ -77,6 +87,7 @@ def upload(w):
         t["w_gate"][j].copy_(dev(g))
         t["w_up"][j].copy_(dev(u))
         t["w_down"][j].copy_(dev(dn))
+    _uploaded[w.name] = t
     return t
 
 
@@ -152,14 +163,24 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
         work["dispatch"]["bytes"] = 0
         kernel_ms["dispatch"] = 0.0
     nbar = w.n_tokens * w.top_k / w.n_experts
+    # load statistics of the paper's latency model (Eq. 4: the most loaded expert / device sets the pace)
+    import numpy as np
+    before = np.bincount(buf.topk_idx.cpu().numpy().ravel(), minlength=w.n_experts)
+    g = w.device_groups
+    dev_before = before.reshape(g, -1).sum(1)
+    dev_after = counts.reshape(g, -1).sum(1)
+    loads = {"max_expert_load_over_mean_topk": float(before.max() / nbar),
+             "max_expert_load_over_mean_kept": float(counts.max() / nbar),
+             "max_device_load_over_mean_topk": float(dev_before.max() / dev_before.mean()),
+             "max_device_load_over_mean_kept": float(dev_after.max() / max(dev_after.mean(), 1e-9))}
     res = {
         "wall_s": wall, "ms_per_step": 1e3 * wall / steps, "tokens_per_s": w.n_tokens * steps / wall,
         "gate_up_ms": gu_ms, "kernel_ms": kernel_ms, "rows": rows, "active_experts": active, "cap": buf.cap,
         "max_rows": buf.max_rows, "work": work, "max_load_over_mean": float(counts.max() / nbar),
         "max_segment_load": int(buf.seg_count.max()), "kept_fraction": rows / (w.n_tokens * w.top_k),
+        "loads": {k: round(v, 3) for k, v in loads.items()},
     }
-    del t, buf
-    torch.cuda.empty_cache()
+    del buf
     return res
 
 
@@ -256,7 +277,7 @@ def main():
                                f"{a.metric} metric",
                    "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
                    "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
-                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3),
+                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3), "loads": r["loads"],
                    "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
                             "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"},
         "roofline": primary, "roofline_other_roof": other, "stages": stages,
@@ -277,7 +298,7 @@ def main():
         d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
         others.append({"workload": name, "mode": m, "scope": osc, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
                        "ms_per_step": o["ms_per_step"], "surviving_pairs": o["rows"], "cap": o["cap"],
-                       "max_segment_load": o["max_segment_load"], "ffn_gate_up": p1, "ffn_down": d1,
+                       "max_segment_load": o["max_segment_load"], "loads": o["loads"], "ffn_gate_up": p1, "ffn_down": d1,
                        "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
     if others:
         out["other_workloads"] = others
