@@ -281,6 +281,7 @@ def main():
                    "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
                             "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"},
         "roofline": primary, "roofline_other_roof": other, "stages": stages,
+        "kernel_ms": {k: round(v, 4) for k, v in km.items()},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, mode, scope, a.gamma)

@@ -193,7 +193,8 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
                     const int r = i / seg_tokens;
                     kx = keys[(size_t)r * N + (i - r * seg_tokens)];
                 }
-                if ((kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+                // non-candidates (key 0) never matter
+                if (kx != 0u && (kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
             }
             __syncthreads();
             // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
@@ -211,6 +212,15 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
             rem = sh_rem;
         }
         tau = prefix;
+    }
+    if (span == 1) {  // one expert: the counts follow from the selection itself
+        if (tid == 0) {
+            const int seg = b * E + e0;
+            seg_tau[seg] = tau;
+            seg_need[seg] = rem;
+            seg_count[seg] = cap == 0 ? 0 : (n_cand > cap ? cap : n_cand);
+        }
+        return;
     }
     // per expert: keys above the threshold and keys equal to it (a thread's keys change run rarely)
     {
@@ -260,7 +270,7 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
                                                         int32_t* __restrict__ expert_offset,
                                                         int32_t* __restrict__ row_token, float* __restrict__ row_weight,
                                                         int32_t* __restrict__ pair_row, int N, int E, int n_blocks,
-                                                        int seg_tokens, int S) {
+                                                        int seg_tokens, int S, int weight_from_key) {
     // a thread owns a run of 16 consecutive tokens; one padding word per run keeps the runs of
     // neighbouring threads on different LDS banks
     __shared__ uint32_t key_s[kEmitChunk + 256];
@@ -339,7 +349,8 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
             const bool keep = (keep_bits >> j) & 1u;
             if (keep) {
                 row_token[pos] = t;
-                row_weight[pos] = scores[(size_t)t * E + e];  // the gating score, whatever ranked the pair
+                // the gating score, whatever ranked the pair (under the Score metric it is the key itself)
+                row_weight[pos] = weight_from_key ? __uint_as_float(kx[j] - 1u) : scores[(size_t)t * E + e];
             }
             pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
             pos += keep;
@@ -384,7 +395,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
         hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
                            ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
-                           s.n_blocks, s.seg_tokens, s.slots);
+                           s.n_blocks, s.seg_tokens, s.slots, d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
     }
     return hipGetLastError();
 }

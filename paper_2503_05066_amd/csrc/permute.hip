@@ -43,18 +43,30 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
         const long long t = i / pieces;
         const int c = (int)(i - t * pieces);
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < S; ++s) {
-            const int r = pair_row[t * S + s];
-            if (r < 0) continue;
-            const float w = row_weight[r];
-            const uint4 v = yp[(long long)r * pieces + c];
-            if (BF16) {
-                accumulate_bf16x8(acc, v, w);
-            } else {
-                acc[0] = fmaf(w, __uint_as_float(v.x), acc[0]);
-                acc[1] = fmaf(w, __uint_as_float(v.y), acc[1]);
-                acc[2] = fmaf(w, __uint_as_float(v.z), acc[2]);
-                acc[3] = fmaf(w, __uint_as_float(v.w), acc[3]);
+        // eight slots at a time: all row indices, then all weights, then all rows are requested before
+        // any is used (three dependent memory levels per batch instead of three per slot); the sum
+        // still runs in ascending slot order
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            int r[8];
+            float w[8];
+            uint4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) r[j] = s0 + j < S ? pair_row[t * S + s0 + j] : -1;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] = r[j] >= 0 ? row_weight[r[j]] : 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = r[j] >= 0 ? yp[(long long)r[j] * pieces + c] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (r[j] < 0) continue;
+                if (BF16) {
+                    accumulate_bf16x8(acc, v[j], w[j]);
+                } else {
+                    acc[0] = fmaf(w[j], __uint_as_float(v[j].x), acc[0]);
+                    acc[1] = fmaf(w[j], __uint_as_float(v[j].y), acc[1]);
+                    acc[2] = fmaf(w[j], __uint_as_float(v[j].z), acc[2]);
+                    acc[3] = fmaf(w[j], __uint_as_float(v[j].w), acc[3]);
+                }
             }
         }
         uint4 o;
