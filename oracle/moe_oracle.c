@@ -146,7 +146,10 @@ int orc_capacity(double gamma, int seg_tokens, int k, int E) {
 
 /* ---------------------------------------------------------------------------
  * Candidate set of every token.
- *   Token Drop (Alg. 1): the token's top-k experts.
+ *   Token Drop (Alg. 1): the token's top-k experts.  Over-selection (Sec. 5.2 "Effectiveness
+ *   of Expanded Drop", over-selection ratio m; appendix table with m = 2k, 3k): the list
+ *   handed in is the token's top-(k+m) instead, and `k` below is that list's width, while the
+ *   capacity keeps using the model's k.
  *   Expanded Drop (Alg. 2, Sec. 4 "Expanded Drop"): top-k plus all m = E/G experts
  *   hosted on the token's own device.  A set: an expert that is both counts once.
  * cand is a dense [N,E] 0/1 matrix.
@@ -186,8 +189,8 @@ void orc_candidates(const int32_t* topk_idx, int N, int E, int k, int G, int mod
  * class per token (0..3) ranks before the metric - a candidate of a lower class is
  * dropped before any candidate of a higher class.  Image First = image tokens class 0,
  * text tokens class 1; Uniform = no classes.
- * Equal importance goes to the lower expert id (only relevant when several experts share a
- * budget), then to the lower token index.
+ * Equal importance goes to the lower token index, then (only relevant when several experts
+ * share a budget) to the lower expert id.
  *
  * Granularity (Sec. 5.2, "Advanced Variant: Device-Level Capacity-Aware Inference"): with a
  * *_DEVICE scope the constraint bounds the aggregated load of the E/G experts of one device,
@@ -217,8 +220,8 @@ static int orc_cand_cmp(const void* a, const void* b) {
     if (p->cls != q->cls) return p->cls > q->cls ? -1 : 1;
     if (p->value > q->value) return -1;
     if (p->value < q->value) return 1;
-    if (p->expert != q->expert) return p->expert < q->expert ? -1 : 1;
-    return (p->token > q->token) - (p->token < q->token);
+    if (p->token != q->token) return p->token < q->token ? -1 : 1;
+    return (p->expert > q->expert) - (p->expert < q->expert);
 }
 
 static double orc_importance(const float* scores, int E, int t, int e, int metric, uint32_t seed) {
@@ -279,6 +282,35 @@ int64_t orc_capacity_drop(const float* scores, const uint8_t* cand, int N, int E
     }
     free(list);
     return kept;
+}
+
+/* ---------------------------------------------------------------------------
+ * At most k experts per token after the drop (Sec. 4 "Expanded Drop" and the appendix
+ * "Maximum Number of Selected Experts", the "w/ max" rows of its table): with k+m
+ * candidates a token may survive at more than k experts; the constrained variant retains
+ * the k surviving experts with the highest gating score (equal scores: lower expert id)
+ * and discards the token's other pairs.  Places freed at an expert are not handed to
+ * tokens that expert dropped earlier (one round of selection and dropping, as the paper
+ * argues against repeated rounds).  keep is updated in place; returns the pairs removed.
+ * ------------------------------------------------------------------------- */
+int64_t orc_limit_experts(const float* scores, int N, int E, int k, uint8_t* keep) {
+    int64_t removed = 0;
+    for (int t = 0; t < N; ++t) {
+        int n_kept = 0;
+        for (int e = 0; e < E; ++e) n_kept += keep[(size_t)t * E + e];
+        while (n_kept > k) {
+            /* discard the surviving expert with the lowest score; among equal scores the highest id */
+            int worst = -1;
+            for (int e = 0; e < E; ++e) {
+                if (!keep[(size_t)t * E + e]) continue;
+                if (worst < 0 || scores[(size_t)t * E + e] <= scores[(size_t)t * E + worst]) worst = e;
+            }
+            keep[(size_t)t * E + worst] = 0;
+            --n_kept;
+            ++removed;
+        }
+    }
+    return removed;
 }
 
 /* ---------------------------------------------------------------------------

@@ -55,6 +55,8 @@ def _load():
         lib.orc_device_budget.argtypes = [dbl, i32, i32, i32, i32]
         lib.orc_device_budget.restype = i32
         lib.orc_capacity_drop.restype = i64
+        lib.orc_limit_experts.argtypes = [vp, i32, i32, i32, vp]
+        lib.orc_limit_experts.restype = i64
         lib.orc_build_plan.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.orc_build_plan.restype = i64
         lib.orc_layer_output.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, i32, vp]
@@ -141,6 +143,16 @@ def capacity_drop(scores, cand, k, device_groups, mode, scope, gamma, metric=MET
     return keep
 
 
+def limit_experts(scores, keep, k):
+    """At most k surviving experts per token ("w/ max"); returns a new keep matrix."""
+    s = _c(scores, np.float32)
+    out = np.array(keep, dtype=np.uint8, order="C", copy=True)
+    n, e = s.shape
+    removed = _load().orc_limit_experts(_p(s), n, e, k, _p(out))
+    assert removed == int(np.asarray(keep, np.int64).sum() - out.sum())
+    return out
+
+
 class Plan:
     """The dispatch plan of one layer call (all numpy arrays)."""
 
@@ -148,8 +160,8 @@ class Plan:
         self.__dict__.update(kw)
 
 
-def slots_per_token(k, n_experts, device_groups, mode) -> int:
-    return k + (n_experts // device_groups if mode == MODE_EXPANDED_DROP else 0)
+def slots_per_token(k, n_experts, device_groups, mode, overselect=0) -> int:
+    return k + overselect + (n_experts // device_groups if mode == MODE_EXPANDED_DROP else 0)
 
 
 def build_plan(scores, cand, keep, slots, n_blocks) -> Plan:
@@ -169,15 +181,21 @@ def build_plan(scores, cand, keep, slots, n_blocks) -> Plan:
                 row_token=row_token[:p_max], row_weight=row_weight[:p_max], pair_row=pair_row)
 
 
-def route_and_drop(logits, k, device_groups, mode, scope, gamma, metric=METRIC_SCORE, token_class=None, seed=0):
-    """softmax -> top-k -> candidates -> drop -> plan, from given fp32 logits."""
+def route_and_drop(logits, k, device_groups, mode, scope, gamma, metric=METRIC_SCORE, token_class=None, seed=0,
+                   overselect=0, max_experts=False):
+    """softmax -> top-(k+overselect) -> candidates -> drop (-> at most k per token) -> plan, from fp32 logits.
+
+    The capacity always uses the model's k; `overselect` only widens the candidate lists.
+    """
     scores = softmax_scores(logits)
-    topk_idx, topk_score = topk(scores, k)
+    topk_idx, topk_score = topk(scores, k + overselect)
     n, e = scores.shape
     cand = candidates(topk_idx, e, device_groups, mode)
     keep = capacity_drop(scores, cand, k, device_groups, mode, scope, gamma, metric, token_class, seed)
+    if max_experts:
+        keep = limit_experts(scores, keep, k)
     n_blocks = device_groups if scope in (SCOPE_LOCAL, SCOPE_LOCAL_DEVICE) else 1
-    plan = build_plan(scores, cand, keep, slots_per_token(k, e, device_groups, mode), n_blocks)
+    plan = build_plan(scores, cand, keep, slots_per_token(k, e, device_groups, mode, overselect), n_blocks)
     seg_tokens = n // n_blocks
     span = e // device_groups if scope in (SCOPE_LOCAL_DEVICE, SCOPE_GLOBAL_DEVICE) else 1
     if mode == MODE_NONE:

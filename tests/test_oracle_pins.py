@@ -490,9 +490,9 @@ def test_device_level_capacity(orc, mode, scope_dev, scope_exp):
             cand = dev.cand[np.ix_(toks, cols)].astype(bool)
             kept = dev.keep[np.ix_(toks, cols)].astype(bool)
             assert kept.sum() == min(cand.sum(), budget)                    # N_1 + ... + N_nl <= n_l gamma N_bar
-            # brute force: rank all candidate pairs of the device together (score, then expert, then token)
+            # brute force: rank all candidate pairs of the device together (score, then token, then expert)
             tt, ee = np.nonzero(cand)
-            order = np.lexsort((toks[tt], cols[ee], -dev.scores[toks[tt], cols[ee]].astype(np.float64)))
+            order = np.lexsort((cols[ee], toks[tt], -dev.scores[toks[tt], cols[ee]].astype(np.float64)))
             expect = np.zeros_like(kept)
             expect[tt[order[:budget]], ee[order[:budget]]] = True
             np.testing.assert_array_equal(kept, expect)
@@ -511,6 +511,97 @@ def test_device_level_capacity(orc, mode, scope_dev, scope_exp):
     np.testing.assert_array_equal(one_d.keep, one_e.keep)
     assert orc.device_budget(1.0, 2048, 8, 128, 16) == 16 * 128 and orc.device_budget(1.3, 128, 2, 8, 2) == 83
     assert orc.device_budget(math.inf, 64, 2, 8, 4) == 256 and orc.device_budget(0.0, 64, 2, 8, 4) == 0
+
+
+def test_device_level_tie_rule(orc):
+    """Equal scores under a shared budget: the lower token goes first, then the lower expert."""
+    # 4 tokens, 2 experts on one device, k = 2: every score is exactly 1/2, 8 tied candidate pairs
+    logits = np.zeros((4, 2), np.float32)
+    for gamma, expect in [(0.75, [[1, 1], [1, 1], [1, 1], [0, 0]]),      # budget 6
+                          (0.625, [[1, 1], [1, 1], [1, 0], [0, 0]]),     # budget 5
+                          (0.125, [[1, 0], [0, 0], [0, 0], [0, 0]])]:    # budget 1
+        r = orc.route_and_drop(logits, 2, 1, TD, 3, gamma)
+        assert r.cap == int(gamma * 8)
+        np.testing.assert_array_equal(r.keep, np.array(expect, np.uint8))
+
+
+# ----------------------------------------------------------------------------
+# over-selection (top-(k+m) candidates) and the "w/ max" constraint (Sec. 4 "Expanded Drop", Sec. 5.2
+# "Effectiveness of Expanded Drop", appendix "Maximum Number of Selected Experts")
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("n,e,k,m,gamma", [(128, 16, 2, 4, 1.0), (96, 12, 2, 6, 0.5), (64, 8, 2, 6, 1.5), (160, 32, 4, 8, 1.0)])
+def test_overselection(orc, n, e, k, m, gamma):
+    logits = small_logits(n, e, 900 + n + m, 1.5)
+    scores = orc.softmax_scores(logits)
+    r = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma, overselect=m)
+    # candidates: the k+m highest scores of every token (brute force by a full sort)
+    rank = np.argsort(np.argsort(-scores.astype(np.float64), axis=1, kind="stable"), axis=1, kind="stable")
+    np.testing.assert_array_equal(r.cand.astype(bool), rank < k + m)
+    # the capacity is still the model's C = gamma * N * k / E, not (k+m)
+    cap = min(n, int(gamma * (n * k) / e))
+    assert r.cap == cap
+    # every expert keeps its cap best candidates: the dense derivation with k+m columns selected but cap from k
+    masked = np.where(rank < k + m, scores.astype(np.float64), -1.0)
+    for j in range(e):
+        order = np.argsort(-masked[:, j], kind="stable")[:cap]
+        expect = np.zeros(n, bool)
+        expect[order] = True
+        np.testing.assert_array_equal(r.keep[:, j].astype(bool), expect & (rank[:, j] < k + m))
+    base = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma)
+    # a wider pool can only fill experts further (load = min(candidates, cap))
+    assert (r.keep.sum(0) >= base.keep.sum(0)).all() and r.keep.sum() > base.keep.sum()
+    assert r.keep.sum(1).max() > k                       # "some tokens may select more than k experts"
+    # m = 0 is the plain method; m = E - k makes every expert a candidate of every token (same as k = E candidates)
+    zero = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma, overselect=0)
+    np.testing.assert_array_equal(zero.keep, base.keep)
+    full = orc.route_and_drop(logits, k, 1, TD, GLOBAL, gamma, overselect=e - k)
+    expect = np.zeros((n, e), np.uint8)
+    for j in range(e):
+        expect[np.argsort(-scores[:, j].astype(np.float64), kind="stable")[:cap], j] = 1
+    np.testing.assert_array_equal(full.keep, expect)
+    # Expanded Drop on one device already has every expert as a candidate: over-selection changes nothing
+    ed = orc.route_and_drop(logits, k, 1, ED, GLOBAL, gamma)
+    ed_m = orc.route_and_drop(logits, k, 1, ED, GLOBAL, gamma, overselect=m)
+    np.testing.assert_array_equal(ed.keep, ed_m.keep)
+
+
+@pytest.mark.parametrize("mode,g,m", [(ED, 4, 0), (TD, 1, 6), (ED, 2, 4)])
+def test_max_k_experts_per_token(orc, mode, g, m):
+    n, e, k, gamma = 128, 16, 2, 1.0
+    logits = small_logits(n, e, 950 + g + m, 1.0)
+    free = orc.route_and_drop(logits, k, g, mode, LOCAL, gamma, overselect=m)
+    lim = orc.route_and_drop(logits, k, g, mode, LOCAL, gamma, overselect=m, max_experts=True)
+    assert free.keep.sum(1).max() > k                    # the constraint binds somewhere
+    assert lim.keep.sum(1).max() == k
+    np.testing.assert_array_equal(lim.cand, free.cand)
+    changed = 0
+    for t in range(n):
+        kept = np.flatnonzero(free.keep[t])
+        if len(kept) <= k:
+            np.testing.assert_array_equal(lim.keep[t], free.keep[t])
+            continue
+        changed += 1
+        # brute force: the k surviving experts with the highest score stay
+        best = kept[np.argsort(-free.scores[t, kept].astype(np.float64), kind="stable")[:k]]
+        expect = np.zeros(e, np.uint8)
+        expect[best] = 1
+        np.testing.assert_array_equal(lim.keep[t], expect)
+    assert changed > 0
+    # no refill: an expert never holds more than before
+    assert (lim.keep.sum(0) <= free.keep.sum(0)).all()
+    # plain Token Drop never exceeds k experts per token: the constraint is a no-op
+    a = orc.route_and_drop(logits, k, g, TD, LOCAL, gamma)
+    b = orc.route_and_drop(logits, k, g, TD, LOCAL, gamma, max_experts=True)
+    np.testing.assert_array_equal(a.keep, b.keep)
+    # the plan of the constrained run is canonical: rows = kept pairs, at most k slots used per token
+    assert lim.plan.rows == lim.keep.sum() and ((lim.plan.pair_row >= 0).sum(1) <= k).all()
+
+
+def test_max_k_tie_goes_to_lower_expert(orc):
+    # one device, 3 experts, k = 1, Expanded Drop, no capacity limit: a token survives at all three experts
+    logits = np.array([[0.0, 0.0, 0.0], [0.0, 1.0, 1.0]], np.float32)
+    r = orc.route_and_drop(logits, 1, 1, ED, GLOBAL, math.inf, max_experts=True)
+    np.testing.assert_array_equal(r.keep, np.array([[1, 0, 0], [0, 1, 0]], np.uint8))
 
 
 # ----------------------------------------------------------------------------
