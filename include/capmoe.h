@@ -64,7 +64,7 @@ typedef struct {
                                MOE_SCOPE_LOCAL_DEVICE / MOE_SCOPE_GLOBAL_DEVICE: one budget for the E/G
                                experts of a device, N_1 + ... + N_nl <= n_l * gamma * N_bar (Sec. 5.2): all
                                candidate pairs of the device's experts are ranked together (equal rank:
-                               lower expert id, then lower token); the paper states the constraint, the
+                               lower token, then lower expert id); the paper states the constraint, the
                                ranking rule is this library's reading.                               */
     double gamma;           /* capacity factor, >= 0 or +infinity (Sec. 4)                           */
     int32_t dtype;          /* MOE_DTYPE_*: type of x, expert weights, xp, yp, y.  The router
@@ -72,6 +72,15 @@ typedef struct {
     int32_t metric;         /* MOE_METRIC_*: SCORE keeps the highest gating scores (the paper's choice),
                                ORDER the earliest tokens, REVERSE_ORDER the latest, RANDOM a uniform
                                draw per pair; 0 = SCORE                                              */
+    int32_t overselect;     /* m >= 0: every token offers itself to its top-(k+m) experts instead of its
+                               top-k (over-selection ratio m of Sec. 5.2, "Effectiveness of Expanded
+                               Drop"; m = 2k, 3k in the appendix "Maximum Number of Selected Experts").
+                               The capacity keeps using k.  k + m <= min(E, 64).  topk_idx and
+                               topk_score are then [N, k+m].  0 = the plain method                  */
+    int32_t max_experts;    /* 1 = "w/ max" of that appendix: after the drop a token keeps at most k of
+                               its surviving experts, those with the highest gating score (equal
+                               scores: lower expert id); places this frees are not refilled.
+                               0 = no limit (the paper's choice)                                     */
 } moe_desc_t;
 
 const char* moe_status_string(int status);
@@ -81,7 +90,8 @@ const char* moe_status_string(int status);
  *   cap             capacity of one segment: min(Ns, trunc(gamma * (Ns*k) / E)), Ns = N (GLOBAL) or
  *                   N/G (LOCAL); Ns for MOE_MODE_NONE or gamma = +inf.  (Sec. 4; Alg. 1)
  *                   Device scopes: the device budget min(Ns*E/G, trunc(gamma * (Ns*k*E/G) / E)).
- *   slots_per_token S = k, or k + E/G for Expanded Drop (a token may keep up to k+m experts, Sec. 4)
+ *   slots_per_token S = k + overselect, plus E/G for Expanded Drop (a token may keep up to k+m experts,
+ *                   Sec. 4)
  *   max_rows        P_max, an upper bound on surviving token-expert pairs: size xp, yp, row_token,
  *                   row_weight for this many rows
  *   workspace_bytes enough for any single call of this descriptor
@@ -98,8 +108,8 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
  *   scores       [N,E] fp32 out: softmax over experts, computed in fp32 by a fixed operation
  *                sequence (max, exp by range reduction and a degree-7 polynomial, ascending sum,
  *                IEEE division), so equal logits give bit-equal scores
- *   topk_idx     [N,k] int32 out, topk_score [N,k] fp32 out: best first; equal scores go to the
- *                lower expert id
+ *   topk_idx     [N,k'] int32 out, topk_score [N,k'] fp32 out, k' = k + desc->overselect: best first;
+ *                equal scores go to the lower expert id
  * Logits must be finite.
  */
 int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
@@ -108,8 +118,8 @@ int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router,
 
 /*
  * Capacity enforcement: Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop (Alg. 2), or none.
- * Candidates of token t: its top-k experts; Expanded Drop adds the E/G experts of the token's own
- * device.  In every capacity segment (expert, or device-block x expert for LOCAL scope) the `cap`
+ * Candidates of token t: the k + overselect experts listed in topk_idx; Expanded Drop adds the E/G
+ * experts of the token's own device.  In every capacity segment (expert, or device-block x expert for LOCAL scope) the `cap`
  * candidates that rank highest under desc->metric (the gating score by default) are kept; equal rank
  * goes to the lower token index.
  * Outputs (the dispatch plan; B = G for the LOCAL scopes, 1 for the GLOBAL ones):
@@ -133,7 +143,7 @@ int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t
  *              Experts"): a candidate of a lower class (0..3) is dropped before any candidate of a
  *              higher class, whatever the metric says; "Image First" = image tokens 0, text tokens 1;
  *              NULL = "Uniform" (one class).
- *   seed       MOE_METRIC_RANDOM draws, for the pair (t, e), the 30 high bits of a 32-bit integer hash
+ *   seed       MOE_METRIC_RANDOM draws, for the pair (t, e), the 29 high bits of a 32-bit integer hash
  *              of the counter t*E + e offset by seed * 0x9E3779B9 (x ^= x>>16; x *= 0x7FEB352D;
  *              x ^= x>>15; x *= 0x846CA68B; x ^= x>>16): a counter-based generator, reproducible
  *              anywhere.  Ignored by the other metrics.
@@ -198,7 +208,8 @@ enum {
     MOE_KERNEL_FFN_GATE_UP = 7,
     MOE_KERNEL_FFN_DOWN = 8,
     MOE_KERNEL_COMBINE = 9,
-    MOE_KERNEL_COUNT = 10
+    MOE_KERNEL_DROP_LIMIT = 10, /* only launched with max_experts */
+    MOE_KERNEL_COUNT = 11
 };
 int moe_profile_attach(int kernel, void* start_event, void* stop_event);
 

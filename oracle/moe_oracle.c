@@ -181,7 +181,7 @@ void orc_candidates(const int32_t* topk_idx, int N, int E, int k, int G, int mod
  *   ORDER          earlier tokens are kept first (later ones are discarded once the
  *                  capacity is filled)
  *   REVERSE_ORDER  later tokens are kept first
- *   RANDOM         an independent uniform draw per pair: the 30 high bits of a 32-bit
+ *   RANDOM         an independent uniform draw per pair: the 29 high bits of a 32-bit
  *                  integer hash of (seed, t*E + e) - a counter-based generator, so that
  *                  any implementation draws the same numbers
  * Multimodal strategies (Sec. "Extension to Multimodal Mixture of Experts": "Image First",
@@ -228,7 +228,7 @@ static double orc_importance(const float* scores, int E, int t, int e, int metri
     switch (metric) {
         case ORC_METRIC_ORDER: return -(double)t;
         case ORC_METRIC_REVERSE_ORDER: return (double)t;
-        case ORC_METRIC_RANDOM: return (double)(orc_pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2);
+        case ORC_METRIC_RANDOM: return (double)(orc_pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 3);
         default: return (double)scores[(size_t)t * E + e];
     }
 }

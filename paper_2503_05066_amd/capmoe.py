@@ -28,6 +28,7 @@ class MoeDesc(ctypes.Structure):
         ("top_k", ctypes.c_int32), ("d_hidden", ctypes.c_int32), ("device_groups", ctypes.c_int32),
         ("mode", ctypes.c_int32), ("capacity_scope", ctypes.c_int32), ("gamma", ctypes.c_double),
         ("dtype", ctypes.c_int32), ("metric", ctypes.c_int32),
+        ("overselect", ctypes.c_int32), ("max_experts", ctypes.c_int32),
     ]
 
 
@@ -76,9 +77,10 @@ def status_string(status: int) -> str:
 
 
 def make_desc(n_tokens, d_model, n_experts, top_k, d_hidden, device_groups=1, mode=MODE_TOKEN_DROP,
-              capacity_scope=SCOPE_LOCAL, gamma=1.0, dtype=DTYPE_BF16, metric=METRIC_SCORE) -> MoeDesc:
+              capacity_scope=SCOPE_LOCAL, gamma=1.0, dtype=DTYPE_BF16, metric=METRIC_SCORE, overselect=0,
+              max_experts=0) -> MoeDesc:
     return MoeDesc(n_tokens, d_model, n_experts, top_k, d_hidden, device_groups, mode, capacity_scope,
-                   float(gamma), dtype, metric)
+                   float(gamma), dtype, metric, overselect, int(max_experts))
 
 
 def _ptr(t):
@@ -155,7 +157,7 @@ def moe_combine(desc, yp, row_weight, pair_row, y, stream=None):
 
 
 KERNELS = ("router_logits", "softmax_topk", "drop_prepare", "drop_select", "drop_emit", "dispatch", "ffn_schedule",
-           "ffn_gate_up", "ffn_down", "combine")
+           "ffn_gate_up", "ffn_down", "combine", "drop_limit")
 
 
 def moe_profile_attach(kernel: int, start_event=None, stop_event=None):
@@ -177,7 +179,7 @@ class LayerBuffers:
 
         self.desc = desc
         self.cap, self.slots, self.max_rows, self.workspace_bytes = moe_query(desc)
-        n, e, k, d = desc.n_tokens, desc.n_experts, desc.top_k, desc.d_model
+        n, e, k, d = desc.n_tokens, desc.n_experts, desc.top_k + desc.overselect, desc.d_model
         blocks = desc.device_groups if desc.capacity_scope in (SCOPE_LOCAL, SCOPE_LOCAL_DEVICE) else 1
         act = torch.bfloat16 if desc.dtype == DTYPE_BF16 else torch.float32
         rows = max(self.max_rows, 1)

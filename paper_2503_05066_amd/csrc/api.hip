@@ -11,15 +11,16 @@ int validate(const moe_desc_t* d) {
     if (d->n_tokens < 0 || d->d_model < 1 || d->n_experts < 1 || d->top_k < 1 || d->d_hidden < 1 ||
         d->device_groups < 1)
         return MOE_ERR_INVALID_ARG;
-    if (d->top_k > d->n_experts) return MOE_ERR_INVALID_ARG;
+    if (d->overselect < 0 || (d->max_experts != 0 && d->max_experts != 1)) return MOE_ERR_INVALID_ARG;
+    if ((int64_t)d->top_k + d->overselect > d->n_experts) return MOE_ERR_INVALID_ARG;
     if (d->n_tokens % d->device_groups != 0 || d->n_experts % d->device_groups != 0) return MOE_ERR_INVALID_ARG;
     if (d->mode < MOE_MODE_NONE || d->mode > MOE_MODE_EXPANDED_DROP) return MOE_ERR_INVALID_ARG;
     if (d->capacity_scope < MOE_SCOPE_LOCAL || d->capacity_scope > MOE_SCOPE_GLOBAL_DEVICE) return MOE_ERR_INVALID_ARG;
     if (d->dtype != MOE_DTYPE_F32 && d->dtype != MOE_DTYPE_BF16) return MOE_ERR_INVALID_ARG;
     if (d->metric < MOE_METRIC_SCORE || d->metric > MOE_METRIC_RANDOM) return MOE_ERR_INVALID_ARG;
     if (std::isnan(d->gamma) || d->gamma < 0.0) return MOE_ERR_INVALID_ARG;
-    if (d->n_experts > kMaxExperts || d->top_k > kMaxTopK) return MOE_ERR_UNSUPPORTED;
-    const int slots = d->top_k + (d->mode == MOE_MODE_EXPANDED_DROP ? d->n_experts / d->device_groups : 0);
+    if (d->n_experts > kMaxExperts || d->top_k + d->overselect > kMaxTopK) return MOE_ERR_UNSUPPORTED;
+    const int slots = d->top_k + d->overselect + (d->mode == MOE_MODE_EXPANDED_DROP ? d->n_experts / d->device_groups : 0);
     if (slots > 255) return MOE_ERR_UNSUPPORTED;
     if ((int64_t)d->n_tokens * d->n_experts >= (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
     if ((int64_t)d->n_tokens * slots >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
@@ -53,7 +54,8 @@ Sizes derive(const moe_desc_t& d) {
         else
             s.cap = (int)c;
     }
-    s.slots = d.top_k + (d.mode == MOE_MODE_EXPANDED_DROP ? s.group_experts : 0);
+    s.list_k = d.top_k + d.overselect;
+    s.slots = s.list_k + (d.mode == MOE_MODE_EXPANDED_DROP ? s.group_experts : 0);
     const int64_t by_tokens = (int64_t)d.n_tokens * (s.slots < d.n_experts ? s.slots : d.n_experts);
     const int64_t by_capacity = (int64_t)s.n_blocks * (d.n_experts / s.span) * s.cap;
     s.max_rows = by_tokens < by_capacity ? by_tokens : by_capacity;

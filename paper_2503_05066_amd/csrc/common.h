@@ -28,6 +28,7 @@ struct Sizes {
     int cap;           // capacity per segment (per expert, or per device for the device scopes)
     int span;          // experts that share one capacity: 1, or E/G for the device scopes
     int slots;         // S
+    int list_k;        // k + overselect: width of topk_idx
     int64_t max_rows;  // P_max
     int group_experts; // m = E / G
     int group_tokens;  // N / G

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
                 else if (metric == MOE_METRIC_REVERSE_ORDER)
                     rank = (uint32_t)local;
                 else if (metric == MOE_METRIC_RANDOM)
-                    rank = pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 2;
+                    rank = pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 3;
                 else
                     rank = key_s[tl * ld + e];
                 key_s[tl * ld + e] = c ? cls + rank + 1u : 0u;
@@ -143,7 +143,7 @@ constexpr int kSelectCache = 16384;  // keys of a segment kept in LDS (64 KB); l
 // capacity is a device budget) over seg_tokens tokens.  The keys of expert e0+r form run r.
 // Outputs, per (block, expert): the threshold, how many keys equal to it survive, the kept count.
 // Several experts under one budget share the threshold; the keys equal to it are granted to the
-// lower expert ids first (inside an expert, the emit kernel grants them to the lower tokens).
+// lower tokens first and, inside a token, to the lower expert ids.
 __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __restrict__ key_t,
                                                           uint32_t* __restrict__ seg_tau,
                                                           int32_t* __restrict__ seg_need,
@@ -223,11 +223,11 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         return;
     }
     // per expert: keys above the threshold and keys equal to it (a thread's keys change run rarely)
-    {
+    auto count_runs = [&](int tie_token, int tie_run) {
         int run = -1, gt = 0, eq = 0;
         for (int i = tid; i < n_keys; i += 256) {
-            const int r = i / seg_tokens;
-            const uint32_t kx = cached ? cache[i] : keys[(size_t)r * N + (i - r * seg_tokens)];
+            const int r = i / seg_tokens, tl = i - r * seg_tokens;
+            const uint32_t kx = cached ? cache[i] : keys[(size_t)r * N + tl];
             if (r != run) {
                 if (gt) atomicAdd(&gt_s[run], gt);
                 if (eq) atomicAdd(&eq_s[run], eq);
@@ -235,22 +235,50 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
                 gt = eq = 0;
             }
             gt += kx > tau;
-            eq += kx == tau && kx != 0u;
+            eq += kx == tau && kx != 0u && (tl < tie_token || (tl == tie_token && r <= tie_run));
         }
         if (gt) atomicAdd(&gt_s[run], gt);
         if (eq) atomicAdd(&eq_s[run], eq);
-    }
+    };
+    count_runs(seg_tokens, span);  // every key equal to the threshold
     __syncthreads();
-    if (tid == 0) {
-        int left = rem;
-        for (int r = 0; r < span; ++r) {
-            const int take = eq_s[r] < left ? eq_s[r] : left;
-            left -= take;
-            const int seg = b * E + e0 + r;
-            seg_tau[seg] = tau;
-            seg_need[seg] = take;
-            seg_count[seg] = gt_s[r] + take;
+    int eq_total = 0;
+    for (int r = 0; r < span; ++r) eq_total += eq_s[r];
+    if (eq_total > rem) {
+        // More keys equal the threshold than the budget has room for: they are granted in
+        // (token, expert) order.  A thread owns a run of consecutive tokens; the thread in whose
+        // run the budget ends finds the last granted pair (token tie_token, expert run tie_run).
+        __shared__ int sh_tie_token, sh_tie_run;
+        const int per = (seg_tokens + 255) / 256;
+        const int tb = tid * per < seg_tokens ? tid * per : seg_tokens;
+        const int te = tb + per < seg_tokens ? tb + per : seg_tokens;
+        auto key_at = [&](int r, int tl) { return cached ? cache[r * seg_tokens + tl] : keys[(size_t)r * N + tl]; };
+        int c = 0;
+        for (int tl = tb; tl < te; ++tl)
+            for (int r = 0; r < span; ++r) c += key_at(r, tl) == tau;
+        int total;
+        const int before = block_exclusive_scan_256(c, red, &total);
+        if (before < rem && rem <= before + c) {  // exactly one thread: 1 <= rem < eq_total = total
+            int left = rem - before;
+            for (int tl = tb; tl < te && left > 0; ++tl)
+                for (int r = 0; r < span && left > 0; ++r)
+                    if (key_at(r, tl) == tau && --left == 0) {
+                        sh_tie_token = tl;
+                        sh_tie_run = r;
+                    }
         }
+        __syncthreads();
+        const int tie_token = sh_tie_token, tie_run = sh_tie_run;
+        for (int r = tid; r < span; r += 256) gt_s[r] = eq_s[r] = 0;
+        __syncthreads();
+        count_runs(tie_token, tie_run);
+        __syncthreads();
+    }
+    if (tid < span) {
+        const int seg = b * E + e0 + tid;
+        seg_tau[seg] = tau;
+        seg_need[seg] = eq_s[tid];  // inside an expert the granted keys are its first ones in token order
+        seg_count[seg] = gt_s[tid] + eq_s[tid];
     }
 }
 
@@ -360,6 +388,66 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// 4. at most k experts per token (optional; appendix "Maximum Number of Selected Experts")
+// ---------------------------------------------------------------------------------------------
+constexpr int kLimitTokens = 64;
+
+// Runs after a first emit.  A thread owns a token: it lists the token's surviving pairs, ranks them
+// by gating score (equal scores: lower expert id first) and removes those ranked k-th or worse.
+// Keys of every pair that does not survive (dropped by capacity, or removed here) become 0, the
+// per-segment counts are lowered, and thresholds are reset so that a second emit keeps exactly the
+// non-zero keys.
+__global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* __restrict__ scores,
+                                                                  uint32_t* __restrict__ key_t,
+                                                                  int32_t* __restrict__ pair_row,
+                                                                  uint32_t* __restrict__ seg_tau,
+                                                                  int32_t* __restrict__ seg_need,
+                                                                  int32_t* __restrict__ seg_count, int N, int E, int S,
+                                                                  int k, int seg_tokens, int segs) {
+    extern __shared__ uint32_t lim[];  // [S][64] score bits, then [S][64] expert | slot << 16
+    uint32_t* sc = lim;
+    uint32_t* es = lim + (size_t)S * kLimitTokens;
+    const int lane = threadIdx.x;
+    const int gtid = blockIdx.x * kLimitTokens + lane;
+    for (int i = gtid; i < segs; i += gridDim.x * kLimitTokens) {
+        seg_tau[i] = 0u;
+        seg_need[i] = 0;
+    }
+    const int t = gtid;
+    if (t >= N) return;
+    int n = 0, slot = 0;
+    for (int e = 0; e < E; ++e) {
+        const size_t at = (size_t)e * N + t;
+        if (key_t[at] == 0u) continue;
+        if (pair_row[(size_t)t * S + slot] >= 0) {
+            sc[n * kLimitTokens + lane] = __float_as_uint(scores[(size_t)t * E + e]);
+            es[n * kLimitTokens + lane] = (uint32_t)e | ((uint32_t)slot << 16);
+            ++n;
+        } else {
+            key_t[at] = 0u;  // dropped by the capacity
+        }
+        ++slot;
+    }
+    if (n <= k) return;
+    const int b = t / seg_tokens;
+    for (int i = 0; i < n; ++i) {
+        const uint32_t si = sc[i * kLimitTokens + lane];
+        int better = 0;  // surviving pairs ahead of pair i: higher score, or equal score and listed earlier (lower id)
+        for (int j = 0; j < n; ++j) {
+            const uint32_t sj = sc[j * kLimitTokens + lane];
+            better += sj > si || (sj == si && j < i);
+        }
+        if (better >= k) {
+            const uint32_t v = es[i * kLimitTokens + lane];
+            const int e = (int)(v & 0xffffu), sl = (int)(v >> 16);
+            key_t[(size_t)e * N + t] = 0u;
+            pair_row[(size_t)t * S + sl] = -1;
+            atomicSub(&seg_count[b * E + e], 1);
+        }
+    }
+}
+
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
                                 const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
                                 int32_t* expert_count, int32_t* seg_count,
@@ -374,7 +462,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
                                       (int)lds);
         ProfileScope prof(MOE_KERNEL_DROP_PREPARE, st);
         hipLaunchKernelGGL(drop_prepare_kernel, dim3(grid), dim3(256), lds, st, scores, topk_idx, ws.key_t, ws.slot_t,
-                           pair_row, N, E, d.top_k, s.slots, d.mode == MOE_MODE_EXPANDED_DROP ? 1 : 0, s.group_tokens,
+                           pair_row, N, E, s.list_k, s.slots, d.mode == MOE_MODE_EXPANDED_DROP ? 1 : 0, s.group_tokens,
                            s.group_experts, d.metric, s.seg_tokens > 0 ? s.seg_tokens : 1, token_class, seed);
     }
     const int segs = s.n_blocks * E;
@@ -391,11 +479,26 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         hipLaunchKernelGGL(drop_select_kernel, dim3(segs / s.span), dim3(256), lds, st, ws.key_t, ws.seg_tau,
                            ws.seg_need, seg_count, N, E, s.seg_tokens, s.span, s.cap);
     }
-    {
+    auto emit = [&]() {
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
         hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
                            ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
                            s.n_blocks, s.seg_tokens, s.slots, d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
+    };
+    emit();
+    if (d.max_experts && s.slots > d.top_k && N > 0) {
+        // the first plan tells which pairs survive the capacity; trim every token to k of them, emit again
+        const size_t lds = (size_t)s.slots * kLimitTokens * 8;
+        if (lds > 64 * 1024)
+            (void)hipFuncSetAttribute((const void*)drop_limit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)lds);
+        {
+            ProfileScope prof(MOE_KERNEL_DROP_LIMIT, st);
+            hipLaunchKernelGGL(drop_limit_kernel, dim3((N + kLimitTokens - 1) / kLimitTokens), dim3(kLimitTokens), lds,
+                               st, scores, ws.key_t, pair_row, ws.seg_tau, ws.seg_need, seg_count, N, E, s.slots,
+                               d.top_k, s.seg_tokens, segs);
+        }
+        emit();
     }
     return hipGetLastError();
 }

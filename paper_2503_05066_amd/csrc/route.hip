@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
 hipError_t launch_softmax_topk(const moe_desc_t& d, float* logits, const float* partial, int ksplit, const float* bias,
                                float* scores, int32_t* topk_idx, float* topk_score, hipStream_t st) {
     ProfileScope prof(MOE_KERNEL_SOFTMAX_TOPK, st);
-    const int N = d.n_tokens, E = d.n_experts, k = d.top_k;
+    const int N = d.n_tokens, E = d.n_experts, k = d.top_k + d.overselect;
     int grid = (N + 3) / 4;
     if (grid > 2048) grid = 2048;
     const int epl = (E + kWave - 1) / kWave;

@@ -33,8 +33,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_descriptor_layout_matches_header():
-    # 8 int32, one double at offset 32, two int32: 48 bytes
-    assert ctypes.sizeof(capmoe.MoeDesc) == 48 and capmoe.MoeDesc.gamma.offset == 32
+    # 8 int32, one double at offset 32, four int32: 56 bytes
+    assert ctypes.sizeof(capmoe.MoeDesc) == 56 and capmoe.MoeDesc.gamma.offset == 32
+    assert capmoe.MoeDesc.overselect.offset == 48 and capmoe.MoeDesc.max_experts.offset == 52
 
 
 @pytest.mark.parametrize("name,mode,scope,gamma,cap,slots,rows", [
@@ -61,6 +62,20 @@ def test_query_sizes(orc, name, mode, scope, gamma, cap, slots, rows):
     assert got[3] > 0
 
 
+def test_overselection_sizes(orc):
+    w = synth.WORKLOADS["olmoe"]
+    for mode, g, m, slots in [(1, 1, 16, 24), (2, 8, 8, 24), (0, 1, 24, 32)]:
+        d = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, g, mode, 0, 1.0, w.dtype,
+                             overselect=m, max_experts=1)
+        cap, s, rows, _ = capmoe.moe_query(d)
+        assert s == slots == orc.slots_per_token(w.top_k, w.n_experts, g, mode, m)
+        # the capacity keeps using the model's k
+        assert cap == (w.n_tokens // g if mode == 0 else orc.capacity(1.0, w.n_tokens // g, w.top_k, w.n_experts))
+    with pytest.raises(capmoe.CapMoeError) as ei:
+        capmoe.moe_query(capmoe.make_desc(1024, 64, 128, 40, 128, overselect=30))   # k + m > 64
+    assert ei.value.status == 2
+
+
 def test_capacity_truncation_matches_oracle(orc):
     for gamma in (1.3, 0.7, 1.1, 2.5, 0.05, 0.999):
         for n, k, e, g in [(128, 2, 8, 1), (120, 3, 12, 4), (96, 5, 16, 2)]:
@@ -81,6 +96,9 @@ def test_bad_arguments_are_refused_on_the_host():
         capmoe.make_desc(128, 64, 8, 2, 128, dtype=5),
         capmoe.make_desc(128, 0, 8, 2, 128),
         capmoe.make_desc(128, 64, 8, 2, 128, metric=4),
+        capmoe.make_desc(128, 64, 8, 2, 128, overselect=-1),
+        capmoe.make_desc(128, 64, 8, 2, 128, overselect=7),    # k + m > E
+        capmoe.make_desc(128, 64, 8, 2, 128, max_experts=2),
     ]
     for d in bad:
         with pytest.raises(capmoe.CapMoeError) as ei:

@@ -44,12 +44,14 @@ def route_and_drop_gpu(desc, logits_host, token_class=None, seed=0):
     return buf
 
 
-def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what, metric=0, token_class=None, seed=0):
+def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what, metric=0, token_class=None, seed=0,
+                         overselect=0, max_experts=False):
     note("case", what, dict(n=n, e=e, k=k, g=g, mode=mode, scope=scope, gamma=gamma, metric=metric, seed=seed,
-                            classes=token_class is not None))
-    desc = capmoe.make_desc(n, 64, e, k, 128, g, mode, scope, gamma, synth.DTYPE_F32, metric)
+                            classes=token_class is not None, overselect=overselect, max_experts=max_experts))
+    desc = capmoe.make_desc(n, 64, e, k, 128, g, mode, scope, gamma, synth.DTYPE_F32, metric, overselect,
+                            int(max_experts))
     buf = route_and_drop_gpu(desc, logits, token_class, seed)
-    ref = orc.route_and_drop(logits, k, g, mode, scope, gamma, metric, token_class, seed)
+    ref = orc.route_and_drop(logits, k, g, mode, scope, gamma, metric, token_class, seed, overselect, max_experts)
     assert buf.cap == ref.cap
     np.testing.assert_array_equal(buf.scores.cpu().numpy().view(np.uint32), ref.scores.view(np.uint32))
     np.testing.assert_array_equal(buf.topk_idx.cpu().numpy(), ref.topk_idx)
@@ -207,6 +209,49 @@ def test_device_level_ties(orc):
     check_route_and_plan(orc, flat, 512, 16, 2, 4, ED, GLOBAL_DEV, 0.5, "device ties flat")
 
 
+# ------------------------------------------------------------------------------------------------
+# over-selected candidate lists and at most k experts per token (appendix "Maximum Number of Selected Experts")
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,mode,scope,gamma,m_factor,limit", [
+    ("olmoe", TD, LOCAL, 1.0, 2, False), ("olmoe", TD, LOCAL, 1.0, 2, True), ("olmoe", TD, LOCAL, 1.0, 3, True),
+    ("olmoe", NONE, LOCAL, 1.0, 2, True), ("mixtral", ED, LOCAL, 1.0, 0, True), ("mixtral", TD, GLOBAL, 1.0, 2, True),
+    ("finegrained", ED, LOCAL, 1.0, 0, True), ("finegrained", ED, LOCAL, 1.25, 1, True),
+    ("finegrained", TD, LOCAL_DEV, 1.0, 2, True), ("decode", ED, LOCAL, 1.0, 2, True),
+    ("decode", TD, GLOBAL_DEV, 1.0, 3, False),
+])
+def test_plan_overselection_and_max_k(orc, name, mode, scope, gamma, m_factor, limit):
+    w = W[name]
+    if name not in _logit_cache:
+        _logit_cache[name] = oracle_logits(orc, w)
+    m = m_factor * w.top_k
+    buf, ref = check_route_and_plan(orc, _logit_cache[name], w.n_tokens, w.n_experts, w.top_k, w.device_groups, mode,
+                                    scope, gamma, f"{name} overselect {m} limit {limit}", 0, None, 0, m, limit)
+    per_token = ref.keep.sum(1)
+    if limit:
+        assert per_token.max() <= w.top_k
+    elif mode != NONE:
+        assert per_token.max() > w.top_k
+
+
+def test_max_k_edge_cases(orc):
+    flat = np.zeros((256, 16), np.float32)      # every score equal: expert ids and token order decide everything
+    check_route_and_plan(orc, flat, 256, 16, 2, 4, ED, LOCAL, 2.0, "max-k flat", 0, None, 0, 4, True)
+    check_route_and_plan(orc, flat, 256, 16, 2, 1, TD, GLOBAL, math.inf, "max-k flat no cap", 0, None, 0, 14, True)
+    w = synth.scaled(W["olmoe"], n_tokens=2048, n_experts=32, top_k=4, device_groups=4)
+    ties = synth.logits_with_ties(w)
+    for mode, scope in [(ED, LOCAL), (ED, GLOBAL), (TD, LOCAL_DEV)]:
+        check_route_and_plan(orc, ties, 2048, 32, 4, 4, mode, scope, 1.0, "max-k ties", 0, None, 0, 8, True)
+    # other metrics rank the drop, the gating score still ranks which k experts a token keeps
+    cls = (np.arange(2048) % 3 == 0).astype(np.uint8)
+    check_route_and_plan(orc, ties, 2048, 32, 4, 4, ED, LOCAL, 0.75, "max-k order metric", 1, cls, 0, 4, True)
+    check_route_and_plan(orc, ties, 2048, 32, 4, 4, ED, LOCAL, 0.75, "max-k random metric", 3, None, 11, 4, True)
+    # a ragged token count and the largest candidate lists
+    rng = np.random.default_rng(5)
+    lg = rng.standard_normal((77, 64)).astype(np.float32)
+    check_route_and_plan(orc, lg, 77, 64, 8, 1, TD, GLOBAL, 1.0, "max-k wide lists", 0, None, 0, 56, True)
+    check_route_and_plan(orc, lg[:3], 3, 64, 8, 1, ED, GLOBAL, math.inf, "max-k three tokens", 0, None, 0, 8, True)
+
+
 def test_random_metric_ties_and_seeds(orc):
     n, e = 1024, 8
     logits = np.zeros((n, e), np.float32)           # all scores equal: only the draws decide
@@ -261,12 +306,14 @@ def run_layer(layer: DeviceLayer, desc, logits_host=None):
     return buf
 
 
-def check_layer(orc, layer, mode, scope, gamma, tokens=None, what=""):
+def check_layer(orc, layer, mode, scope, gamma, tokens=None, what="", overselect=0, max_experts=False):
     w = layer.w
-    note("layer", what, w.name, dict(mode=mode, scope=scope, gamma=gamma))
+    note("layer", what, w.name, dict(mode=mode, scope=scope, gamma=gamma, overselect=overselect, max_experts=max_experts))
     logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
-    ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma)
+    ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma, overselect=overselect,
+                             max_experts=max_experts)
     desc = layer.desc(mode, scope, gamma)
+    desc.overselect, desc.max_experts = overselect, int(max_experts)
     buf = run_layer(layer, desc, logits)
     assert_plan_equal(buf, ref, what)
     rows = ref.plan.rows
@@ -308,6 +355,9 @@ def test_layer_reduced_bf16(orc, n, d, e, k, h, g):
     for mode, scope, gamma in [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (ED, LOCAL, 1.0), (ED, GLOBAL, 1.5),
                                (TD, GLOBAL, 0.0)]:
         check_layer(orc, layer, mode, scope, gamma, what="reduced bf16")
+    if e >= 8:   # over-selected lists, with and without the limit of k experts per token
+        check_layer(orc, layer, TD, LOCAL, 1.0, what="reduced bf16 overselect", overselect=2 * k)
+        check_layer(orc, layer, ED, LOCAL, 1.0, what="reduced bf16 w/ max", overselect=k, max_experts=True)
 
 
 def test_ffn_ragged_expert_sizes(orc):

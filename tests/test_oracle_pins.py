@@ -417,7 +417,7 @@ def test_random_metric(orc):
         kept = toks[a.keep[toks, j] == 1]
         assert len(kept) == min(len(cand), a.cap)
         # brute force: the cap largest draws (ties to the lower token) among the candidates
-        draws = np.array([py_pair_hash(7, int(t) * e + j) >> 2 for t in cand])
+        draws = np.array([py_pair_hash(7, int(t) * e + j) >> 3 for t in cand])
         order = np.lexsort((cand, -draws))
         np.testing.assert_array_equal(np.sort(cand[order[:a.cap]]), kept)
     # every token has the same chance: the kept share does not depend on position or score
