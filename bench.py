@@ -43,12 +43,19 @@ def parse():
     p.add_argument("--scope", default="local", choices=list(SCOPES))
     p.add_argument("--gamma", type=float, default=1.0)
     p.add_argument("--metric", default="score", choices=list(METRICS), help="what ranks the tokens of a full expert")
+    p.add_argument("--overselect", type=int, default=0, help="m: candidate lists are top-(k+m) instead of top-k")
+    p.add_argument("--max-experts", action="store_true", help="at most k surviving experts per token (w/ max)")
+    p.add_argument("--tokens", type=int, default=0, help="override the workload's token count (batch x length sweeps)")
+    p.add_argument("--sweep-gamma", default="", help="comma list of capacity factors measured after the main line")
+    p.add_argument("--no-straggler", action="store_true",
+                   help="skip the per-device FFN timing (the one-GPU stand-in for the latency model of Eq. 4)")
+    p.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling probes (MFMA loop, device copy)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--unfused", action="store_true",
                    help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
-    p.add_argument("--others", default="mixtral:token,mixtral:expanded,mixtral:none,mixtral:token:local_device",
+    p.add_argument("--others", default="finegrained:expanded,finegrained:token,decode:token,decode:expanded,mixtral:none,mixtral:expanded,mixtral:token:local_device,mixtral:token",
                    help="comma list of workload:mode[:scope] measured after the main line ('' for none)")
     return p.parse_args()
 
@@ -63,8 +70,9 @@ def upload(w):
     import numpy as np
     import torch
 
-    if w.name in _uploaded:
-        return _uploaded[w.name]
+    key = (w.name, w.n_tokens)
+    if key in _uploaded:
+        return _uploaded[key]
     _uploaded.clear()
     torch.cuda.empty_cache()
 
@@ -87,7 +95,7 @@ def upload(w):
         t["w_gate"][j].copy_(dev(g))
         t["w_up"][j].copy_(dev(u))
         t["w_down"][j].copy_(dev(dn))
-    _uploaded[w.name] = t
+    _uploaded[key] = t
     return t
 
 
@@ -106,14 +114,14 @@ def algorithmic_work(w, S, rows, active, elem):
     }
 
 
-def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
+def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0, overselect=0, max_experts=0, per_kernel=True):
     import torch
 
     from paper_2503_05066_amd import capmoe, synth
 
     t = upload(w)
     desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
-                            gamma, w.dtype, metric)
+                            gamma, w.dtype, metric, overselect, max_experts)
     buf = capmoe.LayerBuffers(desc)
     K_GU = capmoe.KERNELS.index("ffn_gate_up")
 
@@ -138,10 +146,21 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
     capmoe.moe_profile_attach(K_GU, None, None)
     gu_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
 
+    # per-step durations (event pairs around whole steps), outside the timed region
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    step_ms = sorted(a.elapsed_time(b) for a, b in pairs)
+
     # per-kernel durations, one kernel at a time, outside the timed region
     kernel_ms = {}
     reps = max(5, min(steps, 20))
     for kid, name in enumerate(capmoe.KERNELS):
+        if not per_kernel or (name == "drop_limit" and not max_experts):
+            kernel_ms[name] = 0.0
+            continue
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for a, b in evs:
             a.record()
@@ -165,7 +184,7 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
     nbar = w.n_tokens * w.top_k / w.n_experts
     # load statistics of the paper's latency model (Eq. 4: the most loaded expert / device sets the pace)
     import numpy as np
-    before = np.bincount(buf.topk_idx.cpu().numpy().ravel(), minlength=w.n_experts)
+    before = np.bincount(buf.topk_idx[:, :w.top_k].cpu().numpy().ravel(), minlength=w.n_experts)
     g = w.device_groups
     dev_before = before.reshape(g, -1).sum(1)
     dev_after = counts.reshape(g, -1).sum(1)
@@ -173,7 +192,15 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
              "max_expert_load_over_mean_kept": float(counts.max() / nbar),
              "max_device_load_over_mean_topk": float(dev_before.max() / dev_before.mean()),
              "max_device_load_over_mean_kept": float(dev_after.max() / max(dev_after.mean(), 1e-9))}
+    pairs_topk = w.n_tokens * w.top_k
+    per_token = (buf.pair_row >= 0).sum(1)
+    # Eq. (11) evaluated on the loads before the drop, with the per-expert capacity gamma * N_bar
+    dt_eq11 = float(np.maximum(before - gamma * nbar, 0.0).sum() / before.sum()) if mode != 0 else 0.0
     res = {
+        "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0],
+        "dropped_ratio": 1.0 - rows / pairs_topk, "dt_eq11": dt_eq11,
+        "experts_per_token_mean": rows / max(w.n_tokens, 1), "experts_per_token_max": int(per_token.max()),
+        "tokens_without_expert": int((per_token == 0).sum()),
         "wall_s": wall, "ms_per_step": 1e3 * wall / steps, "tokens_per_s": w.n_tokens * steps / wall,
         "gate_up_ms": gu_ms, "kernel_ms": kernel_ms, "rows": rows, "active_experts": active, "cap": buf.cap,
         "max_rows": buf.max_rows, "work": work, "max_load_over_mean": float(counts.max() / nbar),
@@ -182,6 +209,98 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0):
     }
     del buf
     return res
+
+
+def per_device_ffn(w, mode, scope, gamma, reps=5, overselect=0, max_experts=0):
+    """Expert computation of every simulated device on its own: the device's E/G experts over the rows the
+    plan gives them, timed as separate launches of the layer's FFN.  In the paper's latency model
+    (Eq. 4) all devices wait for the slowest one, so max / mean of these times is the straggler effect
+    this plan would cause, and the maximum is what the drop shortens."""
+    import torch
+
+    from paper_2503_05066_amd import capmoe, synth
+
+    t = upload(w)
+    g, e = w.device_groups, w.n_experts
+    m = e // g
+    desc = capmoe.make_desc(w.n_tokens, w.d_model, e, w.top_k, w.d_hidden, g, mode, scope, gamma, w.dtype, 0,
+                            overselect, max_experts)
+    buf = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
+                         fused_dispatch=True)
+    torch.cuda.synchronize()
+    offs = buf.expert_offset.cpu().numpy()
+    # one device's share as a layer of its own: m experts, any of the N tokens may hold a row at each
+    sub = capmoe.make_desc(w.n_tokens, w.d_model, m, m, w.d_hidden, 1, synth.MODE_NONE, synth.SCOPE_GLOBAL, 1.0,
+                           w.dtype)
+    ws = torch.empty(max(capmoe.moe_query(sub)[3], 256), dtype=torch.uint8, device="cuda")
+    rows, ms = [], []
+    for dev in range(g):
+        r0, r1 = int(offs[dev * m]), int(offs[(dev + 1) * m])
+        rows.append(r1 - r0)
+        if r1 == r0:
+            ms.append(0.0)
+            continue
+        local_offset = (buf.expert_offset[dev * m:(dev + 1) * m + 1] - r0).contiguous()   # the device's own row numbering
+        args = (sub, t["x"], local_offset, buf.row_token[r0:], t["w_gate"][dev * m:(dev + 1) * m],
+                t["w_up"][dev * m:(dev + 1) * m], t["w_down"][dev * m:(dev + 1) * m], buf.yp[r0:], ws)
+        for _ in range(2):
+            capmoe.moe_dispatch_ffn(*args)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            capmoe.moe_dispatch_ffn(*args)
+            b.record()
+        torch.cuda.synchronize()
+        ms.append(sorted(a.elapsed_time(b) for a, b in evs)[reps // 2])
+    del buf, ws
+    mean_ms = sum(ms) / len(ms)
+    return {"per_device_rows": rows, "per_device_ffn_ms": [round(v, 4) for v in ms], "max_ms": round(max(ms), 4),
+            "mean_ms": round(mean_ms, 4), "max_over_mean_ms": round(max(ms) / max(mean_ms, 1e-9), 3),
+            "max_over_mean_rows": round(max(rows) / max(sum(rows) / len(rows), 1e-9), 3)}
+
+
+def straggler(w, mode, scope, gamma, overselect=0, max_experts=0):
+    from paper_2503_05066_amd import synth
+
+    base = per_device_ffn(w, synth.MODE_NONE, synth.SCOPE_LOCAL, 1.0)
+    drop = per_device_ffn(w, mode, scope, gamma, overselect=overselect, max_experts=max_experts)
+    return {"note": "expert FFN of each simulated device timed alone; Eq. 4: the slowest device sets the layer's pace",
+            "no_drop": base, "with_drop": drop,
+            "slowest_device_speedup": round(base["max_ms"] / max(drop["max_ms"], 1e-9), 3)}
+
+
+def measured_peaks():
+    """What this chip sustains: a register-only MFMA loop and a plain device copy (denominators beside the
+    published peaks)."""
+    import torch
+
+    from paper_2503_05066_amd import capmoe
+
+    sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    best = 0.0
+    for _ in range(3):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        flops = capmoe.moe_probe_mfma_bf16(2048, 4096, sink)
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, flops / (a.elapsed_time(b) * 1e-3) / 1e12)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    copy = 0.0
+    for _ in range(4):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        dst.copy_(src)
+        b.record()
+        torch.cuda.synchronize()
+        copy = max(copy, 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9)
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"mfma_bf16_TFLOPs": round(best, 1), "copy_GBs": round(copy, 1),
+            "how": "best of 3 launches of 2048 blocks x 4 waves x 4096 x 8 register-only MFMAs; best of 4 "
+                   "1 GiB device copies (read + written bytes)"}
 
 
 def roofline_of(work, ms):
@@ -229,9 +348,21 @@ def cpu_baseline(w, mode, scope, gamma):
         sample *= 4
     n_s = len(toks)
     est = t_route * n_s / w.n_tokens + t_ffn   # seconds for n_s tokens
-    return {"value": n_s / est, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+    # the same on one thread, on a sixteenth of the sample
+    threads = oracle.num_threads()
+    one = toks[:max(1, n_s // 16)]
+    oracle.set_num_threads(1)
+    t0 = time.perf_counter()
+    oracle.layer_output(x, ref.scores, ref.keep, tabs[0], tabs[1], tabs[2], token_list=one)
+    t_one = time.perf_counter() - t0
+    oracle.set_num_threads(threads)
+    # (routing and drop are serial except for the logits; their share is small either way)
+    single = len(one) / (t_route * len(one) / w.n_tokens + t_one)
+    return {"value": n_s / est, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "single_thread_tokens_per_s": round(single, 1),
             "sample": f"routing+drop on all {w.n_tokens} tokens ({t_route:.2f} s, prorated), expert FFN+combine on "
-                      f"{n_s} sampled tokens ({t_ffn:.2f} s)"}
+                      f"{n_s} sampled tokens ({t_ffn:.2f} s); single thread: FFN+combine on {len(one)} of them "
+                      f"({t_one:.2f} s)"}
 
 
 def main():
@@ -248,14 +379,19 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[a.workload]
+    if a.tokens:
+        w = synth.scaled(w, n_tokens=a.tokens)
     mode, scope = MODES[a.mode], SCOPES[a.scope]
-    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused, metric=METRICS[a.metric])
+    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused, metric=METRICS[a.metric],
+                overselect=a.overselect, max_experts=int(a.max_experts))
     primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
     primary["kernel"] = other["kernel"] = "ffn_gemm_bf16_kernel<..., SWIGLU> (gate/up GEMM + SwiGLU epilogue)"
-    primary["traffic"] = other["traffic"] = MEASURED_TRAFFIC.get((a.workload, a.mode, a.scope, a.gamma))
+    plain = not (a.tokens or a.overselect or a.max_experts or a.metric != "score" or a.unfused)
+    primary["traffic"] = other["traffic"] = (MEASURED_TRAFFIC.get((a.workload, a.mode, a.scope, a.gamma))
+                                             if plain else None)
     stages = {}
     km = r["kernel_ms"]
-    drop_ms = km["drop_prepare"] + km["drop_select"] + km["drop_emit"]
+    drop_ms = km["drop_prepare"] + km["drop_select"] + km["drop_emit"] + km["drop_limit"]
     for name, ms in [("router_logits", km["router_logits"]), ("softmax_topk", km["softmax_topk"]), ("drop", drop_ms),
                      ("dispatch", km["dispatch"]), ("ffn_gate_up", km["ffn_gate_up"]), ("ffn_down", km["ffn_down"]),
                      ("combine", km["combine"])]:
@@ -274,15 +410,30 @@ def main():
         "dtype": "bf16" if w.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n_tokens} d={w.d_model} E={w.n_experts} k={w.top_k} h={w.d_hidden} "
                                f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity, "
-                               f"{a.metric} metric",
+                               f"{a.metric} metric"
+                               + (f", top-(k+{a.overselect}) candidates" if a.overselect else "")
+                               + (", at most k experts per token" if a.max_experts else ""),
                    "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
                    "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
                    "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3), "loads": r["loads"],
+                   "dropped_ratio": round(r["dropped_ratio"], 4), "DT_eq11": round(r["dt_eq11"], 4),
+                   "experts_per_token_mean": round(r["experts_per_token_mean"], 3),
+                   "experts_per_token_max": r["experts_per_token_max"],
+                   "tokens_without_expert": r["tokens_without_expert"],
                    "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
                             "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"},
         "roofline": primary, "roofline_other_roof": other, "stages": stages,
         "kernel_ms": {k: round(v, 4) for k, v in km.items()},
+        "step_ms_median": round(r["step_ms_median"], 4), "step_ms_min": round(r["step_ms_min"], 4),
     }
+    if not a.no_peaks:
+        pk = measured_peaks()
+        out["measured_peaks"] = pk
+        for rf in (primary, other):
+            ceiling = pk["mfma_bf16_TFLOPs"] if rf["bound"] == "mfma" else pk["copy_GBs"]
+            rf["frac_of_measured_ceiling"] = round(rf["achieved"] / ceiling, 4)
+    if not a.no_straggler and w.device_groups > 1:
+        out["straggler"] = straggler(w, mode, scope, a.gamma, a.overselect, int(a.max_experts))
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, mode, scope, a.gamma)
     others = []
@@ -298,11 +449,30 @@ def main():
         p1, p2 = roofline_of(o["work"]["ffn_gate_up"], o["gate_up_ms"])
         d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
         others.append({"workload": name, "mode": m, "scope": osc, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
-                       "ms_per_step": o["ms_per_step"], "surviving_pairs": o["rows"], "cap": o["cap"],
+                       "ms_per_step": o["ms_per_step"], "step_ms_median": round(o["step_ms_median"], 4),
+                       "step_ms_min": round(o["step_ms_min"], 4), "dropped_ratio": round(o["dropped_ratio"], 4),
+                       "experts_per_token_mean": round(o["experts_per_token_mean"], 3),
+                       "surviving_pairs": o["rows"], "cap": o["cap"],
                        "max_segment_load": o["max_segment_load"], "loads": o["loads"], "ffn_gate_up": p1, "ffn_down": d1,
                        "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
     if others:
         out["other_workloads"] = others
+    if not a.no_straggler and w.device_groups == 1:
+        # the default workload has one device; show the latency model on the Mixtral-shaped one (4 devices x 2 experts)
+        names = {o["workload"] for o in others}
+        if "mixtral" in names:
+            out["straggler_mixtral"] = straggler(synth.WORKLOADS["mixtral"], MODES["token"], SCOPES["local"], a.gamma)
+    if a.sweep_gamma:
+        sweep = []
+        for gs in a.sweep_gamma.split(","):
+            gm = float(gs)
+            o = measure(w, mode if gm != float("inf") else MODES["none"], scope, gm, max(5, a.steps // 5),
+                        max(2, a.warmup // 5), fused=not a.unfused, metric=METRICS[a.metric], overselect=a.overselect,
+                        max_experts=int(a.max_experts), per_kernel=False)
+            sweep.append({"gamma": gm, "tokens_per_s": round(o["tokens_per_s"], 1), "ms_per_step": round(o["ms_per_step"], 4),
+                          "dropped_ratio": round(o["dropped_ratio"], 4), "DT_eq11": round(o["dt_eq11"], 4),
+                          "surviving_pairs": o["rows"], "loads": o["loads"]})
+        out["gamma_sweep"] = sweep
     if a.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)

@@ -213,6 +213,16 @@ enum {
 };
 int moe_profile_attach(int kernel, void* start_event, void* stop_event);
 
+/*
+ * Matrix-core ceiling probe (instrumentation, not part of the method): launches `blocks` workgroups of
+ * 4 wavefronts that each issue iterations * 8 independent bf16 MFMAs (32x32x16) on register operands.
+ *   sink   device, at least blocks * 256 floats (receives checksums)
+ *   flops  host, optional: floating-point operations of the launch, 2*32*32*16 per MFMA
+ * The caller times the launch; flops / time is what the matrix cores sustain with no memory traffic.
+ * blocks <= 65536, iterations <= 2^20.
+ */
+int moe_probe_mfma_bf16(int blocks, int iterations, float* sink, int64_t* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,11 @@ int orc_num_threads(void) {
 #endif
 }
 
+/* Number of host threads the parallel loops use from now on (timing only; results do not depend on it). */
+void orc_set_num_threads(int n) {
+    if (n >= 1) omp_set_num_threads(n);
+}
+
 /* ---------------------------------------------------------------------------
  * Router logits: the gate projection G(x) inside Eq. (1), `self.gate(x)` in Alg. 1 / Alg. 2.
  * logits[t,e] = sum_j x[t,j] * w[e,j] (+ bias[e]); summed in fp64, stored as fp32.

@@ -39,6 +39,8 @@ def _load():
         lib = ctypes.CDLL(build())
         i32, i64, dbl, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.orc_num_threads.restype = i32
+        lib.orc_set_num_threads.argtypes = [i32]
+        lib.orc_set_num_threads.restype = None
         lib.orc_router_logits.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         lib.orc_router_logits.restype = None
         lib.orc_softmax_scores.argtypes = [vp, i32, i32, vp]
@@ -75,6 +77,10 @@ def _c(a, dtype):
 
 def num_threads() -> int:
     return int(_load().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().orc_set_num_threads(int(n))
 
 
 def router_logits(x, w_router, bias=None):

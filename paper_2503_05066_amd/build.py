@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libcapmoe.so")
 
-SOURCES = ["api.hip", "route.hip", "router_mfma.hip", "drop.hip", "permute.hip", "ffn.hip"]
+SOURCES = ["api.hip", "route.hip", "router_mfma.hip", "drop.hip", "permute.hip", "ffn.hip", "probe.hip"]
 # the packed-fp32 feature is switched off for all device code; the router file must not contract
 # multiplies and adds (its softmax is a fixed sequence of individually rounded operations)
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

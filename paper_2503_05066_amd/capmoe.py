@@ -64,6 +64,8 @@ def load():
         lib.moe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_profile_attach.argtypes = [i32, vp, vp]
         lib.moe_profile_attach.restype = i32
+        lib.moe_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
+        lib.moe_probe_mfma_bf16.restype = i32
         for f in ("moe_query", "moe_route_topk", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
                   "moe_grouped_ffn",
                   "moe_dispatch_ffn", "moe_combine"):
@@ -169,6 +171,15 @@ def moe_profile_attach(kernel: int, start_event=None, stop_event=None):
             ev.record()
         return ctypes.c_void_p(ev.cuda_event)
     _check(load().moe_profile_attach(int(kernel), handle(start_event), handle(stop_event)), "moe_profile_attach")
+
+
+def moe_probe_mfma_bf16(blocks: int, iterations: int, sink, stream=None) -> int:
+    """Launch the matrix-core probe; returns the flops of the launch (the caller times it)."""
+    flops = ctypes.c_int64(0)
+    assert sink.numel() >= blocks * 256
+    _check(load().moe_probe_mfma_bf16(int(blocks), int(iterations), _ptr(sink), ctypes.byref(flops), _stream(stream)),
+           "moe_probe_mfma_bf16")
+    return int(flops.value)
 
 
 class LayerBuffers:
