@@ -15,8 +15,8 @@ constexpr int kWave = 64;
 
 // Tile heights of the expert GEMMs; the tile schedule in the workspace is built for these.
 constexpr int kFfnTileM = 256;      // bf16 MFMA kernels, compute-bound tiles
-constexpr int kFfnTileSmall = 64;   // bf16 MFMA kernels, tail of an expert with at most 128 rows left
-constexpr int kFfnSmallMax = 128;   // remainders up to this many rows are cut into small tiles
+constexpr int kFfnTileSmall = 64;   // bf16 MFMA kernels, tail of an expert with at most 64 rows left
+constexpr int kFfnSmallMax = 64;    // a remainder of up to this many rows is one small tile (larger: a partly filled big tile)
 constexpr int kFfnTileMF32 = 16;    // fp32 fallback kernels (tiny layers)
 
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
