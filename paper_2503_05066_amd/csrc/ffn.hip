@@ -425,17 +425,26 @@ struct TileConfig {
     else
         loop.template run<0>(acc);
 
-    // ---- epilogue: a lane holds, for activation row (lane & 31) of each 32-row sub-tile, output
-    // columns 8*q + 4*(lane/32) + v (q, v = 0..3) of each 32-column sub-tile ----
+    // ---- epilogue ----
+    // A lane holds, for activation row (lane & 31) of each 32-row sub-tile, output columns
+    // 8*q + 4*(lane/32) + v (q, v = 0..3) of each 32-column sub-tile: 8-byte runs scattered over 32 rows.
+    // Stored like that, a wave instruction touches 64 different cache lines, which costs up to a
+    // third of a short GEMM.  The tile is therefore transposed through LDS (free after the K loop: its
+    // last barrier follows the last operand read): bf16 rows of OUT_COLS columns, 16-byte piece p of
+    // row r at position p ^ (r mod PIECES) so that neither side has bank conflicts beyond the access
+    // width, then every row leaves as consecutive 16-byte pieces of consecutive lanes.
     constexpr int TNO = SWIGLU ? TN / 2 : TN;
+    constexpr int OUT_COLS = kNCols, ROWB = OUT_COLS * 2, PIECES = ROWB / 16;
+    static_assert(BM * ROWB <= kLdsBytes, "the output tile must fit in the operand stages");
+    static_assert((PIECES & (PIECES - 1)) == 0, "piece swizzle");
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
         const int r = wm * WTM + j * 32 + lr;
-        if (r >= rows) continue;
-        uint16_t* crow = C + (size_t)(row0 + r) * Nout + n0;
+        uint8_t* lrow = smem + r * ROWB + lk * 8;
+        const int sw = r & (PIECES - 1);
 #pragma unroll
         for (int i = 0; i < TNO; ++i) {
-            const int cbase = (SWIGLU ? wn * (WTN / 2) : wn * WTN) + i * 32 + 4 * lk;
+            const int piece0 = ((SWIGLU ? wn * (WTN / 2) : wn * WTN) + i * 32) / 8;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float o[4];
@@ -444,7 +453,7 @@ struct TileConfig {
                     const float g = acc[i][j][q * 4 + v];
                     if (SWIGLU) {
                         const float u = acc[i + TN / 2][j][q * 4 + v];
-                        o[v] = g / (1.0f + __expf(-g)) * u;
+                        o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
                     } else {
                         o[v] = g;
                     }
@@ -452,8 +461,16 @@ struct TileConfig {
                 uint2 pk;
                 pk.x = pack_bf16x2(o[0], o[1]);
                 pk.y = pack_bf16x2(o[2], o[3]);
-                *(uint2*)(crow + cbase + q * 8) = pk;
+                *(uint2*)(lrow + (((piece0 + q) ^ sw) << 4)) = pk;
             }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < BM * PIECES; idx += kThreads) {
+        const int r = idx / PIECES, pc = idx % PIECES;
+        if (r < rows) {
+            const uint4 v = *(const uint4*)(smem + r * ROWB + ((pc ^ (r & (PIECES - 1))) << 4));
+            *(uint4*)(C + (size_t)(row0 + r) * Nout + n0 + pc * 8) = v;
         }
     }
 }
