@@ -17,7 +17,7 @@
 
 namespace capmoe {
 
-constexpr int kPrepTokens = 64;
+constexpr int kPrepTokens = 16;  // tokens per block: small, the kernel is latency-bound and wants every CU
 
 // The draw of MOE_METRIC_RANDOM: a 32-bit integer hash (two multiply-xorshift rounds) of the pair's
 // counter, offset by the seed; the header states the same formula.
@@ -64,9 +64,10 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
         }
     }
     __syncthreads();
-    // flags -> keys and slots (slot = number of candidate experts with a lower id); a wave walks 16 tokens
-    for (int i = 0; i < 16; ++i) {
-        const int tl = wv * 16 + i, t = t0 + tl;
+    // flags -> keys and slots (slot = number of candidate experts with a lower id); a wave walks its tokens
+    constexpr int kWalk = kPrepTokens / 4;
+    for (int i = 0; i < kWalk; ++i) {
+        const int tl = wv * kWalk + i, t = t0 + tl;
         if (tl >= nt) break;
         int base = 0;
         const uint32_t cls = token_class ? (uint32_t)(token_class[t] & 3) << 30 : 0u;
@@ -95,11 +96,13 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
         for (int s = base + lane; s < S; s += kWave) pair_row[(size_t)t * S + s] = -1;
     }
     __syncthreads();
-    // transposed write: 64 consecutive tokens of one expert per wave
-    for (int e = wv; e < E; e += 4) {
-        if (lane < nt) {
-            key_t[(size_t)e * N + t0 + lane] = key_s[lane * ld + e];
-            slot_t[(size_t)e * N + t0 + lane] = slot_s[lane * ld + e];
+    // transposed write: a wave writes the block's consecutive tokens of 64 / kPrepTokens experts at a time
+    constexpr int kRows = kWave / kPrepTokens;
+    const int tl = lane % kPrepTokens;
+    for (int e = wv * kRows + lane / kPrepTokens; e < E; e += 4 * kRows) {
+        if (tl < nt) {
+            key_t[(size_t)e * N + t0 + tl] = key_s[tl * ld + e];
+            slot_t[(size_t)e * N + t0 + tl] = slot_s[tl * ld + e];
         }
     }
 }
@@ -137,7 +140,7 @@ __device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
 // ---------------------------------------------------------------------------------------------
 // 2. threshold per segment
 // ---------------------------------------------------------------------------------------------
-constexpr int kSelectCache = 16384;  // keys of a segment kept in LDS (64 KB); longer segments re-read L2
+constexpr int kSelectCache = 32768;  // keys of a segment kept in LDS (up to 128 KB); longer segments re-read L2
 
 // One block per capacity segment: `span` experts (1, or the E/G experts of a device when the
 // capacity is a device budget) over seg_tokens tokens.  The keys of expert e0+r form run r.
@@ -162,14 +165,29 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
     const int n_keys = span * seg_tokens;
     const bool cached = n_keys <= kSelectCache;
 
-    int mine = 0;
-    for (int i = tid; i < n_keys; i += 256) {
-        const int r = i / seg_tokens;
-        const uint32_t kx = keys[(size_t)r * N + (i - r * seg_tokens)];
-        if (cached) cache[i] = kx;
-        mine += kx != 0u;
-    }
+    // load the keys; the histogram of their top byte (the first radix pass) is taken on the way
+    hist[tid] = 0;
     for (int r = tid; r < span; r += 256) gt_s[r] = eq_s[r] = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int i0 = tid; i0 < n_keys; i0 += 256 * 8) {
+        uint32_t kx[8];  // eight independent loads in flight before anything waits
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + 256 * u;
+            const int r = i / seg_tokens;
+            kx[u] = i < n_keys ? keys[(size_t)r * N + (i - r * seg_tokens)] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + 256 * u;
+            if (cached && i < n_keys) cache[i] = kx[u];
+            if (kx[u] != 0u) {
+                ++mine;
+                atomicAdd(&hist[kx[u] >> 24], 1);
+            }
+        }
+    }
     const int n_cand = block_sum_256(mine, red);  // its barriers also order the LDS writes before the reads
 
     // threshold: keys above tau are kept, `rem` of the keys equal to tau are kept
@@ -182,21 +200,31 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         uint32_t prefix = 0;
         rem = cap;
         for (int shift = 24; shift >= 0; shift -= 8) {
-            hist[tid] = 0;
-            __syncthreads();
-            const uint32_t hi_mask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
-            for (int i = tid; i < n_keys; i += 256) {
-                uint32_t kx;
-                if (cached) {
-                    kx = cache[i];
-                } else {
-                    const int r = i / seg_tokens;
-                    kx = keys[(size_t)r * N + (i - r * seg_tokens)];
+            if (shift != 24) {
+                hist[tid] = 0;
+                __syncthreads();
+                const uint32_t hi_mask = 0xffffffffu << (shift + 8);
+                for (int i0 = tid; i0 < n_keys; i0 += 256 * 8) {
+                    uint32_t kx[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int i = i0 + 256 * u;
+                        if (i >= n_keys) {
+                            kx[u] = 0u;
+                        } else if (cached) {
+                            kx[u] = cache[i];
+                        } else {
+                            const int r = i / seg_tokens;
+                            kx[u] = keys[(size_t)r * N + (i - r * seg_tokens)];
+                        }
+                    }
+                    // non-candidates (key 0) never matter
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (kx[u] != 0u && (kx[u] & hi_mask) == prefix) atomicAdd(&hist[(kx[u] >> shift) & 255u], 1);
                 }
-                // non-candidates (key 0) never matter
-                if (kx != 0u && (kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+                __syncthreads();
             }
-            __syncthreads();
             // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
             // digit; the digit where that count first reaches `rem` holds the cap-th key
             const int mine_d = 255 - tid;
@@ -471,7 +499,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         const size_t n_keys = (size_t)s.seg_tokens * s.span;
         const size_t lds = (n_keys <= (size_t)kSelectCache ? n_keys : 0) * 4;
         static bool configured = false;
-        if (!configured) {  // 64 KB of keys plus the kernel's own few hundred bytes
+        if (!configured) {  // up to 128 KB of keys plus the kernel's own few kilobytes
             (void)hipFuncSetAttribute((const void*)drop_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       kSelectCache * 4);
             configured = true;
