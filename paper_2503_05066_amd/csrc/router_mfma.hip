@@ -9,7 +9,7 @@
 // are added, in slice order, by the softmax kernel (deterministic: no floating-point atomics).
 // The fp32 weights of a 32-wide k-slab are split in registers and the three planes go to LDS
 // (shared by the 4 waves, two stages); each wave reads its own 32 token rows straight from global
-// memory.
+// memory.  Loads run several slabs ahead of the multiplication in a register ring.
 #include "common.h"
 
 namespace capmoe {
@@ -78,27 +78,12 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
         wsrc[i] = w + (size_t)(e < E ? e : E - 1) * d + k_begin + kc * 8;  // padding rows repeat the last expert
         wdst[i] = e * 64 + ((kc ^ ((e >> 2) & 3)) << 4);                   // EP is a multiple of 4: same swizzle per plane
     }
-    float4 wreg[NP][2];
-    auto load_w = [&](int slab) {
-#pragma unroll
-        for (int i = 0; i < NP; ++i)
-            if (wlive[i]) {
-                wreg[i][0] = *(const float4*)(wsrc[i] + slab * kRmSlab);
-                wreg[i][1] = *(const float4*)(wsrc[i] + slab * kRmSlab + 4);
-            }
-    };
-    auto store_w = [&](int slab) {
-        uint8_t* dst = smem + (slab & 1) * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < NP; ++i)
-            if (wlive[i]) {
-                uint4 hi, mid, lo;
-                split_planes(wreg[i][0], wreg[i][1], hi, mid, lo);
-                *(uint4*)(dst + wdst[i]) = hi;
-                *(uint4*)(dst + EP * 64 + wdst[i]) = mid;
-                *(uint4*)(dst + 2 * EP * 64 + wdst[i]) = lo;
-            }
-    };
+    // Register ring of D slabs: the fp32 weights and the token fragments of slab s + D are requested
+    // while slab s is multiplied, so that a block keeps D slabs of loads in flight (the kernel is
+    // bound by load latency: a slab is only 6 * TN MFMAs of work per wave).
+    constexpr int D = TN <= 2 ? 4 : (TN <= 4 ? 2 : 1);
+    float4 wreg[D][NP][2];
+    bf16x8 xreg[D][2];
 
     f32x16 acc[TN];
 #pragma unroll
@@ -116,35 +101,63 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
             w_off[p][i] = p * EP * 64 + R * 64 + ((lk ^ ((R >> 2) & 3)) << 4);
         }
 
-    load_w(0);
-    bf16x8 xa[2], xn[2];
-    xa[0] = *(const bf16x8*)(xrow);
-    xa[1] = *(const bf16x8*)(xrow + 16);
-    store_w(0);
-    __syncthreads();
-    for (int s = 0; s < n_slabs; ++s) {
-        if (s + 1 < n_slabs) {
-            load_w(s + 1);
-            xn[0] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab);
-            xn[1] = *(const bf16x8*)(xrow + (s + 1) * kRmSlab + 16);
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+        if (u < n_slabs) {
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                if (wlive[i]) {
+                    wreg[u][i][0] = *(const float4*)(wsrc[i] + u * kRmSlab);
+                    wreg[u][i][1] = *(const float4*)(wsrc[i] + u * kRmSlab + 4);
+                }
+            xreg[u][0] = *(const bf16x8*)(xrow + u * kRmSlab);
+            xreg[u][1] = *(const bf16x8*)(xrow + u * kRmSlab + 16);
         }
-        const uint8_t* st = smem + (s & 1) * STAGE_BYTES;
+    }
+    for (int s0 = 0; s0 < n_slabs; s0 += D) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int u = 0; u < D; ++u) {
+            const int sl = s0 + u;
+            if (sl < n_slabs) {  // block-uniform
+                uint8_t* st = smem + (sl & 1) * STAGE_BYTES;
+                // split this slab's weights into the three planes of the stage the previous slab does not use
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                // smallest plane first
+                for (int i = 0; i < NP; ++i)
+                    if (wlive[i]) {
+                        uint4 hi, mid, lo;
+                        split_planes(wreg[u][i][0], wreg[u][i][1], hi, mid, lo);
+                        *(uint4*)(st + wdst[i]) = hi;
+                        *(uint4*)(st + EP * 64 + wdst[i]) = mid;
+                        *(uint4*)(st + 2 * EP * 64 + wdst[i]) = lo;
+                    }
+                const bf16x8 xa0 = xreg[u][0], xa1 = xreg[u][1];
+                if (sl + D < n_slabs) {  // refill the slot
 #pragma unroll
-                for (int p = 2; p >= 0; --p) {
-                    const bf16x8 wf = *(const bf16x8*)(st + (w_off[p][i] ^ (ks << 5)));
-                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa[ks], acc[i], 0, 0, 0);
+                    for (int i = 0; i < NP; ++i)
+                        if (wlive[i]) {
+                            wreg[u][i][0] = *(const float4*)(wsrc[i] + (sl + D) * kRmSlab);
+                            wreg[u][i][1] = *(const float4*)(wsrc[i] + (sl + D) * kRmSlab + 4);
+                        }
+                    xreg[u][0] = *(const bf16x8*)(xrow + (sl + D) * kRmSlab);
+                    xreg[u][1] = *(const bf16x8*)(xrow + (sl + D) * kRmSlab + 16);
+                }
+                // one barrier per slab: the stage written now was last read two slabs ago, i.e. before
+                // the previous barrier
+                __syncthreads();
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+                    for (int i = 0; i < TN; ++i) {
+                        // smallest plane first
+#pragma unroll
+                        for (int p = 2; p >= 0; --p) {
+                            const bf16x8 wf = *(const bf16x8*)(st + (w_off[p][i] ^ (ks << 5)));
+                            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, ks == 0 ? xa0 : xa1, acc[i], 0, 0, 0);
+                        }
+                    }
                 }
             }
         }
-        if (s + 1 < n_slabs) store_w(s + 1);  // the other stage: last read before the previous barrier
-        __syncthreads();
-        xa[0] = xn[0];
-        xa[1] = xn[1];
     }
 
     // lane holds token (lane & 31) and experts 8q + 4*(lane/32) + v of each 32-expert tile
