@@ -9,7 +9,7 @@
 
 namespace capmoe {
 
-constexpr int kMaxExperts = 256;  // 64 tokens x E keys and slots must fit in LDS
+constexpr int kMaxExperts = 256;  // expert ids fit a byte (slot tables), one LDS histogram row per expert
 constexpr int kMaxTopK = 64;
 constexpr int kWave = 64;
 

@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
                                                            const uint8_t* __restrict__ token_class, uint32_t seed) {
     extern __shared__ uint32_t lds[];
     const int ld = E | 1;                                  // odd row pitch: conflict-free transposed reads
-    uint32_t* key_s = lds;                                 // [64][ld] score bits, then keys
-    uint8_t* slot_s = (uint8_t*)(lds + kPrepTokens * ld);  // [64][ld] candidate flags, then slots
+    uint32_t* key_s = lds;                                 // [kPrepTokens][ld] score bits, then keys
+    uint8_t* slot_s = (uint8_t*)(lds + kPrepTokens * ld);  // [kPrepTokens][ld] candidate flags, then slots
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int t0 = blockIdx.x * kPrepTokens;
     const int nt = N - t0 < kPrepTokens ? N - t0 : kPrepTokens;  // tokens of this block

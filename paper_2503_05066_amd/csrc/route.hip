@@ -202,7 +202,10 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
             else
                 v[i] = -1.0f;
         }
-        // top-k by repeated maximum; (larger score, then lower expert id) wins
+        // top-k by repeated maximum; (larger score, then lower expert id) wins; lane j keeps the j-th
+        // winner so that the lists leave as one coalesced store each
+        int my_idx = 0;
+        float my_val = 0.0f;
         for (int j = 0; j < k; ++j) {
             float bv = -1.0f;
             int be = 0x7fffffff;
@@ -226,10 +229,14 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
 #pragma unroll
             for (int i = 0; i < EPL; ++i)
                 if (be == lane + kWave * i) v[i] = -1.0f;  // the winner leaves the pool
-            if (lane == 0) {
-                topk_idx[(size_t)t * k + j] = be;
-                topk_score[(size_t)t * k + j] = bv;
+            if (lane == j) {
+                my_idx = be;
+                my_val = bv;
             }
+        }
+        if (lane < k) {
+            topk_idx[(size_t)t * k + lane] = my_idx;
+            topk_score[(size_t)t * k + lane] = my_val;
         }
     }
 }
