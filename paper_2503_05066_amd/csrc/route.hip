@@ -156,12 +156,14 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
                                                            const float* __restrict__ bias, float* __restrict__ scores,
                                                            int32_t* __restrict__ topk_idx,
                                                            float* __restrict__ topk_score, int N, int E, int k) {
-    __shared__ float numer[4][EPL * kWave];
+    __shared__ __attribute__((aligned(16))) float numer[4][EPL * kWave];
+    __shared__ uint2 winners[4][kMaxTopK];  // (score bits, expert) of a token's k winners, ascending expert
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    // the loop count is the same for all four waves of a block, so the barriers inside are uniform
+    // a wave works alone: its LDS row is private, and LDS operations of one wave complete in order
     for (int base = blockIdx.x * 4; base < N; base += gridDim.x * 4) {
         const int t = base + wv;
         const bool live = t < N;
+        if (!live) break;
         float* l = logits + (size_t)(live ? t : 0) * E;
         float v[EPL];
         float m = -INFINITY;
@@ -170,9 +172,17 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
             const int e = lane + kWave * i;
             if (e < E && partial) {
                 // the router GEMM left one partial sum per K slice: add them in slice order
+                // (eight loads in flight at a time: one dependent load per addition costs a microsecond each)
                 float sum = bias ? bias[e] : 0.0f;
-                for (int sl = 0; sl < ksplit; ++sl)
-                    sum = __fadd_rn(sum, partial[((size_t)sl * N + (live ? t : 0)) * E + e]);
+                for (int s0 = 0; s0 < ksplit; s0 += 8) {
+                    float p[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        p[u] = s0 + u < ksplit ? partial[((size_t)(s0 + u) * N + t) * E + e] : 0.0f;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (s0 + u < ksplit) sum = __fadd_rn(sum, p[u]);
+                }
                 v[i] = sum;
                 if (live) l[e] = sum;
             } else {
@@ -187,12 +197,15 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
             v[i] = e < E ? exp_nonpositive(__fsub_rn(v[i], m)) : 0.0f;
             numer[wv][e] = v[i];
         }
-        __syncthreads();
-        // every lane adds the numerators in ascending expert order (same address for all lanes)
+        __builtin_amdgcn_wave_barrier();
+        // every lane adds the numerators in ascending expert order (same address for all lanes, four per
+        // read; the entries past E are +0 and leave the sum as it is)
         float sum = 0.0f;
-        for (int e = 0; e < E; ++e) sum = __fadd_rn(sum, numer[wv][e]);
-        __syncthreads();
-        if (!live) continue;
+        for (int e = 0; e < E; e += 4) {
+            const float4 n4 = *(const float4*)&numer[wv][e];
+            sum = __fadd_rn(__fadd_rn(__fadd_rn(__fadd_rn(sum, n4.x), n4.y), n4.z), n4.w);
+        }
+        __builtin_amdgcn_wave_barrier();  // the row is rewritten for the wave's next token only after these reads
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
             const int e = lane + kWave * i;
@@ -202,42 +215,60 @@ __global__ __launch_bounds__(256) void softmax_topk_kernel(float* __restrict__ l
             else
                 v[i] = -1.0f;
         }
-        // top-k by repeated maximum; (larger score, then lower expert id) wins; lane j keeps the j-th
-        // winner so that the lists leave as one coalesced store each
-        int my_idx = 0;
-        float my_val = 0.0f;
+        // top-k by selection: scores are >= +0, so their bit patterns order like the values.
+        // (1) the k-th largest pattern by a 30-step binary search on ballots (1.0f has bit 29 as its highest),
+        // (2) winners = patterns above it, plus the lowest expert ids among those equal to it,
+        // (3) every winner finds its place (larger score first, then lower expert id) by counting the
+        //     winners ahead of it in a list the wave keeps in LDS.
+        // Repeated wave-wide arg-max costs k rounds of cross-lane steps; this is a few ballots per bit.
+        uint32_t bits[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) bits[i] = __float_as_uint(v[i] < 0.0f ? 0.0f : v[i]);
+        uint32_t tau = 0;
+        for (int bit = 29; bit >= 0; --bit) {
+            const uint32_t cand = tau | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) cnt += __popcll(__ballot(lane + kWave * i < E && bits[i] >= cand));
+            if (cnt >= k) tau = cand;
+        }
+        int n_gt = 0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) n_gt += __popcll(__ballot(lane + kWave * i < E && bits[i] > tau));
+        const int need = k - n_gt;  // >= 1: how many of the patterns equal to tau win
+        const uint64_t below = (1ull << lane) - 1ull;
+        int eq_before = 0, win_before = 0;
+        uint2* list = &winners[wv][0];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            const int e = lane + kWave * i;
+            const bool valid = e < E;
+            const bool eq = valid && bits[i] == tau;
+            const uint64_t eq_mask = __ballot(eq);
+            const bool win = valid && (bits[i] > tau || (eq && eq_before + __popcll(eq_mask & below) < need));
+            const uint64_t win_mask = __ballot(win);
+            if (win) list[win_before + __popcll(win_mask & below)] = make_uint2(bits[i], (uint32_t)e);
+            eq_before += __popcll(eq_mask);
+            win_before += __popcll(win_mask);
+            if (!win) bits[i] = 0xffffffffu;  // marks "no output"
+        }
+        __builtin_amdgcn_wave_barrier();
+        int place[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) place[i] = 0;
         for (int j = 0; j < k; ++j) {
-            float bv = -1.0f;
-            int be = 0x7fffffff;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) {
-                const int e = lane + kWave * i;
-                if (v[i] > bv) {  // own experts ascend with i, so '>' keeps the lower id on ties
-                    bv = v[i];
-                    be = e;
-                }
-            }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const float ov = __shfl_xor(bv, off, kWave);
-                const int oe = __shfl_xor(be, off, kWave);
-                if (ov > bv || (ov == bv && oe < be)) {
-                    bv = ov;
-                    be = oe;
-                }
-            }
+            const uint2 w = list[j];  // same address in every lane
 #pragma unroll
             for (int i = 0; i < EPL; ++i)
-                if (be == lane + kWave * i) v[i] = -1.0f;  // the winner leaves the pool
-            if (lane == j) {
-                my_idx = be;
-                my_val = bv;
+                place[i] += (w.x > bits[i] || (w.x == bits[i] && (int)w.y < lane + kWave * i)) ? 1 : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < EPL; ++i)
+            if (bits[i] != 0xffffffffu) {
+                topk_idx[(size_t)t * k + place[i]] = lane + kWave * i;
+                topk_score[(size_t)t * k + place[i]] = __uint_as_float(bits[i]);
             }
-        }
-        if (lane < k) {
-            topk_idx[(size_t)t * k + lane] = my_idx;
-            topk_score[(size_t)t * k + lane] = my_val;
-        }
+        __builtin_amdgcn_wave_barrier();  // the list is rewritten for the wave's next token only after these reads
     }
 }
 
