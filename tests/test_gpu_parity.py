@@ -198,6 +198,19 @@ def test_plan_device_level_capacity(orc, name, mode, scope, gamma, metric):
         assert ref.plan.rows >= expert_level.plan.rows                  # less restrictive than per-expert limits
 
 
+@pytest.mark.parametrize("n,e,k,g,mode,scope,gamma", [
+    (256, 256, 8, 2, ED, LOCAL, 1.0),          # 136 candidate slots per token
+    (256, 256, 8, 1, TD, 3, 1.0),              # one budget over all 256 experts: 65536 keys in one segment
+    (2048, 64, 6, 2, ED, 2, 0.7),              # 32 experts x 1024 tokens under one budget: the largest cached segment
+    (4100, 16, 2, 4, TD, 2, 1.0),              # ragged blocks of 1025 tokens
+    (64, 8, 2, 8, TD, 3, 1.5),                 # one expert per device: device budget = expert capacity
+])
+def test_plan_large_segments(orc, n, e, k, g, mode, scope, gamma):
+    rng = np.random.default_rng(n + e)
+    logits = (rng.standard_normal((n, e)) * 2 + rng.standard_normal(e)[None, :] * 1.5).astype(np.float32)
+    check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, "large segment")
+
+
 def test_device_level_ties(orc):
     w = synth.scaled(W["olmoe"], n_tokens=2048, n_experts=32, top_k=4, device_groups=4)
     logits = synth.logits_with_ties(w)
