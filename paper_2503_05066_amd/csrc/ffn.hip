@@ -353,7 +353,9 @@ struct TileConfig {
     static_assert(STAGES != 0 || BK == 64, "the pipelined loop is written for 64-wide slabs");
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wm = wv % WAVES_M, wn = wv / WAVES_M;
+    // waves w and w + 4 share a SIMD: with the row half in the upper bit of the wave id, the live waves of a
+    // half-filled tile (rows past the expert's end skip their MFMAs) still cover all four SIMDs
+    const int wm = wv / WAVES_N, wn = wv % WAVES_N;
 
     // ---- sources of this lane's pieces ----
     const uint16_t* src[LOADS];
