@@ -55,7 +55,7 @@ def parse():
                    help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
-    p.add_argument("--others", default="finegrained:expanded,finegrained:token,decode:token,decode:expanded,mixtral:none,mixtral:expanded,mixtral:token:local_device,mixtral:token",
+    p.add_argument("--others", default="olmoe:none,finegrained:expanded,finegrained:token,finegrained:none,decode:token,decode:expanded,decode:none,mixtral:none,mixtral:expanded,mixtral:token:local_device,mixtral:token",
                    help="comma list of workload:mode[:scope] measured after the main line ('' for none)")
     return p.parse_args()
 

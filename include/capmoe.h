@@ -191,6 +191,20 @@ int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight,
                 void* stream);
 
 /*
+ * The whole layer in one call: moe_route_topk, moe_capacity_drop_ranked, moe_dispatch_ffn and moe_combine
+ * enqueued in that order on `stream` (Eq. 1, Alg. 1 / Alg. 2, Eq. 2).  Same buffers, same results bit for
+ * bit as the separate calls; xp is not materialised.  token_class may be NULL; logits, scores, the top-k
+ * lists and the plan are outputs the caller may inspect afterwards.  Nothing is enqueued unless every
+ * argument check of the four calls passes.
+ */
+int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                      const void* w_gate, const void* w_up, const void* w_down, const uint8_t* token_class,
+                      uint32_t seed, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                      int32_t* expert_count, int32_t* seg_count, int32_t* expert_offset, int32_t* row_token,
+                      float* row_weight, int32_t* pair_row, void* yp, void* y, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
  * Profiling hook (instrumentation, not part of the method).  While a pair of hipEvent_t (passed as
  * void*) is attached to a kernel id, every launch of that kernel records `start` before and `stop`
  * after it on the launch stream; hipEventElapsedTime(start, stop) is then that launch's duration.

@@ -62,6 +62,8 @@ def load():
         lib.moe_grouped_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch_ffn.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
+        lib.moe_layer_forward.argtypes = [dp] + [vp] * 7 + [ctypes.c_uint32] + [vp] * 13 + [sz, vp]
+        lib.moe_layer_forward.restype = i32
         lib.moe_profile_attach.argtypes = [i32, vp, vp]
         lib.moe_profile_attach.restype = i32
         lib.moe_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
@@ -156,6 +158,18 @@ def moe_dispatch_ffn(desc, x, expert_offset, row_token, w_gate, w_up, w_down, yp
 def moe_combine(desc, yp, row_weight, pair_row, y, stream=None):
     _check(load().moe_combine(ctypes.byref(desc), _ptr(yp), _ptr(row_weight), _ptr(pair_row), _ptr(y),
                               _stream(stream)), "moe_combine")
+
+
+def moe_layer_forward(desc, x, w_router, bias, w_gate, w_up, w_down, token_class, seed, buf, stream=None):
+    """The whole layer through the one-call entry point, into the buffers of a LayerBuffers."""
+    ws = buf.workspace
+    _check(load().moe_layer_forward(
+        ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(bias), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+        _ptr(token_class), int(seed) & 0xFFFFFFFF, _ptr(buf.logits), _ptr(buf.scores), _ptr(buf.topk_idx),
+        _ptr(buf.topk_score), _ptr(buf.expert_count), _ptr(buf.seg_count), _ptr(buf.expert_offset),
+        _ptr(buf.row_token), _ptr(buf.row_weight), _ptr(buf.pair_row), _ptr(buf.yp), _ptr(buf.y), _ptr(ws),
+        ws.numel() * ws.element_size(), _stream(stream)), "moe_layer_forward")
+    return buf.y
 
 
 KERNELS = ("router_logits", "softmax_topk", "drop_prepare", "drop_select", "drop_emit", "dispatch", "ffn_schedule",

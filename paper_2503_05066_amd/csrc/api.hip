@@ -285,4 +285,49 @@ int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight,
     return MOE_OK;
 }
 
+int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                      const void* w_gate, const void* w_up, const void* w_down, const uint8_t* token_class,
+                      uint32_t seed, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                      int32_t* expert_count, int32_t* seg_count, int32_t* expert_offset, int32_t* row_token,
+                      float* row_weight, int32_t* pair_row, void* yp, void* y, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    // every check of the four calls first, so that a refusal leaves nothing enqueued
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    const Sizes s = derive(*desc);
+    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    if (!expert_count || !seg_count || !expert_offset || !workspace) return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    size_t need = drop_workspace(*desc, s, nullptr).bytes;
+    const size_t need_route = route_workspace(*desc, nullptr).bytes;
+    if (need_route > need) need = need_route;
+    if (desc->n_tokens > 0) {
+        if (!x || !w_router || !logits || !scores || !topk_idx || !topk_score || !pair_row || !yp || !y || !row_weight)
+            return MOE_ERR_INVALID_ARG;
+        if (misaligned16(x) || misaligned16(w_router) || misaligned16(yp) || misaligned16(y)) return MOE_ERR_INVALID_ARG;
+    }
+    if (s.max_rows > 0) {
+        if (!row_token || !row_weight || !w_gate || !w_up || !w_down || !yp) return MOE_ERR_INVALID_ARG;
+        if (misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
+            return MOE_ERR_INVALID_ARG;
+        const int sh = ffn_shape_supported(*desc);
+        if (sh != MOE_OK) return sh;
+        const size_t need_ffn = ffn_workspace(*desc, s, nullptr).bytes;
+        if (need_ffn > need) need = need_ffn;
+    }
+    if (workspace_bytes < need) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    int st = moe_route_topk(desc, x, w_router, bias, 0, logits, scores, topk_idx, topk_score, workspace,
+                            workspace_bytes, stream);
+    if (st != MOE_OK) return st;
+    st = moe_capacity_drop_ranked(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
+                                  row_token, row_weight, pair_row, workspace, workspace_bytes, stream);
+    if (st != MOE_OK) return st;
+    if (s.max_rows > 0) {
+        st = moe_dispatch_ffn(desc, x, expert_offset, row_token, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
+                              stream);
+        if (st != MOE_OK) return st;
+    }
+    return moe_combine(desc, yp, row_weight, pair_row, y, stream);
+}
+
 }  // extern "C"

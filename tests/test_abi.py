@@ -18,14 +18,14 @@ pytestmark = pytest.mark.usefixtures("built_library")
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "capmoe.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = capmoe.load()
     names = declared_functions()
     assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_dispatch_ffn", "moe_combine",
-            "moe_query", "moe_profile_attach",
+            "moe_query", "moe_profile_attach", "moe_layer_forward", "moe_probe_mfma_bf16", "moe_capacity_drop_ranked",
             "moe_status_string"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
@@ -116,4 +116,5 @@ def test_bad_arguments_are_refused_on_the_host():
     assert lib.moe_grouped_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_dispatch_ffn(ctypes.byref(ok), z, z, z, z, z, z, z, z, 0, z) == 1
     assert lib.moe_combine(ctypes.byref(ok), z, z, z, z, z) == 1
+    assert lib.moe_layer_forward(ctypes.byref(ok), *([z] * 7), 0, *([z] * 13), 0, z) == 1
     assert lib.moe_query(None, None, None, None, None) == 1

@@ -350,6 +350,34 @@ def check_layer(orc, layer, mode, scope, gamma, tokens=None, what="", overselect
     return buf, ref
 
 
+def test_one_call_entry_matches_separate_calls():
+    """moe_layer_forward enqueues the same four calls: every output equal bit for bit."""
+    cases = [(synth.scaled(W["tiny"], device_groups=4), ED, LOCAL, 1.0, 0, False),
+             (synth.scaled(W["olmoe"], name="reduced", n_tokens=640, d_model=256, n_experts=8, top_k=2, d_hidden=384,
+                           device_groups=4, skew="normal", skew_param=1.5), TD, LOCAL, 1.0, 2, True),
+             (synth.scaled(W["olmoe"], name="reduced", n_tokens=300, d_model=384, n_experts=4, top_k=2, d_hidden=256,
+                           device_groups=1), TD, GLOBAL, 0.0, 0, False)]
+    for w, mode, scope, gamma, m, limit in cases:
+        layer = DeviceLayer(w, host_weights=False)
+        desc = layer.desc(mode, scope, gamma)
+        desc.overselect, desc.max_experts, desc.metric = m, int(limit), 3 if limit else 0
+        cls = torch.from_numpy((np.arange(w.n_tokens) % 2).astype(np.uint8)).cuda() if limit else None
+        seed = 9 if limit else 0
+        a, b = capmoe.LayerBuffers(desc), capmoe.LayerBuffers(desc)
+        capmoe.layer_forward(a, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                             fused_dispatch=True, token_class=cls, seed=seed)
+        capmoe.moe_layer_forward(desc, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                                 cls, seed, b)
+        torch.cuda.synchronize()
+        rows = int(a.expert_offset[-1])
+        assert rows == int(b.expert_offset[-1])
+        for name in ("logits", "scores", "topk_idx", "topk_score", "expert_count", "seg_count", "expert_offset",
+                     "pair_row", "y"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), name
+        assert torch.equal(a.row_token[:rows], b.row_token[:rows]) and torch.equal(a.yp[:rows], b.yp[:rows])
+        assert torch.equal(a.row_weight[:rows].view(torch.int32), b.row_weight[:rows].view(torch.int32))
+
+
 def test_layer_tiny_fp32(orc):
     layer = DeviceLayer(W["tiny"])
     for mode, scope, gamma in [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (TD, LOCAL, 0.5), (TD, LOCAL, math.inf)]:
