@@ -433,47 +433,90 @@ __global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* _
                                                                   int32_t* __restrict__ seg_need,
                                                                   int32_t* __restrict__ seg_count, int N, int E, int S,
                                                                   int k, int seg_tokens, int segs) {
-    extern __shared__ uint32_t lim[];  // [S][64] score bits, then [S][64] expert | slot << 16
+    // per thread (token): [S] score bits, [S] expert | slot << 16 of the surviving pairs, [S] bytes "slot kept";
+    // entry i of lane l sits at i * 64 + l: no bank conflicts
+    extern __shared__ uint32_t lim[];
     uint32_t* sc = lim;
     uint32_t* es = lim + (size_t)S * kLimitTokens;
+    uint8_t* kept = (uint8_t*)(lim + (size_t)2 * S * kLimitTokens);
+    __shared__ int removed[kMaxExperts];  // pairs this block removes per expert (one global atomic each at the end)
     const int lane = threadIdx.x;
     const int gtid = blockIdx.x * kLimitTokens + lane;
     for (int i = gtid; i < segs; i += gridDim.x * kLimitTokens) {
         seg_tau[i] = 0u;
         seg_need[i] = 0;
     }
+    for (int e = lane; e < E; e += kLimitTokens) removed[e] = 0;
+    __syncthreads();
     const int t = gtid;
-    if (t >= N) return;
-    int n = 0, slot = 0;
-    for (int e = 0; e < E; ++e) {
-        const size_t at = (size_t)e * N + t;
-        if (key_t[at] == 0u) continue;
-        if (pair_row[(size_t)t * S + slot] >= 0) {
-            sc[n * kLimitTokens + lane] = __float_as_uint(scores[(size_t)t * E + e]);
-            es[n * kLimitTokens + lane] = (uint32_t)e | ((uint32_t)slot << 16);
-            ++n;
-        } else {
-            key_t[at] = 0u;  // dropped by the capacity
+    // the block's tokens lie in one capacity block when its first and last do
+    const int t_first = blockIdx.x * kLimitTokens;
+    const int t_last = t_first + kLimitTokens - 1 < N ? t_first + kLimitTokens - 1 : N - 1;
+    const bool one_block = t_first / seg_tokens == t_last / seg_tokens;
+    if (t < N) {
+        // which candidate slots survived the capacity (loads in batches of independent ones: a chain of
+        // dependent loads costs about a microsecond per link)
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            int32_t pr[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) pr[u] = s0 + u < S ? pair_row[(size_t)t * S + s0 + u] : -1;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) kept[(s0 + u) * kLimitTokens + lane] = pr[u] >= 0;
         }
-        ++slot;
+        // walk the experts in ascending id: the c-th candidate of the token owns slot c
+        int n = 0, slot = 0;
+        for (int e0 = 0; e0 < E; e0 += 32) {
+            uint32_t kx[32];
+#pragma unroll
+            for (int u = 0; u < 32; ++u) kx[u] = e0 + u < E ? key_t[(size_t)(e0 + u) * N + t] : 0u;
+#pragma unroll
+            for (int u = 0; u < 32; ++u) {
+                if (kx[u] == 0u) continue;
+                if (kept[slot * kLimitTokens + lane]) {
+                    es[n * kLimitTokens + lane] = (uint32_t)(e0 + u) | ((uint32_t)slot << 16);
+                    ++n;
+                } else {
+                    key_t[(size_t)(e0 + u) * N + t] = 0u;  // dropped by the capacity
+                }
+                ++slot;
+            }
+        }
+        if (n > k) {
+            for (int i0 = 0; i0 < n; i0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    v[u] = i0 + u < n ? scores[(size_t)t * E + (es[(i0 + u) * kLimitTokens + lane] & 0xffffu)] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (i0 + u < n) sc[(i0 + u) * kLimitTokens + lane] = __float_as_uint(v[u]);
+            }
+            const int b = t / seg_tokens;
+            for (int i = 0; i < n; ++i) {
+                const uint32_t si = sc[i * kLimitTokens + lane];
+                int better = 0;  // survivors ahead of pair i: higher score, or equal score and lower expert id
+                for (int j = 0; j < n; ++j) {
+                    const uint32_t sj = sc[j * kLimitTokens + lane];
+                    better += sj > si || (sj == si && j < i);
+                }
+                if (better >= k) {
+                    const uint32_t v = es[i * kLimitTokens + lane];
+                    const int e = (int)(v & 0xffffu), sl = (int)(v >> 16);
+                    key_t[(size_t)e * N + t] = 0u;
+                    pair_row[(size_t)t * S + sl] = -1;
+                    if (one_block)
+                        atomicAdd(&removed[e], 1);
+                    else
+                        atomicSub(&seg_count[b * E + e], 1);
+                }
+            }
+        }
     }
-    if (n <= k) return;
-    const int b = t / seg_tokens;
-    for (int i = 0; i < n; ++i) {
-        const uint32_t si = sc[i * kLimitTokens + lane];
-        int better = 0;  // surviving pairs ahead of pair i: higher score, or equal score and listed earlier (lower id)
-        for (int j = 0; j < n; ++j) {
-            const uint32_t sj = sc[j * kLimitTokens + lane];
-            better += sj > si || (sj == si && j < i);
-        }
-        if (better >= k) {
-            const uint32_t v = es[i * kLimitTokens + lane];
-            const int e = (int)(v & 0xffffu), sl = (int)(v >> 16);
-            key_t[(size_t)e * N + t] = 0u;
-            pair_row[(size_t)t * S + sl] = -1;
-            atomicSub(&seg_count[b * E + e], 1);
-        }
-    }
+    __syncthreads();
+    if (one_block)
+        for (int e = lane; e < E; e += kLimitTokens)
+            if (removed[e]) atomicSub(&seg_count[(t_first / seg_tokens) * E + e], removed[e]);
 }
 
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
@@ -516,7 +559,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     emit();
     if (d.max_experts && s.slots > d.top_k && N > 0) {
         // the first plan tells which pairs survive the capacity; trim every token to k of them, emit again
-        const size_t lds = (size_t)s.slots * kLimitTokens * 8;
+        const size_t lds = (size_t)s.slots * kLimitTokens * 9;  // two words and a byte per slot and token
         if (lds > 64 * 1024)
             (void)hipFuncSetAttribute((const void*)drop_limit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (int)lds);
