@@ -265,6 +265,32 @@ def test_max_k_edge_cases(orc):
     check_route_and_plan(orc, lg[:3], 3, 64, 8, 1, ED, GLOBAL, math.inf, "max-k three tokens", 0, None, 0, 8, True)
 
 
+def test_plan_random_option_mix(orc):
+    """Random combinations of every option (mode, scope, gamma, metric, classes, seed, over-selection, the
+    per-token limit) on random shapes, half of them with few distinct logit values (ties everywhere)."""
+    rng = np.random.default_rng(2025)
+    for trial in range(48):
+        g = int(rng.choice([1, 2, 4, 8]))
+        mloc = int(rng.choice([1, 2, 4, 8]))
+        e = g * mloc
+        n = g * int(rng.integers(1, 160))
+        k = int(rng.integers(1, min(e, 8) + 1))
+        m_over = int(rng.integers(0, min(e - k, 12) + 1)) if rng.random() < 0.4 else 0
+        mode = int(rng.choice([NONE, TD, ED]))
+        scope = int(rng.integers(0, 4))
+        gamma = float(rng.choice([0.0, 0.3, 0.5, 1.0, 1.3, 2.0, math.inf]))
+        metric = int(rng.integers(0, 4))
+        classes = rng.integers(0, 4, n).astype(np.uint8) if rng.random() < 0.4 else None
+        seed = int(rng.integers(1, 1000)) if metric == 3 or rng.random() < 0.3 else 0
+        limit = bool(rng.random() < 0.4)
+        if trial % 2:
+            logits = rng.integers(-3, 4, (n, e)).astype(np.float32) * 0.5
+        else:
+            logits = (rng.standard_normal((n, e)) * 2).astype(np.float32)
+        check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, f"mix {trial}", metric, classes, seed, m_over,
+                             limit)
+
+
 def test_random_metric_ties_and_seeds(orc):
     n, e = 1024, 8
     logits = np.zeros((n, e), np.float32)           # all scores equal: only the draws decide

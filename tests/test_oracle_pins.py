@@ -692,3 +692,84 @@ def test_workload_skew(orc):
     nbar = w.n_tokens * w.top_k / w.n_experts
     assert r.cand.sum(0).max() / nbar > 5.0        # peak load several times the mean
     assert r.keep.sum(0).max() == 512
+
+
+# ----------------------------------------------------------------------------
+# every option at once against a pure-Python restatement of the definitions (tiny random cases)
+# ----------------------------------------------------------------------------
+def definition_in_python(scores, k, g, mode, scope, gamma, metric, classes, seed, m_over, limit):
+    """The kept set written with Python lists and sorted(): candidates (Eq. 1 top-(k+m), plus the own device's
+    experts for Expanded Drop), one ranking per capacity segment (expert, or all experts of a device) over the
+    tokens the constraint ranges over, the first `cap` stay (Eqs. 8-10 with exactly cap kept), then optionally
+    the k best surviving experts per token."""
+    n, e = scores.shape
+    mloc = e // g
+    cand = [[False] * e for _ in range(n)]
+    for t in range(n):
+        order = sorted(range(e), key=lambda j: (-float(scores[t, j]), j))
+        for j in order[:k + m_over]:
+            cand[t][j] = True
+        if mode == ED:
+            for j in range((t // (n // g)) * mloc, (t // (n // g) + 1) * mloc):
+                cand[t][j] = True
+    blocks = g if scope in (0, 2) else 1
+    span = mloc if scope in (2, 3) else 1
+    ns = n // blocks
+    if mode == NONE or math.isinf(gamma):
+        cap = ns * span
+    else:
+        cap = min(ns * span, int(gamma * (ns * k * span) / e))
+    keep = [[False] * e for _ in range(n)]
+    for b in range(blocks):
+        for e0 in range(0, e, span):
+            pairs = [(t, j) for j in range(e0, e0 + span) for t in range(b * ns, (b + 1) * ns) if cand[t][j]]
+
+            def importance(p):
+                t, j = p
+                if metric == 1:
+                    return -t
+                if metric == 2:
+                    return t
+                if metric == 3:
+                    return py_pair_hash(seed, t * e + j) >> 3
+                return float(scores[t, j])
+            pairs.sort(key=lambda p: (-(int(classes[p[0]]) if classes is not None else 0), -importance(p), p[0], p[1]))
+            for t, j in pairs[:cap]:
+                keep[t][j] = True
+    if limit:
+        for t in range(n):
+            alive = sorted([j for j in range(e) if keep[t][j]], key=lambda j: (-float(scores[t, j]), j))
+            for j in alive[k:]:
+                keep[t][j] = False
+    return np.array(cand, np.uint8), np.array(keep, np.uint8), cap
+
+
+def test_all_options_against_the_definition_in_python(orc):
+    rng = np.random.default_rng(77)
+    checked = 0
+    for trial in range(120):
+        g = int(rng.choice([1, 2, 4]))
+        mloc = int(rng.choice([1, 2, 3]))
+        e = g * mloc
+        n = g * int(rng.integers(1, 9))
+        k = int(rng.integers(1, e + 1))
+        m_over = int(rng.integers(0, e - k + 1)) if rng.random() < 0.4 else 0
+        mode = int(rng.choice([NONE, TD, ED]))
+        scope = int(rng.integers(0, 4))
+        gamma = float(rng.choice([0.0, 0.3, 0.5, 1.0, 1.3, 2.0, math.inf]))
+        metric = int(rng.integers(0, 4))
+        classes = rng.integers(0, 4, n).astype(np.uint8) if rng.random() < 0.4 else None
+        seed = int(rng.integers(0, 1000))
+        limit = bool(rng.random() < 0.4)
+        # few distinct logit values: ties in the top-k, at thresholds and between experts of a device
+        logits = rng.integers(-2, 3, (n, e)).astype(np.float32) * 0.5
+        r = orc.route_and_drop(logits, k, g, mode, scope, gamma, metric, classes, seed, m_over, limit)
+        cand, keep, cap = definition_in_python(r.scores, k, g, mode, scope, gamma, metric, classes, seed, m_over, limit)
+        what = dict(trial=trial, n=n, e=e, k=k, g=g, mode=mode, scope=scope, gamma=gamma, metric=metric, m=m_over,
+                    limit=limit, classes=classes is not None)
+        assert r.cap == cap, what
+        np.testing.assert_array_equal(r.cand, cand, err_msg=str(what))
+        np.testing.assert_array_equal(r.keep, keep, err_msg=str(what))
+        assert r.plan.rows == int(keep.sum())
+        checked += int(keep.sum() < cand.sum())
+    assert checked > 30       # the capacity (or the per-token limit) really binds in many of the cases
