@@ -446,6 +446,40 @@ def test_ffn_ragged_expert_sizes(orc):
     assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "ragged")
 
 
+@pytest.mark.parametrize("trial", range(5))
+def test_ffn_random_expert_sizes(orc, trial):
+    """Random row counts per expert (empty experts, 1 row, around every tile boundary, several tiles) and random
+    widths: both tile kinds, partly filled tiles, both output-tile widths of the down GEMM."""
+    rng = np.random.default_rng(300 + trial)
+    e = int(rng.integers(1, 10))
+    choices = [0, 1, 63, 64, 65, 128, 191, 192, 193, 255, 256, 257, 320, 383, 512, 600]
+    counts = [int(rng.choice(choices)) for _ in range(e)]
+    if sum(counts) == 0:
+        counts[0] = 70
+    d, h = int(rng.choice([128, 256, 384, 512])), int(rng.choice([128, 256, 640]))
+    n = sum(counts)
+    w = synth.scaled(W["olmoe"], name="ragged", n_tokens=n, d_model=d, n_experts=e, top_k=1, d_hidden=h,
+                     device_groups=1)
+    note("ffn random", dict(counts=counts, d=d, h=h))
+    layer = DeviceLayer(w, trial=trial)
+    owner = np.repeat(np.arange(e), counts)
+    rng.shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    desc = layer.desc(NONE, GLOBAL, 1.0)
+    buf = run_layer(layer, desc, logits)
+    assert_plan_equal(buf, ref, "ffn random")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "ffn random")
+    fused = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(fused, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         torch.from_numpy(logits).cuda(), fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.y, buf.y)
+
+
 def sample_tokens(ref, n, count, seed):
     rng = np.random.default_rng(seed)
     kept_per_token = ref.keep.sum(1)
