@@ -276,7 +276,11 @@ struct PipelinedLoop {
 #pragma unroll
         for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, 0);
 
-        for (int kt = 0; kt < KT; ++kt) {
+        // One slab: k-steps 0..2, the barrier, k-step 3.  MORE: there is a next slab to read operands of;
+        // REFILL: there is a slab kt+2 to request.  Both are compile-time so that the steady state carries no
+        // branches between its matrix instructions; the last two slabs run the other instances.
+        auto slab = [&](int kt, auto more_c, auto refill_c) {
+            constexpr bool MORE = decltype(more_c)::value, REFILL = decltype(refill_c)::value;
             const uint8_t* s = smem + (kt & 1) * STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < 3; ++ks) {
@@ -292,22 +296,25 @@ struct PipelinedLoop {
                 }
             }
             // slab kt+1 has landed for this wave and this wave no longer reads slab kt
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0) & ~(15 << 8));
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE_BYTES;
-            const bool more = kt + 1 < KT, refill = kt + 2 < KT;
 #pragma unroll
             for (int q = 0; q < NSTEP3; ++q) {
                 if (q < NMFMA) {
                     const int j = q / TN, i = q % TN;
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
                 }
-                if (q < NREAD && more) read_item(q, 0, sn, 0);
-                if (q < LOADS && refill) fill_one(q, kt + 2);
+                if (MORE && q < NREAD) read_item(q, 0, sn, 0);
+                if (REFILL && q < LOADS) fill_one(q, kt + 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        };
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) slab(kt, std::true_type{}, std::true_type{});
+        if (kt + 1 < KT) slab(kt++, std::true_type{}, std::false_type{});
+        slab(kt, std::false_type{}, std::false_type{});
     }
 };
 
@@ -415,7 +422,8 @@ struct TileConfig {
 
     using Loop = typename std::conditional<STAGES == 0, PipelinedLoop<BM, BN, NW, TM, TN, LOADS>,
                                            MainLoop<BM, BN, BK, (STAGES == 0 ? 2 : STAGES), NW, TM, TN, LOADS>>::type;
-    Loop loop{smem, src, a_off, a_sw, b_off, b_sw, K / BK, wv, lk};
+    // the wave id as a scalar: LDS destinations of the fills (M0) are then computed on the scalar unit
+    Loop loop{smem, src, a_off, a_sw, b_off, b_sw, K / BK, __builtin_amdgcn_readfirstlane(wv), lk};
     if (live == TM)
         loop.template run<TM>(acc);
     else if (TM > 2 && live == 3)
