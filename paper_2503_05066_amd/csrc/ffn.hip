@@ -141,18 +141,39 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // at zero" (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at 7, lgkmcnt 11:8).
 __host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | ((n >> 4) << 14); }
 
+// What a wave needs to request its pieces of a K slab: one buffer descriptor per operand tensor (the
+// block's activation rows, its weight rows, and for SwiGLU tiles the up-projection rows) and one 32-bit
+// byte offset per wave-wide load.  Load i uses the activations for i < A_LOADS, the second weight tensor
+// from B1_FROM on.  The loads are MUBUF loads with an LDS destination: unlike the global (FLAT-encoded)
+// form, the compiler does not count them against the LDS counter, so the operand reads of the matrix
+// loop keep fine-grained waits; the K advance goes into the scalar offset.
+template <int LOADS, int A_LOADS, int B1_FROM>
+struct Fills {
+    __amdgpu_buffer_rsrc_t a, b0, b1;
+    uint32_t voff[LOADS];
+    template <int I>
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc() const {
+        return I < A_LOADS ? a : (I >= B1_FROM ? b1 : b0);
+    }
+    __device__ __forceinline__ void one(int i, uint8_t* lds_dst, uint32_t k_bytes) const {
+        // i is a compile-time constant after unrolling
+        const __amdgpu_buffer_rsrc_t r = i < A_LOADS ? a : (i >= B1_FROM ? b1 : b0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lptr_t)lds_dst, 16, voff[i], k_bytes, 0, 0);
+    }
+};
+
 // K loop of one wave.  A ring of STAGES LDS stages: while stage kt is multiplied, the fills of
 // the next STAGES-1 slabs are in flight (asynchronous, straight from global memory into LDS); one
 // barrier per slab separates the readers of a stage from its next fill.
 // LIVE = number of 32-row activation sub-tiles that are multiplied (the rest lie past the expert's
 // last row).
-template <int BM, int BN, int BK, int STAGES, int NW, int TM, int TN, int LOADS>
+template <int BM, int BN, int BK, int STAGES, int NW, int TM, int TN, int LOADS, class FillsT>
 struct MainLoop {
     static constexpr int ROW_BYTES = BK * 2;
     static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
     static constexpr int CPR = BK / 8;  // 16-byte pieces per row
     uint8_t* smem;
-    const uint16_t* const* src;
+    const FillsT& fills;
     const int* a_off;
     const int* a_sw;
     const int* b_off;
@@ -162,9 +183,7 @@ struct MainLoop {
     __device__ __forceinline__ void fill(int kt) const {
         uint8_t* dst = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BK), (lptr_t)(dst + (wv + NW * i) * 1024),
-                                             16, 0, 0);
+        for (int i = 0; i < LOADS; ++i) fills.one(i, dst + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
     }
 
     template <int LIVE>
@@ -213,12 +232,12 @@ struct MainLoop {
 //     k-step 3 of slab kt:     MFMAs              |  operand reads of slab kt+1 step 0, fills of slab kt+2
 // Operands are read in the order the next step's MFMAs need them, so every read has a full k-step
 // of matrix work to hide behind.  __builtin_amdgcn_sched_barrier(0) pins the order written here.
-template <int BM, int BN, int NW, int TM, int TN, int LOADS>
+template <int BM, int BN, int NW, int TM, int TN, int LOADS, class FillsT>
 struct PipelinedLoop {
     static constexpr int BK = 64;
     static constexpr int STAGE_BYTES = (BM + BN) * 128;
     uint8_t* smem;
-    const uint16_t* const* src;
+    const FillsT& fills;
     const int* a_off;
     const int* a_sw;
     const int* b_off;
@@ -226,8 +245,7 @@ struct PipelinedLoop {
     int KT, wv, lk;
 
     __device__ __forceinline__ void fill_one(int i, int kt) const {
-        __builtin_amdgcn_global_load_lds((gptr_t)(src[i] + (size_t)kt * BK),
-                                         (lptr_t)(smem + (kt & 1) * STAGE_BYTES + (wv + NW * i) * 1024), 16, 0, 0);
+        fills.one(i, smem + (kt & 1) * STAGE_BYTES + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
     }
     __device__ __forceinline__ void fill(int kt) const {
 #pragma unroll
@@ -365,23 +383,33 @@ struct TileConfig {
     const int wm = wv / WAVES_N, wn = wv % WAVES_N;
 
     // ---- sources of this lane's pieces ----
-    const uint16_t* src[LOADS];
+    // Each descriptor opens the block's own window of a tensor (its activation rows, its weight rows), so
+    // 32-bit byte offsets suffice whatever the tensor size; with a gather list the window is the whole
+    // unpermuted input, whose size the host checks.
+    constexpr int A_LOADS = A_GROUPS / NW, B_LOADS = LOADS - A_LOADS;
+    constexpr int B1_FROM = SWIGLU ? A_LOADS + B_LOADS / 2 : LOADS;
+    static_assert(A_GROUPS % NW == 0 && (!SWIGLU || B_LOADS % 2 == 0), "a wave-wide load must not straddle two tensors");
+    constexpr int kRsrcFlags = 0x00020000;  // raw buffer of 32-bit words, no swizzle (gfx9 descriptor word 3)
+    using FillsT = Fills<LOADS, A_LOADS, B1_FROM>;
+    FillsT fills;
+    fills.a = __builtin_amdgcn_make_buffer_rsrc((void*)(gather ? A : A + (size_t)row0 * K), 0, -1, kRsrcFlags);
+    fills.b0 = __builtin_amdgcn_make_buffer_rsrc((void*)(B0 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags);
+    fills.b1 = SWIGLU ? __builtin_amdgcn_make_buffer_rsrc((void*)(B1 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags)
+                      : fills.b0;
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
         const int g = wv + NW * i;               // row group inside the stage (wave-uniform)
         const int r = g * RPL + lane / CPR;      // row inside the stage: A rows first, then weight rows
         const int kc = (lane % CPR) ^ (CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3);
-        if (g < A_GROUPS) {
+        if (i < A_LOADS) {
             const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
             // with a gather list the activation rows are fetched from the unpermuted input
-            const int arow = gather ? gather[row0 + rr] : row0 + rr;
-            src[i] = A + (size_t)arow * K + kc * 8;
+            const uint32_t arow = gather ? (uint32_t)gather[row0 + rr] : (uint32_t)rr;
+            fills.voff[i] = (arow * (uint32_t)K + kc * 8) * 2u;
         } else {
-            const int rb = r - BM;
-            if (SWIGLU && rb >= BN / 2)
-                src[i] = B1 + ((size_t)e * Nout + n0 + rb - BN / 2) * K + kc * 8;
-            else
-                src[i] = B0 + ((size_t)e * Nout + n0 + rb) * K + kc * 8;
+            int rb = r - BM;
+            if (SWIGLU && rb >= BN / 2) rb -= BN / 2;  // the up-projection rows of the same hidden columns
+            fills.voff[i] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
         }
     }
 
@@ -420,10 +448,10 @@ struct TileConfig {
     int live = (rows - wm * WTM + 31) / 32;
     live = __builtin_amdgcn_readfirstlane(live < 0 ? 0 : (live > TM ? TM : live));
 
-    using Loop = typename std::conditional<STAGES == 0, PipelinedLoop<BM, BN, NW, TM, TN, LOADS>,
-                                           MainLoop<BM, BN, BK, (STAGES == 0 ? 2 : STAGES), NW, TM, TN, LOADS>>::type;
+    using Loop = typename std::conditional<STAGES == 0, PipelinedLoop<BM, BN, NW, TM, TN, LOADS, FillsT>,
+                                           MainLoop<BM, BN, BK, (STAGES == 0 ? 2 : STAGES), NW, TM, TN, LOADS, FillsT>>::type;
     // the wave id as a scalar: LDS destinations of the fills (M0) are then computed on the scalar unit
-    Loop loop{smem, src, a_off, a_sw, b_off, b_sw, K / BK, __builtin_amdgcn_readfirstlane(wv), lk};
+    Loop loop{smem, fills, a_off, a_sw, b_off, b_sw, K / BK, __builtin_amdgcn_readfirstlane(wv), lk};
     if (live == TM)
         loop.template run<TM>(acc);
     else if (TM > 2 && live == 3)
