@@ -149,6 +149,7 @@ __host__ __device__ constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4)
 // loop keep fine-grained waits; the K advance goes into the scalar offset.
 template <int LOADS, int A_LOADS, int B1_FROM>
 struct Fills {
+    static constexpr int kALoads = A_LOADS;
     __amdgpu_buffer_rsrc_t a, b0, b1;
     uint32_t voff[LOADS];
     template <int I>
@@ -235,7 +236,12 @@ struct MainLoop {
 template <int BM, int BN, int NW, int TM, int TN, int LOADS, class FillsT>
 struct PipelinedLoop {
     static constexpr int BK = 64;
-    static constexpr int STAGE_BYTES = (BM + BN) * 128;
+    // LDS: two slots of activation rows, then a ring of three slots of weight rows.  The weights are the
+    // operand that streams from HBM, so their fills run two slabs ahead (a window of two slab times to
+    // land); activation tiles are shared by the blocks of a column group and come from L2: one slab ahead.
+    static constexpr int A_SLOT = BM * 128, B_SLOT = BN * 128, B_BASE = 2 * A_SLOT;
+    static constexpr int LDS_BYTES = 2 * A_SLOT + 3 * B_SLOT;
+    static constexpr int A_LOADS = FillsT::kALoads, B_LOADS = LOADS - A_LOADS;
     uint8_t* smem;
     const FillsT& fills;
     const int* a_off;
@@ -244,21 +250,44 @@ struct PipelinedLoop {
     const int* b_sw;
     int KT, wv, lk;
 
-    __device__ __forceinline__ void fill_one(int i, int kt) const {
-        fills.one(i, smem + (kt & 1) * STAGE_BYTES + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+    // load i of a slab: the activation loads come first
+    __device__ __forceinline__ void fill_a(int i, int kt) const {
+        fills.one(i, smem + (kt & 1) * A_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
     }
-    __device__ __forceinline__ void fill(int kt) const {
+    __device__ __forceinline__ void fill_b(int i, int kt, int slot) const {
+        fills.one(A_LOADS + i, smem + B_BASE + slot * B_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+    }
+    __device__ __forceinline__ void fill_a_all(int kt) const {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) fill_one(i, kt);
+        for (int i = 0; i < A_LOADS; ++i) fill_a(i, kt);
+    }
+    __device__ __forceinline__ void fill_b_all(int kt, int slot) const {
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) fill_b(i, kt, slot);
     }
 
     template <int LIVE>
     __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
+        // Fill schedule (every wave, also one with nothing to multiply):
+        //   before the loop   A(0) B(0) | barrier | B(1) A(1) B(2)
+        //   after barrier kt  A(kt+2) B(kt+3)           (the slots slab kt has just released)
+        // Loads complete in order, so "all but the last B_LOADS" at barrier kt means A(kt+1) and B(kt+1) have
+        // landed while B(kt+2) may still be in flight.
+        fill_a_all(0);
+        fill_b_all(0, 0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_barrier();
+        if (1 < KT) fill_b_all(1, 1);
+        if (1 < KT) fill_a_all(1);
+        if (2 < KT) fill_b_all(2, 2);
         if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
-            for (int kt = 0; kt <= KT; ++kt) {
-                if (kt < KT) fill(kt);
+            int slot = 0;
+            for (int kt = 0; kt < KT; ++kt) {
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 __builtin_amdgcn_s_barrier();
+                if (kt + 2 < KT) fill_a_all(kt + 2);
+                if (kt + 3 < KT) fill_b_all(kt + 3, slot);
+                slot = slot == 2 ? 0 : slot + 1;
             }
             return;
         }
@@ -267,39 +296,37 @@ struct PipelinedLoop {
         constexpr int NSTEP = NMFMA > NREAD ? NMFMA : NREAD;
         constexpr int NSTEP3 = NSTEP > LOADS ? NSTEP : LOADS;
         bf16x8 xa[2][NL], wb[2][TN];
-        // lane's operand addresses for k-step 0 of stage 0; step ks flips piece bits 1-2 (byte bits 5-6)
+        // lane's operand addresses for k-step 0 inside a slot; step ks flips piece bits 1-2 (byte bits 5-6)
         int ra[NL], rb[TN];
 #pragma unroll
         for (int j = 0; j < NL; ++j) ra[j] = a_off[j] + ((lk ^ a_sw[j]) << 4);
 #pragma unroll
-        for (int i = 0; i < TN; ++i) rb[i] = b_off[i] + ((lk ^ b_sw[i]) << 4);
+        for (int i = 0; i < TN; ++i) rb[i] = b_off[i] - BM * 128 + ((lk ^ b_sw[i]) << 4);
 
         // r-th operand read of a k-step, in the order the MFMAs (activation sub-tile major) need them:
         // weight 0, activation 0, weights 1.., activations 1..
-        auto read_item = [&](int r, int set, const uint8_t* s, int flip) {
+        auto read_item = [&](int r, int set, const uint8_t* sa, const uint8_t* sb, int flip) {
             if (r == 0)
-                wb[set][0] = *(const bf16x8*)(s + (rb[0] ^ flip));
+                wb[set][0] = *(const bf16x8*)(sb + (rb[0] ^ flip));
             else if (r == 1)
-                xa[set][0] = *(const bf16x8*)(s + (ra[0] ^ flip));
+                xa[set][0] = *(const bf16x8*)(sa + (ra[0] ^ flip));
             else if (r <= TN)
-                wb[set][r - 1] = *(const bf16x8*)(s + (rb[r - 1] ^ flip));
+                wb[set][r - 1] = *(const bf16x8*)(sb + (rb[r - 1] ^ flip));
             else
-                xa[set][r - TN] = *(const bf16x8*)(s + (ra[r - TN] ^ flip));
+                xa[set][r - TN] = *(const bf16x8*)(sa + (ra[r - TN] ^ flip));
         };
-
-        fill(0);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-        __builtin_amdgcn_s_barrier();
-        if (1 < KT) fill(1);
 #pragma unroll
-        for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, 0);
+        for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, smem + B_BASE, 0);
 
         // One slab: k-steps 0..2, the barrier, k-step 3.  MORE: there is a next slab to read operands of;
-        // REFILL: there is a slab kt+2 to request.  Both are compile-time so that the steady state carries no
-        // branches between its matrix instructions; the last two slabs run the other instances.
-        auto slab = [&](int kt, auto more_c, auto refill_c) {
-            constexpr bool MORE = decltype(more_c)::value, REFILL = decltype(refill_c)::value;
-            const uint8_t* s = smem + (kt & 1) * STAGE_BYTES;
+        // REFILL_A / REFILL_B: slabs kt+2 / kt+3 exist and are requested.  Compile-time, so that the steady
+        // state carries no branches between its matrix instructions; the last three slabs run the other
+        // instances.  slot = kt mod 3.
+        auto slab = [&](int kt, int slot, auto more_c, auto refill_a_c, auto refill_b_c) {
+            constexpr bool MORE = decltype(more_c)::value, REFILL_A = decltype(refill_a_c)::value,
+                           REFILL_B = decltype(refill_b_c)::value;
+            const uint8_t* sa = smem + (kt & 1) * A_SLOT;
+            const uint8_t* sb = smem + B_BASE + slot * B_SLOT;
 #pragma unroll
             for (int ks = 0; ks < 3; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1, flip = (ks + 1) << 5;
@@ -309,30 +336,49 @@ struct PipelinedLoop {
                         const int j = q / TN, i = q % TN;
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
                     }
-                    if (q < NREAD) read_item(q, nxt, s, flip);
+                    if (q < NREAD) read_item(q, nxt, sa, sb, flip);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            // slab kt+1 has landed for this wave and this wave no longer reads slab kt
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            // slab kt+1 has landed for this wave (the younger weight fill may still fly) and this wave no
+            // longer reads slab kt
+            if (REFILL_A)
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(B_LOADS));
+            else
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            const uint8_t* sn = smem + ((kt + 1) & 1) * STAGE_BYTES;
+            const int next_slot = slot == 2 ? 0 : slot + 1;
+            const uint8_t* na = smem + ((kt + 1) & 1) * A_SLOT;
+            const uint8_t* nb = smem + B_BASE + next_slot * B_SLOT;
 #pragma unroll
             for (int q = 0; q < NSTEP3; ++q) {
                 if (q < NMFMA) {
                     const int j = q / TN, i = q % TN;
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
                 }
-                if (MORE && q < NREAD) read_item(q, 0, sn, 0);
-                if (REFILL && q < LOADS) fill_one(q, kt + 2);
+                if (MORE && q < NREAD) read_item(q, 0, na, nb, 0);
+                if (REFILL_A && q < A_LOADS) fill_a(q, kt + 2);
+                if (REFILL_B && q >= A_LOADS && q < LOADS) fill_b(q - A_LOADS, kt + 3, slot);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        int kt = 0;
-        for (; kt + 2 < KT; ++kt) slab(kt, std::true_type{}, std::true_type{});
-        if (kt + 1 < KT) slab(kt++, std::true_type{}, std::false_type{});
-        slab(kt, std::false_type{}, std::false_type{});
+        int kt = 0, slot = 0;
+        const std::true_type yes{};
+        const std::false_type no{};
+        for (; kt + 3 < KT; ++kt) {
+            slab(kt, slot, yes, yes, yes);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        if (kt + 2 < KT) {
+            slab(kt++, slot, yes, yes, no);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        if (kt + 1 < KT) {
+            slab(kt++, slot, yes, no, no);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        slab(kt, slot, no, no, no);
     }
 };
 
@@ -357,7 +403,7 @@ struct TileConfig {
     static constexpr int kBM = BM, kBN = BN;
     static constexpr int kNCols = SWIGLU ? BN / 2 : BN;
     static constexpr int kThreads = 64 * WAVES_M * WAVES_N;
-    static constexpr int kLdsBytes = (STAGES == 0 ? 2 : STAGES) * (BM + BN) * BK * 2;
+    static constexpr int kLdsBytes = STAGES == 0 ? 2 * BM * 128 + 3 * BN * 128 : STAGES * (BM + BN) * BK * 2;
 
     static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
                                                const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
