@@ -269,32 +269,37 @@ struct PipelinedLoop {
     template <int LIVE>
     __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
         // Fill schedule (every wave, also one with nothing to multiply):
-        //   before the loop   A(0) B(0) | barrier | B(1) A(1) B(2)
-        //   after barrier kt  A(kt+2) B(kt+3)           (the slots slab kt has just released)
+        //   before the loop        A(0) B(0) | barrier | A(1) B(1)
+        //   k-steps 0..2 of slab kt  B(kt+2), one load every few matrix instructions (its slot was released
+        //                            at barrier kt-1)
+        //   after barrier kt         A(kt+2) (the slot slab kt has just released)
+        // so the address unit sees an even stream of requests instead of every wave's whole slab at once.
         // Loads complete in order, so "all but the last B_LOADS" at barrier kt means A(kt+1) and B(kt+1) have
         // landed while B(kt+2) may still be in flight.
         fill_a_all(0);
         fill_b_all(0, 0);
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         __builtin_amdgcn_s_barrier();
-        if (1 < KT) fill_b_all(1, 1);
         if (1 < KT) fill_a_all(1);
-        if (2 < KT) fill_b_all(2, 2);
+        if (1 < KT) fill_b_all(1, 1);
         if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
-            int slot = 0;
+            int slot2 = 2;  // slot of slab kt + 2
             for (int kt = 0; kt < KT; ++kt) {
+                if (kt + 2 < KT) fill_b_all(kt + 2, slot2);
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
                 __builtin_amdgcn_s_barrier();
                 if (kt + 2 < KT) fill_a_all(kt + 2);
-                if (kt + 3 < KT) fill_b_all(kt + 3, slot);
-                slot = slot == 2 ? 0 : slot + 1;
+                slot2 = slot2 == 2 ? 0 : slot2 + 1;
             }
             return;
         }
         constexpr int NL = LIVE > 0 ? LIVE : 1;
         constexpr int NMFMA = TN * NL, NREAD = NL + TN;
         constexpr int NSTEP = NMFMA > NREAD ? NMFMA : NREAD;
-        constexpr int NSTEP3 = NSTEP > LOADS ? NSTEP : LOADS;
+        constexpr int A_EVERY = NSTEP / A_LOADS > 0 ? NSTEP / A_LOADS : 1;  // k-step 3: one A load per A_EVERY steps
+        constexpr int NSTEP3 = NSTEP > A_LOADS ? NSTEP : A_LOADS;
+        static_assert(3 * NSTEP >= B_LOADS, "room for the weight loads in k-steps 0..2");
+        constexpr int B_FIRST = 3 * NSTEP >= 2 * B_LOADS ? 1 : 0;
         bf16x8 xa[2][NL], wb[2][TN];
         // lane's operand addresses for k-step 0 inside a slot; step ks flips piece bits 1-2 (byte bits 5-6)
         int ra[NL], rb[TN];
@@ -319,14 +324,14 @@ struct PipelinedLoop {
         for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, smem + B_BASE, 0);
 
         // One slab: k-steps 0..2, the barrier, k-step 3.  MORE: there is a next slab to read operands of;
-        // REFILL_A / REFILL_B: slabs kt+2 / kt+3 exist and are requested.  Compile-time, so that the steady
-        // state carries no branches between its matrix instructions; the last three slabs run the other
-        // instances.  slot = kt mod 3.
-        auto slab = [&](int kt, int slot, auto more_c, auto refill_a_c, auto refill_b_c) {
-            constexpr bool MORE = decltype(more_c)::value, REFILL_A = decltype(refill_a_c)::value,
-                           REFILL_B = decltype(refill_b_c)::value;
+        // REFILL: slab kt+2 exists and is requested.  Compile-time, so that the steady state carries no
+        // branches between its matrix instructions; the last two slabs run the other instances.
+        // slot = kt mod 3.
+        auto slab = [&](int kt, int slot, auto more_c, auto refill_c) {
+            constexpr bool MORE = decltype(more_c)::value, REFILL = decltype(refill_c)::value;
             const uint8_t* sa = smem + (kt & 1) * A_SLOT;
             const uint8_t* sb = smem + B_BASE + slot * B_SLOT;
+            const int slot2 = slot == 0 ? 2 : slot - 1;  // (kt + 2) mod 3
 #pragma unroll
             for (int ks = 0; ks < 3; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1, flip = (ks + 1) << 5;
@@ -337,12 +342,17 @@ struct PipelinedLoop {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
                     }
                     if (q < NREAD) read_item(q, nxt, sa, sb, flip);
+                    if (REFILL) {
+#pragma unroll
+                        for (int i = 0; i < B_LOADS; ++i)
+                            if (ks * NSTEP + q == (i * 3 * NSTEP) / B_LOADS + B_FIRST) fill_b(i, kt + 2, slot2);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             // slab kt+1 has landed for this wave (the younger weight fill may still fly) and this wave no
             // longer reads slab kt
-            if (REFILL_A)
+            if (REFILL)
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(B_LOADS));
             else
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
@@ -358,27 +368,22 @@ struct PipelinedLoop {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
                 }
                 if (MORE && q < NREAD) read_item(q, 0, na, nb, 0);
-                if (REFILL_A && q < A_LOADS) fill_a(q, kt + 2);
-                if (REFILL_B && q >= A_LOADS && q < LOADS) fill_b(q - A_LOADS, kt + 3, slot);
+                if (REFILL && q % A_EVERY == 0 && q / A_EVERY < A_LOADS) fill_a(q / A_EVERY, kt + 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         int kt = 0, slot = 0;
         const std::true_type yes{};
         const std::false_type no{};
-        for (; kt + 3 < KT; ++kt) {
-            slab(kt, slot, yes, yes, yes);
-            slot = slot == 2 ? 0 : slot + 1;
-        }
-        if (kt + 2 < KT) {
-            slab(kt++, slot, yes, yes, no);
+        for (; kt + 2 < KT; ++kt) {
+            slab(kt, slot, yes, yes);
             slot = slot == 2 ? 0 : slot + 1;
         }
         if (kt + 1 < KT) {
-            slab(kt++, slot, yes, no, no);
+            slab(kt++, slot, yes, no);
             slot = slot == 2 ? 0 : slot + 1;
         }
-        slab(kt, slot, no, no, no);
+        slab(kt, slot, no, no);
     }
 };
 
@@ -560,6 +565,298 @@ struct TileConfig {
 }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Big tiles: 16x16x32 matrix instructions, four waves
+// ---------------------------------------------------------------------------------------------
+// Under sustained load the chip is power-limited, so what a kernel reaches is set by the energy it spends
+// per flop.  Measured on this part with random operands: the 16x16x32 instruction sustains about 10 % more
+// flops than 32x32x16 (half the accumulator traffic per flop), and a wave tile of 128 x 128 needs a third
+// fewer LDS operand reads per flop than 128 x 64.  With one wave per SIMD nothing hides a stalled
+// instruction, so the requests for the next slabs are spread over the whole slab (a burst of fills from
+// every wave right after the barrier backs up the address unit and stalls the matrix pipe behind it).
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// c += a x b with the accumulator pinned to the accumulation registers: a wave of these tiles holds 256
+// accumulator values, exactly the accumulation half of its register budget, and must never shuffle them
+// through the other half.  The compiler does not see the instruction inside the statement, so the code
+// that reads the accumulators after the last one waits out its latency itself.
+__device__ __forceinline__ void mfma_16x16x32(f32x4& c, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+// K loop of a wave.  LDS: two slots of activation rows, then a ring of three slots of weight rows (the
+// operand that streams from HBM gets a window of up to two slabs to land).  A slab is two 32-wide k-steps;
+// matrix instructions lag the operand reads by one k-step:
+//     k-step 0 of slab kt:  MFMAs  |  operand reads of k-step 1  |  requests for the weights of slab kt+2
+//     barrier kt (slab kt+1 landed, slab kt no longer read)
+//     k-step 1 of slab kt:  MFMAs  |  operand reads of slab kt+1 |  requests for the activations of slab kt+2
+// Loads complete in order, so "all but the last B_LOADS" at barrier kt means the activations and weights of
+// slab kt+1 have landed while the weights of slab kt+2 may still be in flight.  LIVE = number of 16-row
+// activation sub-tiles that are multiplied (the rest lie past the expert's last row).
+template <int BM, int BN, int NW, int TM, int TN, int WTN, bool SWIGLU, int LOADS, class FillsT>
+struct PipelinedLoop16 {
+    static constexpr int BK = 64;
+    static constexpr int A_SLOT = BM * 128, B_SLOT = BN * 128, B_BASE = 2 * A_SLOT;
+    static constexpr int LDS_BYTES = 2 * A_SLOT + 3 * B_SLOT;
+    static constexpr int A_LOADS = FillsT::kALoads, B_LOADS = LOADS - A_LOADS;
+    uint8_t* smem;
+    const FillsT& fills;
+    int a_lane, b_lane;  // byte offset, inside a slot, of this lane's piece of the wave's first row (k-step 0)
+    int KT, wv;
+
+    // byte offset of weight sub-tile i relative to the wave's first weight row: with SwiGLU the second half
+    // of the sub-tiles are the up-projection rows of the same hidden columns
+    static __device__ __forceinline__ constexpr int b_tile(int i) {
+        return SWIGLU ? ((i / (TN / 2)) * (BN / 2) + (i % (TN / 2)) * 16) * 128 : i * 16 * 128;
+    }
+    __device__ __forceinline__ void fill_a(int i, int kt) const {
+        fills.one(i, smem + (kt & 1) * A_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+    }
+    __device__ __forceinline__ void fill_b(int i, int kt, int slot) const {
+        fills.one(A_LOADS + i, smem + B_BASE + slot * B_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+    }
+    __device__ __forceinline__ void fill_a_all(int kt) const {
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) fill_a(i, kt);
+    }
+    __device__ __forceinline__ void fill_b_all(int kt, int slot) const {
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) fill_b(i, kt, slot);
+    }
+
+    template <int LIVE>
+    __device__ __forceinline__ void run(f32x4 (&acc)[TN][TM]) const {
+        fill_a_all(0);
+        fill_b_all(0, 0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+        __builtin_amdgcn_s_barrier();
+        if (1 < KT) fill_a_all(1);
+        if (1 < KT) fill_b_all(1, 1);
+        if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
+            int slot2 = 2;  // slot of slab kt + 2
+            for (int kt = 0; kt < KT; ++kt) {
+                if (kt + 2 < KT) fill_b_all(kt + 2, slot2);
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                __builtin_amdgcn_s_barrier();
+                if (kt + 2 < KT) fill_a_all(kt + 2);
+                slot2 = slot2 == 2 ? 0 : slot2 + 1;
+            }
+            return;
+        }
+        constexpr int NL = LIVE > 0 ? LIVE : 1;
+        constexpr int NMFMA = TN * NL, NREAD = NL + TN;
+        // reads go out in the first half of a k-step, so that they have returned long before the barrier
+        constexpr int READ_EVERY = NMFMA / 2 / NREAD > 0 ? NMFMA / 2 / NREAD : 1;
+        constexpr int B_EVERY = NMFMA / B_LOADS, A_EVERY = NMFMA / 2 / A_LOADS > 0 ? NMFMA / 2 / A_LOADS : 1;
+        static_assert(LIVE == 0 || (NMFMA >= NREAD * READ_EVERY && NMFMA >= B_LOADS && NMFMA >= A_LOADS * A_EVERY), "k-step too short");
+        bf16x8 xa[2][NL], wb[2][TN];
+
+        // r-th operand read of a k-step, in the order the MFMAs (activation sub-tile major) need them:
+        // weight 0, activation 0, weights 1.., activations 1..  pa / pb: this lane's piece of the wave's first
+        // activation / weight row in the slot and k-step being read.
+        auto read_item = [&](int r, int set, const uint8_t* pa, const uint8_t* pb) {
+            if (r == 0)
+                wb[set][0] = *(const bf16x8*)(pb + b_tile(0));
+            else if (r == 1)
+                xa[set][0] = *(const bf16x8*)(pa);
+            else if (r <= TN)
+                wb[set][r - 1] = *(const bf16x8*)(pb + b_tile(r - 1));
+            else
+                xa[set][r - TN] = *(const bf16x8*)(pa + (r - TN) * 16 * 128);
+        };
+#pragma unroll
+        for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem + a_lane, smem + B_BASE + b_lane);
+
+        // One slab.  MORE: there is a next slab to read operands of; REFILL: slab kt+2 exists and is
+        // requested.  Compile-time, so that the steady state carries no branches between its matrix
+        // instructions; the last two slabs run the other instances.  slot = kt mod 3.
+        auto slab = [&](int kt, int slot, auto more_c, auto refill_c) {
+            constexpr bool MORE = decltype(more_c)::value, REFILL = decltype(refill_c)::value;
+            const int slot2 = slot == 0 ? 2 : slot - 1;  // (kt + 2) mod 3
+            const int next_slot = slot == 2 ? 0 : slot + 1;
+            {
+                // the second k-step's pieces sit four pieces further: bit 6 of the byte offset
+                const uint8_t* pa = smem + (kt & 1) * A_SLOT + (a_lane ^ 64);
+                const uint8_t* pb = smem + B_BASE + slot * B_SLOT + (b_lane ^ 64);
+#pragma unroll
+                for (int q = 0; q < NMFMA; ++q) {
+                    const int j = q / TN, i = q % TN;
+                    mfma_16x16x32(acc[i][j], wb[0][i], xa[0][j]);
+                    if (q % READ_EVERY == 0 && q / READ_EVERY < NREAD) read_item(q / READ_EVERY, 1, pa, pb);
+                    if (REFILL && q % B_EVERY == B_EVERY / 2 && q / B_EVERY < B_LOADS) fill_b(q / B_EVERY, kt + 2, slot2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // slab kt+1 has landed for this wave (the younger weight requests may still fly), this wave's
+            // operand reads of slab kt have returned (the LDS counter is part of the wait)
+            if (REFILL)
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(B_LOADS));
+            else
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            {
+                const uint8_t* pa = smem + ((kt + 1) & 1) * A_SLOT + a_lane;
+                const uint8_t* pb = smem + B_BASE + next_slot * B_SLOT + b_lane;
+#pragma unroll
+                for (int q = 0; q < NMFMA; ++q) {
+                    const int j = q / TN, i = q % TN;
+                    mfma_16x16x32(acc[i][j], wb[1][i], xa[1][j]);
+                    if (MORE && q % READ_EVERY == 0 && q / READ_EVERY < NREAD) read_item(q / READ_EVERY, 0, pa, pb);
+                    if (REFILL && q % A_EVERY == A_EVERY / 2 && q / A_EVERY < A_LOADS) fill_a(q / A_EVERY, kt + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        int kt = 0, slot = 0;
+        const std::true_type yes{};
+        const std::false_type no{};
+        for (; kt + 2 < KT; ++kt) {
+            slab(kt, slot, yes, yes);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        if (kt + 1 < KT) {
+            slab(kt++, slot, yes, no);
+            slot = slot == 2 ? 0 : slot + 1;
+        }
+        slab(kt, slot, no, no);
+        // the last matrix instructions retire before anything else reads the accumulators
+        asm volatile("s_nop 15\n\ts_nop 15");
+    }
+};
+
+// Block tile of BM activation rows x BN weight rows, WAVES_M x WAVES_N waves, on the loop above.  Same LDS
+// row layout and the same requests as TileConfig with 64-wide slabs; only the lane-to-piece mapping of the
+// operand reads and of the accumulators differs: lane l reads row (l & 15), piece (l >> 4) of a k-step and
+// ends with output columns 4*(l >> 4) .. +3 of activation row (l & 15) of each 16 x 16 sub-tile.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
+struct TileConfig16 {
+    static constexpr int kBM = BM, kBN = BN;
+    static constexpr int kNCols = SWIGLU ? BN / 2 : BN;
+    static constexpr int kThreads = 64 * WAVES_M * WAVES_N;
+    static constexpr int kLdsBytes = 2 * BM * 128 + 3 * BN * 128;
+
+    static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+                                               const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
+                                               const int32_t* __restrict__ gather, int e, int row0, int rows, int n0,
+                                               int K, int Nout, uint8_t* smem) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    constexpr int TM = WTM / 16, TN = WTN / 16;
+    constexpr int A_GROUPS = BM / 8, GROUPS = (BM + BN) / 8;  // eight 128-byte rows per wave-wide load
+    constexpr int LOADS = GROUPS / NW, A_LOADS = A_GROUPS / NW, B_LOADS = LOADS - A_LOADS;
+    constexpr int B1_FROM = SWIGLU ? A_LOADS + B_LOADS / 2 : LOADS;
+    static_assert(GROUPS % NW == 0 && A_GROUPS % NW == 0 && (!SWIGLU || B_LOADS % 2 == 0),
+                  "a wave-wide load must not straddle two tensors");
+    static_assert(WTM % 32 == 0 && WTN % 16 == 0 && (!SWIGLU || TN % 2 == 0), "wave tile");
+    static_assert(B_LOADS < 64, "vmcnt range");
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int wm = wv / WAVES_N, wn = wv % WAVES_N;
+
+    // ---- sources of this lane's pieces (as in TileConfig) ----
+    constexpr int kRsrcFlags = 0x00020000;  // raw buffer of 32-bit words, no swizzle (gfx9 descriptor word 3)
+    using FillsT = Fills<LOADS, A_LOADS, B1_FROM>;
+    FillsT fills;
+    fills.a = __builtin_amdgcn_make_buffer_rsrc((void*)(gather ? A : A + (size_t)row0 * K), 0, -1, kRsrcFlags);
+    fills.b0 = __builtin_amdgcn_make_buffer_rsrc((void*)(B0 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags);
+    fills.b1 = SWIGLU ? __builtin_amdgcn_make_buffer_rsrc((void*)(B1 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags)
+                      : fills.b0;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        const int g = wv + NW * i;          // row group: activation rows first, then weight rows
+        const int r = g * 8 + lane / 8;
+        const int kc = (lane % 8) ^ ((r >> 1) & 7);
+        if (i < A_LOADS) {
+            const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
+            const uint32_t arow = gather ? (uint32_t)gather[row0 + rr] : (uint32_t)rr;
+            fills.voff[i] = (arow * (uint32_t)K + kc * 8) * 2u;
+        } else {
+            int rb = r - BM;
+            if (SWIGLU && rb >= BN / 2) rb -= BN / 2;  // the up-projection rows of the same hidden columns
+            fills.voff[i] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
+        }
+    }
+
+    // ---- this lane's operand pieces: row (lane & 15) of a sub-tile, piece (lane >> 4) of a k-step ----
+    // every sub-tile starts at a multiple of 16 rows, so the piece swizzle (row >> 1) & 7 depends on the
+    // lane only and the sub-tiles differ by constant offsets
+    const int lr = lane & 15, lk = lane >> 4;
+    const int piece0 = (lk ^ ((lr >> 1) & 7)) << 4;
+    const int a_lane = (wm * WTM + lr) * 128 + piece0;
+    const int b_lane = ((SWIGLU ? wn * (WTN / 2) : wn * WTN) + lr) * 128 + piece0;
+
+    f32x4 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+
+    // 16-row sub-tiles of this wave that hold rows of the expert, in pairs (wave-uniform); the main loop
+    // is specialised on it so that the common full tile carries no conditionals
+    int live = (rows - wm * WTM + 31) / 32 * 2;
+    live = __builtin_amdgcn_readfirstlane(live < 0 ? 0 : (live > TM ? TM : live));
+
+    using Loop = PipelinedLoop16<BM, BN, NW, TM, TN, WTN, SWIGLU, LOADS, FillsT>;
+    static_assert(Loop::LDS_BYTES == kLdsBytes, "LDS size");
+    Loop loop{smem, fills, a_lane, b_lane, K / 64, __builtin_amdgcn_readfirstlane(wv)};
+    if (live == TM)
+        loop.template run<TM>(acc);
+    else if (TM > 6 && live == 6)
+        loop.template run<(TM > 6 ? 6 : TM)>(acc);
+    else if (TM > 4 && live == 4)
+        loop.template run<(TM > 4 ? 4 : TM)>(acc);
+    else if (TM > 2 && live == 2)
+        loop.template run<(TM > 2 ? 2 : TM)>(acc);
+    else
+        loop.template run<0>(acc);
+
+    // ---- epilogue ----
+    // The tile is transposed through LDS (free after the K loop: its last barrier follows the last operand
+    // read) exactly as in TileConfig: bf16 rows of OUT_COLS columns, 16-byte piece p of row r at position
+    // p ^ (r mod PIECES), then every row leaves as consecutive 16-byte pieces of consecutive lanes.
+    constexpr int TNO = SWIGLU ? TN / 2 : TN;
+    constexpr int OUT_COLS = kNCols, ROWB = OUT_COLS * 2, PIECES = ROWB / 16;
+    static_assert(BM * ROWB <= kLdsBytes, "the output tile must fit in the operand slots");
+    static_assert((PIECES & (PIECES - 1)) == 0, "piece swizzle");
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int r = wm * WTM + j * 16 + lr;
+        uint8_t* lrow = smem + r * ROWB + (lk & 1) * 8;
+        const int sw = r & (PIECES - 1);
+#pragma unroll
+        for (int i = 0; i < TNO; ++i) {
+            const int piece = ((SWIGLU ? wn * (WTN / 2) : wn * WTN) + i * 16) / 8 + (lk >> 1);
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float g = acc[i][j][v];
+                if (SWIGLU) {
+                    const float u = acc[i + TN / 2][j][v];
+                    o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                } else {
+                    o[v] = g;
+                }
+            }
+            uint2 pk;
+            pk.x = pack_bf16x2(o[0], o[1]);
+            pk.y = pack_bf16x2(o[2], o[3]);
+            *(uint2*)(lrow + ((piece ^ sw) << 4)) = pk;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < BM * PIECES; idx += kThreads) {
+        const int r = idx / PIECES, pc = idx % PIECES;
+        if (r < rows) {
+            const uint4 v = *(const uint4*)(smem + r * ROWB + ((pc ^ (r & (PIECES - 1))) << 4));
+            *(uint4*)(C + (size_t)(row0 + r) * Nout + n0 + pc * 8) = v;
+        }
+    }
+}
+};
+
 // Decode a block's position in a list of `total` = tiles x column blocks work items, ordered
 // [column group][row tile][column in group].
 __device__ inline void decode_item(int logical, int nt, int col_group, int& tile, int& nb) {
@@ -643,17 +940,17 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
         // big tiles: 256 x 256 x 64, two stages, software-pipelined; small tiles: 64 x 256 x 64, four stages
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
-            launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, true>,
+            launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, true>,
                         true>(xp, w_gate, w_up, ws.hidden, row_token, ws, K1, N1, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         if (N2 % 256 == 0)
-            launch_bf16<TileConfig<kFfnTileM, 256, 64, 0, 2, 4, false>,
-                        TileConfig<kFfnTileSmall, 256, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
+            launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, false>,
+                        TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
                                                                                     K2, N2, st);
         else  // d is a multiple of 128 only: 128 output columns per block
-            launch_bf16<TileConfig<kFfnTileM, 128, 64, 0, 2, 4, false>,
-                        TileConfig<kFfnTileSmall, 128, 64, 4, 2, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
+            launch_bf16<TileConfig16<kFfnTileM, 128, 2, 2, false>,
+                        TileConfig<kFfnTileSmall, 128, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
                                                                                     K2, N2, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
