@@ -127,11 +127,13 @@ __global__ __launch_bounds__(256) void grouped_gemm_f32_kernel(const float* __re
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA path
 // ---------------------------------------------------------------------------------------------
+// two floats -> two bf16 (round to nearest even) in one word, lo in the low half: the hardware conversion
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-    const uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    const uint32_t ra = (a + 0x7fffu + ((a >> 16) & 1u)) >> 16;
-    const uint32_t rb = (b + 0x7fffu + ((b >> 16) & 1u)) & 0xffff0000u;
-    return ra | rb;
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *(const uint32_t*)&b;
 }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -224,169 +226,6 @@ struct MainLoop {
     }
 };
 
-// Software-pipelined K loop (two LDS stages of 64-wide slabs).  MFMAs lag the operand reads by one
-// 16-wide k-step and the two are interleaved one by one, so that LDS reads and the fills of the
-// next slab issue in the shadow of the matrix instructions (an MFMA occupies the matrix pipe for 32
-// cycles but the wave's issue port only for a few):
-//     k-step 0..2 of slab kt:  MFMAs of the step  |  operand reads of the next step
-//     barrier (slab kt+1 landed, slab kt no longer read)
-//     k-step 3 of slab kt:     MFMAs              |  operand reads of slab kt+1 step 0, fills of slab kt+2
-// Operands are read in the order the next step's MFMAs need them, so every read has a full k-step
-// of matrix work to hide behind.  __builtin_amdgcn_sched_barrier(0) pins the order written here.
-template <int BM, int BN, int NW, int TM, int TN, int LOADS, class FillsT>
-struct PipelinedLoop {
-    static constexpr int BK = 64;
-    // LDS: two slots of activation rows, then a ring of three slots of weight rows.  The weights are the
-    // operand that streams from HBM, so their fills run two slabs ahead (a window of two slab times to
-    // land); activation tiles are shared by the blocks of a column group and come from L2: one slab ahead.
-    static constexpr int A_SLOT = BM * 128, B_SLOT = BN * 128, B_BASE = 2 * A_SLOT;
-    static constexpr int LDS_BYTES = 2 * A_SLOT + 3 * B_SLOT;
-    static constexpr int A_LOADS = FillsT::kALoads, B_LOADS = LOADS - A_LOADS;
-    uint8_t* smem;
-    const FillsT& fills;
-    const int* a_off;
-    const int* a_sw;
-    const int* b_off;
-    const int* b_sw;
-    int KT, wv, lk;
-
-    // load i of a slab: the activation loads come first
-    __device__ __forceinline__ void fill_a(int i, int kt) const {
-        fills.one(i, smem + (kt & 1) * A_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
-    }
-    __device__ __forceinline__ void fill_b(int i, int kt, int slot) const {
-        fills.one(A_LOADS + i, smem + B_BASE + slot * B_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
-    }
-    __device__ __forceinline__ void fill_a_all(int kt) const {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) fill_a(i, kt);
-    }
-    __device__ __forceinline__ void fill_b_all(int kt, int slot) const {
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) fill_b(i, kt, slot);
-    }
-
-    template <int LIVE>
-    __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
-        // Fill schedule (every wave, also one with nothing to multiply):
-        //   before the loop        A(0) B(0) | barrier | A(1) B(1)
-        //   k-steps 0..2 of slab kt  B(kt+2), one load every few matrix instructions (its slot was released
-        //                            at barrier kt-1)
-        //   after barrier kt         A(kt+2) (the slot slab kt has just released)
-        // so the address unit sees an even stream of requests instead of every wave's whole slab at once.
-        // Loads complete in order, so "all but the last B_LOADS" at barrier kt means A(kt+1) and B(kt+1) have
-        // landed while B(kt+2) may still be in flight.
-        fill_a_all(0);
-        fill_b_all(0, 0);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-        __builtin_amdgcn_s_barrier();
-        if (1 < KT) fill_a_all(1);
-        if (1 < KT) fill_b_all(1, 1);
-        if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
-            int slot2 = 2;  // slot of slab kt + 2
-            for (int kt = 0; kt < KT; ++kt) {
-                if (kt + 2 < KT) fill_b_all(kt + 2, slot2);
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-                __builtin_amdgcn_s_barrier();
-                if (kt + 2 < KT) fill_a_all(kt + 2);
-                slot2 = slot2 == 2 ? 0 : slot2 + 1;
-            }
-            return;
-        }
-        constexpr int NL = LIVE > 0 ? LIVE : 1;
-        constexpr int NMFMA = TN * NL, NREAD = NL + TN;
-        constexpr int NSTEP = NMFMA > NREAD ? NMFMA : NREAD;
-        constexpr int A_EVERY = NSTEP / A_LOADS > 0 ? NSTEP / A_LOADS : 1;  // k-step 3: one A load per A_EVERY steps
-        constexpr int NSTEP3 = NSTEP > A_LOADS ? NSTEP : A_LOADS;
-        static_assert(3 * NSTEP >= B_LOADS, "room for the weight loads in k-steps 0..2");
-        constexpr int B_FIRST = 3 * NSTEP >= 2 * B_LOADS ? 1 : 0;
-        bf16x8 xa[2][NL], wb[2][TN];
-        // lane's operand addresses for k-step 0 inside a slot; step ks flips piece bits 1-2 (byte bits 5-6)
-        int ra[NL], rb[TN];
-#pragma unroll
-        for (int j = 0; j < NL; ++j) ra[j] = a_off[j] + ((lk ^ a_sw[j]) << 4);
-#pragma unroll
-        for (int i = 0; i < TN; ++i) rb[i] = b_off[i] - BM * 128 + ((lk ^ b_sw[i]) << 4);
-
-        // r-th operand read of a k-step, in the order the MFMAs (activation sub-tile major) need them:
-        // weight 0, activation 0, weights 1.., activations 1..
-        auto read_item = [&](int r, int set, const uint8_t* sa, const uint8_t* sb, int flip) {
-            if (r == 0)
-                wb[set][0] = *(const bf16x8*)(sb + (rb[0] ^ flip));
-            else if (r == 1)
-                xa[set][0] = *(const bf16x8*)(sa + (ra[0] ^ flip));
-            else if (r <= TN)
-                wb[set][r - 1] = *(const bf16x8*)(sb + (rb[r - 1] ^ flip));
-            else
-                xa[set][r - TN] = *(const bf16x8*)(sa + (ra[r - TN] ^ flip));
-        };
-#pragma unroll
-        for (int r = 0; r < NREAD; ++r) read_item(r, 0, smem, smem + B_BASE, 0);
-
-        // One slab: k-steps 0..2, the barrier, k-step 3.  MORE: there is a next slab to read operands of;
-        // REFILL: slab kt+2 exists and is requested.  Compile-time, so that the steady state carries no
-        // branches between its matrix instructions; the last two slabs run the other instances.
-        // slot = kt mod 3.
-        auto slab = [&](int kt, int slot, auto more_c, auto refill_c) {
-            constexpr bool MORE = decltype(more_c)::value, REFILL = decltype(refill_c)::value;
-            const uint8_t* sa = smem + (kt & 1) * A_SLOT;
-            const uint8_t* sb = smem + B_BASE + slot * B_SLOT;
-            const int slot2 = slot == 0 ? 2 : slot - 1;  // (kt + 2) mod 3
-#pragma unroll
-            for (int ks = 0; ks < 3; ++ks) {
-                const int cur = ks & 1, nxt = cur ^ 1, flip = (ks + 1) << 5;
-#pragma unroll
-                for (int q = 0; q < NSTEP; ++q) {
-                    if (q < NMFMA) {
-                        const int j = q / TN, i = q % TN;
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[cur][i], xa[cur][j], acc[i][j], 0, 0, 0);
-                    }
-                    if (q < NREAD) read_item(q, nxt, sa, sb, flip);
-                    if (REFILL) {
-#pragma unroll
-                        for (int i = 0; i < B_LOADS; ++i)
-                            if (ks * NSTEP + q == (i * 3 * NSTEP) / B_LOADS + B_FIRST) fill_b(i, kt + 2, slot2);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            // slab kt+1 has landed for this wave (the younger weight fill may still fly) and this wave no
-            // longer reads slab kt
-            if (REFILL)
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(B_LOADS));
-            else
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            const int next_slot = slot == 2 ? 0 : slot + 1;
-            const uint8_t* na = smem + ((kt + 1) & 1) * A_SLOT;
-            const uint8_t* nb = smem + B_BASE + next_slot * B_SLOT;
-#pragma unroll
-            for (int q = 0; q < NSTEP3; ++q) {
-                if (q < NMFMA) {
-                    const int j = q / TN, i = q % TN;
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[1][i], xa[1][j], acc[i][j], 0, 0, 0);
-                }
-                if (MORE && q < NREAD) read_item(q, 0, na, nb, 0);
-                if (REFILL && q % A_EVERY == 0 && q / A_EVERY < A_LOADS) fill_a(q / A_EVERY, kt + 2);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        int kt = 0, slot = 0;
-        const std::true_type yes{};
-        const std::false_type no{};
-        for (; kt + 2 < KT; ++kt) {
-            slab(kt, slot, yes, yes);
-            slot = slot == 2 ? 0 : slot + 1;
-        }
-        if (kt + 1 < KT) {
-            slab(kt++, slot, yes, no);
-            slot = slot == 2 ? 0 : slot + 1;
-        }
-        slab(kt, slot, no, no);
-    }
-};
-
 // Block tile: BM activation rows x BN weight rows, K slab BK (32 or 64); WAVES_M x WAVES_N waves.
 //
 // An LDS stage is (BM + BN) rows of BK bf16.  Rows are filled by direct global->LDS loads: one
@@ -408,7 +247,7 @@ struct TileConfig {
     static constexpr int kBM = BM, kBN = BN;
     static constexpr int kNCols = SWIGLU ? BN / 2 : BN;
     static constexpr int kThreads = 64 * WAVES_M * WAVES_N;
-    static constexpr int kLdsBytes = STAGES == 0 ? 2 * BM * 128 + 3 * BN * 128 : STAGES * (BM + BN) * BK * 2;
+    static constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2;
 
     static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
                                                const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
@@ -426,11 +265,9 @@ struct TileConfig {
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
     static_assert(!SWIGLU || TN % 2 == 0, "a wave needs matching gate and up columns");
     static_assert((STAGES - 2) * LOADS < 64, "vmcnt range");
-    static_assert(STAGES != 0 || BK == 64, "the pipelined loop is written for 64-wide slabs");
+    static_assert(STAGES >= 2, "ring depth");
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    // waves w and w + 4 share a SIMD: with the row half in the upper bit of the wave id, the live waves of a
-    // half-filled tile (rows past the expert's end skip their MFMAs) still cover all four SIMDs
     const int wm = wv / WAVES_N, wn = wv % WAVES_N;
 
     // ---- sources of this lane's pieces ----
@@ -499,8 +336,7 @@ struct TileConfig {
     int live = (rows - wm * WTM + 31) / 32;
     live = __builtin_amdgcn_readfirstlane(live < 0 ? 0 : (live > TM ? TM : live));
 
-    using Loop = typename std::conditional<STAGES == 0, PipelinedLoop<BM, BN, NW, TM, TN, LOADS, FillsT>,
-                                           MainLoop<BM, BN, BK, (STAGES == 0 ? 2 : STAGES), NW, TM, TN, LOADS, FillsT>>::type;
+    using Loop = MainLoop<BM, BN, BK, STAGES, NW, TM, TN, LOADS, FillsT>;
     // the wave id as a scalar: LDS destinations of the fills (M0) are then computed on the scalar unit
     Loop loop{smem, fills, a_off, a_sw, b_off, b_sw, K / BK, __builtin_amdgcn_readfirstlane(wv), lk};
     if (live == TM)
@@ -542,7 +378,7 @@ struct TileConfig {
                     const float g = acc[i][j][q * 4 + v];
                     if (SWIGLU) {
                         const float u = acc[i + TN / 2][j][q * 4 + v];
-                        o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                        o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
                     } else {
                         o[v] = g;
                     }
@@ -835,7 +671,7 @@ struct TileConfig16 {
                 const float g = acc[i][j][v];
                 if (SWIGLU) {
                     const float u = acc[i + TN / 2][j][v];
-                    o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                    o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
                 } else {
                     o[v] = g;
                 }
