@@ -13,6 +13,8 @@
 //                     ascending token order and gives ties at the threshold to the lower token index.
 // Every kernel first pulls what it needs from global memory in one batch of independent loads
 // (these kernels are latency-bound: a dependent load per loop iteration costs a microsecond each).
+#include <type_traits>
+
 #include "common.h"
 
 namespace capmoe {
@@ -519,12 +521,363 @@ __global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* _
             if (removed[e]) atomicSub(&seg_count[(t_first / seg_tokens) * E + e], removed[e]);
 }
 
+// ---------------------------------------------------------------------------------------------
+// 5. all of it in one launch, for small problems
+// ---------------------------------------------------------------------------------------------
+// With a few thousand tokens the three kernels above are a chain of short launches, each of which
+// waits for the previous one to drain.  When every expert has its own capacity (no device budget, no
+// per-token limit) a block can do the whole job for its segment alone: it needs the other segments
+// only for its first output row, and their kept counts are min(candidates, capacity), which the
+// block gets by counting the candidates of every segment itself from the top-k lists (read from L2
+// by every block: small next to a launch as long as the lists are short).
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedWaves = kFusedThreads / kWave;
+constexpr int kFusedMaxTokens = 8192;  // tokens of a segment: its keys and slots live in LDS
+constexpr int kFusedMaxSegs = 2048;    // capacity segments (one candidate counter each)
+constexpr int kFusedCounters = 4096;   // counters in LDS: as many private copies of the segment counters as fit
+constexpr long long kFusedMaxWork = 8ll << 20;  // segments x top-k list entries: above it, three launches are cheaper
+
+// exclusive prefix sum of v over the block's 1024 threads; *total gets the block sum
+__device__ inline int fused_exclusive_scan(int v, int* red, int* total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int o = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) red[wv] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) {
+        const int r = red[w];
+        before += w < wv ? r : 0;
+        all += r;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+// EXPANDED: Expanded Drop; ONE_BLOCK: a single capacity block (every token belongs to the block's segment
+// list); VW: entries of a top-k list fetched per load (divides k).  The pass over the lists is the bulk of
+// the kernel's instructions, so it is specialised.
+template <bool EXPANDED, bool ONE_BLOCK, int VW>
+__global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ topk_idx, const uint8_t* __restrict__ token_class,
+    uint32_t seed, int32_t* __restrict__ expert_count, int32_t* __restrict__ seg_count,
+    int32_t* __restrict__ expert_offset, int32_t* __restrict__ row_token, float* __restrict__ row_weight,
+    int32_t* __restrict__ pair_row, int N, int E, int k, int S, int group_tokens, int group_experts, int metric,
+    int seg_tokens, int n_blocks, int cap, int weight_from_key) {
+    // a thread owns a run of consecutive tokens of the segment; one padding word per 16 keeps the runs of
+    // neighbouring threads on different LDS banks
+    __shared__ uint32_t key_s[kFusedMaxTokens + kFusedMaxTokens / 16];
+    __shared__ uint8_t slot_s[kFusedMaxTokens];
+    __shared__ int cand[kFusedCounters];
+    __shared__ int hist[256];
+    __shared__ int red[kFusedWaves];
+    __shared__ int red3[kFusedWaves][3];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_rem;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int seg = blockIdx.x, b = seg / E, e = seg - b * E;
+    const int segs = n_blocks * E;
+    // Candidate counters: one private copy per lane of a wave where they fit (lanes that meet the same hot
+    // expert in one instruction would otherwise serialise on its counter), an odd-ish pitch so that the
+    // copies of one expert sit in different banks.
+    const int pitch = segs + 1;
+    const int copies = kFusedCounters / pitch < kWave ? kFusedCounters / pitch : kWave;  // >= 1
+    auto pad = [](int i) { return i + (i >> 4); };
+
+    for (int i = tid; i < copies * pitch; i += kFusedThreads) cand[i] = 0;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+
+    // ---- one pass over the top-k lists, a thread per token: candidates of every segment (the experts of a
+    // token's own device are counted later), and for the tokens of this block's segment what their list says
+    // about expert e: listed experts with a lower id (bits 0-9), listed experts in all (bits 10-19), e itself
+    // listed (bit 20); under Expanded Drop the experts of the token's own device do not count as listed, they
+    // are candidates anyway
+    {
+        typedef int32_t vec_t __attribute__((ext_vector_type(VW)));
+        int* mine = cand + (lane % copies) * pitch;
+        constexpr int kTok = 4;        // tokens per thread and round
+        constexpr int kVec = 8 / VW;   // loads per token and chunk of eight entries
+        for (int t0 = tid; t0 < N; t0 += kFusedThreads * kTok) {
+            uint32_t info[kTok] = {0u, 0u, 0u, 0u};
+            int tq[kTok];
+#pragma unroll
+            for (int q = 0; q < kTok; ++q) {
+                const int t = t0 + kFusedThreads * q;
+                tq[q] = t < N ? t : N - 1;  // a token past the end re-reads the last one and is ignored below
+            }
+            for (int j0 = 0; j0 < k; j0 += 8) {
+                vec_t x[kTok][kVec];  // independent loads, all issued before anything waits
+#pragma unroll
+                for (int q = 0; q < kTok; ++q)
+#pragma unroll
+                    for (int c = 0; c < kVec; ++c) {
+                        const int j = j0 + c * VW < k ? j0 + c * VW : k - VW;  // past the list: a valid re-read
+                        x[q][c] = *(const vec_t*)(topk_idx + (size_t)tq[q] * k + j);
+                    }
+#pragma unroll
+                for (int q = 0; q < kTok; ++q) {
+                    if (t0 + kFusedThreads * q >= N) continue;
+                    const int t = tq[q];
+                    const int bb = ONE_BLOCK ? 0 : t / seg_tokens;
+                    const int g0 = EXPANDED ? (t / group_tokens) * group_experts : 0;
+                    int* row = mine + bb * E;
+#pragma unroll
+                    for (int c = 0; c < kVec; ++c) {
+                        if (j0 + c * VW >= k) continue;  // the same for every thread
+#pragma unroll
+                        for (int u = 0; u < VW; ++u) {
+                            const int xe = x[q][c][u];
+                            const bool outside = !EXPANDED || xe < g0 || xe >= g0 + group_experts;
+                            if (outside) atomicAdd(&row[xe], 1);
+                            info[q] += (outside && xe < e ? 1u : 0u) + (outside ? 1u << 10 : 0u) + (xe == e ? 1u << 20 : 0u);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kTok; ++q) {
+                const int t = t0 + kFusedThreads * q;
+                if (t < N && (ONE_BLOCK || t / seg_tokens == b)) key_s[pad(t - b * seg_tokens)] = info[q];
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- keys and slots of this block's segment ----
+    {
+        constexpr int kPer = kFusedMaxTokens / kFusedThreads;
+        const int g_e = e / group_experts;  // device of this expert
+        uint32_t info[kPer], rank[kPer];
+        bool c[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int tl = tid + kFusedThreads * j;
+            const int t = b * seg_tokens + tl;
+            info[j] = tl < seg_tokens ? key_s[pad(tl)] : 0u;
+            c[j] = tl < seg_tokens && ((info[j] >> 20) != 0u || (EXPANDED && t / group_tokens == g_e));
+            // rank within the class, below 2^30: score bits (scores are in [0,1]), position, or a draw
+            rank[j] = 0u;
+            if (c[j]) {
+                if (metric == MOE_METRIC_ORDER)
+                    rank[j] = (uint32_t)(seg_tokens - 1 - tl);
+                else if (metric == MOE_METRIC_REVERSE_ORDER)
+                    rank[j] = (uint32_t)tl;
+                else if (metric == MOE_METRIC_RANDOM)
+                    rank[j] = pair_hash(seed, (uint32_t)t * (uint32_t)E + (uint32_t)e) >> 3;
+                else
+                    rank[j] = __float_as_uint(scores[(size_t)t * E + e]);
+                if (token_class) rank[j] += (uint32_t)(token_class[t] & 3) << 30;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int tl = tid + kFusedThreads * j;
+            if (tl >= seg_tokens) continue;
+            const int t = b * seg_tokens + tl;
+            int below = (int)(info[j] & 1023u);
+            const int listed = (int)((info[j] >> 10) & 1023u);
+            if (EXPANDED) {
+                const int lower = e - (t / group_tokens) * group_experts;  // experts of the token's device below e
+                below += lower < 0 ? 0 : (lower > group_experts ? group_experts : lower);
+            }
+            const uint32_t key = c[j] ? rank[j] + 1u : 0u;
+            if (c[j]) atomicAdd(&hist[key >> 24], 1);
+            key_s[pad(tl)] = key;
+            slot_s[tl] = (uint8_t)below;
+            if (e == 0) {  // slots beyond the token's candidate count stay unused
+                const int n_c = listed + (EXPANDED ? group_experts : 0);
+                for (int sl = n_c; sl < S; ++sl) pair_row[(size_t)t * S + sl] = -1;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- kept rows of every segment: this block's first row, its expert's total ----
+    int before = 0, own_total = 0, n_cand = 0;
+    for (int i = tid; i < segs; i += kFusedThreads) {
+        int c = 0;
+        for (int r = 0; r < copies; ++r) c += cand[r * pitch + i];
+        const int bb = i / E, ee = i - bb * E;
+        if (EXPANDED) {  // plus the tokens of block bb that sit on the expert's device
+            const int lo = (ee / group_experts) * group_tokens, hi = lo + group_tokens;
+            const int s0 = bb * seg_tokens, s1 = s0 + seg_tokens;
+            const int a = lo > s0 ? lo : s0, z = hi < s1 ? hi : s1;
+            c += z > a ? z - a : 0;
+        }
+        const int kept = c < cap ? c : cap;
+        if (ee < e || (ee == e && bb < b)) before += kept;
+        if (ee == e) own_total += kept;
+        if (i == seg) n_cand = c;
+    }
+    // block sums of the three (one pair of barriers)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        before += __shfl_xor(before, off, kWave);
+        own_total += __shfl_xor(own_total, off, kWave);
+        n_cand += __shfl_xor(n_cand, off, kWave);
+    }
+    if (lane == 0) {
+        red3[wv][0] = before;
+        red3[wv][1] = own_total;
+        red3[wv][2] = n_cand;
+    }
+    __syncthreads();
+    int row0 = 0, total;
+    own_total = n_cand = 0;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) {
+        row0 += red3[w][0];
+        own_total += red3[w][1];
+        n_cand += red3[w][2];
+    }
+    if (tid == 0) {
+        seg_count[seg] = n_cand < cap ? n_cand : cap;
+        if (b == 0) {
+            expert_count[e] = own_total;
+            expert_offset[e] = row0;
+            if (e == E - 1) expert_offset[E] = row0 + own_total;
+        }
+    }
+
+    // ---- threshold: keys above tau are kept, `need` of the keys equal to tau are kept (Eq. 8) ----
+    uint32_t tau = 0;  // every candidate (key >= 1) passes
+    int need = 0;
+    if (cap == 0) {
+        tau = 0xffffffffu;  // nothing passes
+    } else if (n_cand > cap) {
+        // cap-th largest key, most significant byte first; the histogram of the top byte is already there
+        uint32_t prefix = 0;
+        need = cap;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (shift != 24) {
+                __syncthreads();
+                if (tid < 256) hist[tid] = 0;
+                __syncthreads();
+                const uint32_t hi_mask = 0xffffffffu << (shift + 8);
+                for (int tl = tid; tl < seg_tokens; tl += kFusedThreads) {
+                    const uint32_t kx = key_s[pad(tl)];
+                    if (kx != 0u && (kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
+                }
+                __syncthreads();
+            }
+            // the first wave owns the digits, lane l the four digits 255-4l .. 252-4l: a scan over its lanes
+            // counts the keys with a larger digit; the digit where that count first reaches `need` holds the
+            // cap-th key
+            if (wv == 0) {
+                int h[4], sum = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    h[u] = hist[255 - 4 * lane - u];
+                    sum += h[u];
+                }
+                int incl = sum;
+#pragma unroll
+                for (int off = 1; off < kWave; off <<= 1) {
+                    const int o = __shfl_up(incl, off, kWave);
+                    if (lane >= off) incl += o;
+                }
+                int above = incl - sum;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (above < need && above + h[u] >= need) {  // exactly one lane and digit
+                        sh_prefix = prefix | ((uint32_t)(255 - 4 * lane - u) << shift);
+                        sh_rem = need - above;
+                    }
+                    above += h[u];
+                }
+            }
+            __syncthreads();
+            prefix = sh_prefix;
+            need = sh_rem;
+        }
+        tau = prefix;
+    }
+
+    // ---- ordered compaction: rows in ascending token order, ties at the threshold to the lower tokens ----
+    const int run = (seg_tokens + kFusedThreads - 1) / kFusedThreads;  // at most 8
+    const int tb = tid * run;
+    uint32_t kx[kFusedMaxTokens / kFusedThreads];
+    int eq_cnt = 0;
+#pragma unroll
+    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+        kx[j] = j < run && tb + j < seg_tokens ? key_s[pad(tb + j)] : 0u;
+        eq_cnt += kx[j] != 0u && kx[j] == tau;
+    }
+    int eq_rank = fused_exclusive_scan(eq_cnt, red, &total);
+    uint32_t keep_bits = 0;
+    int keep_cnt = 0;
+#pragma unroll
+    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+        const bool c = kx[j] != 0u;
+        const bool eq = c && kx[j] == tau;
+        const bool keep = c && (kx[j] > tau || (eq && eq_rank < need));
+        eq_rank += eq;
+        keep_cnt += keep;
+        keep_bits |= (uint32_t)keep << j;
+    }
+    int pos = row0 + fused_exclusive_scan(keep_cnt, red, &total);
+#pragma unroll
+    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+        if (kx[j] == 0u) continue;
+        const int t = b * seg_tokens + tb + j;
+        const bool keep = (keep_bits >> j) & 1u;
+        if (keep) {
+            row_token[pos] = t;
+            // the gating score, whatever ranked the pair (under the Score metric it is the key itself)
+            row_weight[pos] = weight_from_key ? __uint_as_float(kx[j] - 1u) : scores[(size_t)t * E + e];
+        }
+        pair_row[(size_t)t * S + slot_s[tb + j]] = keep ? pos : -1;
+        pos += keep;
+    }
+}
+
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
                                 const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
                                 int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
                                 hipStream_t st) {
     const int N = d.n_tokens, E = d.n_experts;
+    {
+        const int segs_all = s.n_blocks * E;
+        const bool fused = s.span == 1 && !(d.max_experts && s.slots > d.top_k) && N > 0 && s.seg_tokens <= kFusedMaxTokens &&
+                           segs_all + 1 <= kFusedCounters && segs_all <= kFusedMaxSegs &&
+                           (long long)segs_all * N * s.list_k <= kFusedMaxWork;
+        if (fused) {
+            ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
+            const bool ex = d.mode == MOE_MODE_EXPANDED_DROP, one = s.n_blocks == 1;
+            auto launch = [&](auto kern) {
+                hipLaunchKernelGGL(kern, dim3(segs_all), dim3(kFusedThreads), 0, st, scores, topk_idx, token_class, seed,
+                                   expert_count, seg_count, expert_offset, row_token, row_weight, pair_row, N, E, s.list_k,
+                                   s.slots, s.group_tokens, s.group_experts, d.metric, s.seg_tokens, s.n_blocks, s.cap,
+                                   d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
+            };
+            auto by_width = [&](auto ex_c, auto one_c) {
+                constexpr bool EX = decltype(ex_c)::value, ONE = decltype(one_c)::value;
+                if (s.list_k % 4 == 0)
+                    launch(drop_fused_kernel<EX, ONE, 4>);
+                else if (s.list_k % 2 == 0)
+                    launch(drop_fused_kernel<EX, ONE, 2>);
+                else
+                    launch(drop_fused_kernel<EX, ONE, 1>);
+            };
+            if (ex && one)
+                by_width(std::true_type{}, std::true_type{});
+            else if (ex)
+                by_width(std::true_type{}, std::false_type{});
+            else if (one)
+                by_width(std::false_type{}, std::true_type{});
+            else
+                by_width(std::false_type{}, std::false_type{});
+            return hipGetLastError();
+        }
+    }
     if (N > 0) {
         const int grid = (N + kPrepTokens - 1) / kPrepTokens;
         const size_t lds = (size_t)kPrepTokens * (E | 1) * 5;
