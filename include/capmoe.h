@@ -215,7 +215,7 @@ enum {
     MOE_KERNEL_ROUTER_LOGITS = 0,
     MOE_KERNEL_SOFTMAX_TOPK = 1,
     MOE_KERNEL_DROP_PREPARE = 2,
-    MOE_KERNEL_DROP_SELECT = 3,
+    MOE_KERNEL_DROP_SELECT = 3, /* also the single kernel that replaces prepare, select and emit on small problems */
     MOE_KERNEL_DROP_EMIT = 4,
     MOE_KERNEL_DISPATCH = 5,
     MOE_KERNEL_FFN_SCHEDULE = 6,

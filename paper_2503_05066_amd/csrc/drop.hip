@@ -13,6 +13,8 @@
 //                     ascending token order and gives ties at the threshold to the lower token index.
 // Every kernel first pulls what it needs from global memory in one batch of independent loads
 // (these kernels are latency-bound: a dependent load per loop iteration costs a microsecond each).
+// Small problems with per-expert capacities run all three steps in one launch (drop_fused, below),
+// the optional per-token limit adds a fourth kernel and a second emit.
 #include <type_traits>
 
 #include "common.h"

@@ -130,6 +130,12 @@ def test_plan_full_size(orc, name, mode, scope, gamma):
     (512, 16, 4, 4, ED, GLOBAL, math.inf),  # no limit: all k+m candidates survive
     (512, 16, 4, 4, NONE, GLOBAL, 0.3),     # mode none ignores gamma
     (5000, 8, 2, 1, TD, GLOBAL, 0.05),
+    (9000, 8, 2, 1, TD, GLOBAL, 1.0),       # a segment longer than the single-launch drop holds: three kernels
+    (9000, 12, 3, 3, ED, GLOBAL, 0.9),
+    (8192, 8, 2, 2, ED, LOCAL, 1.0),        # the longest segments the single launch takes are 8192 tokens: 4096 here,
+    (8192, 4, 2, 1, TD, GLOBAL, 1.1),       # and exactly 8192 here
+    (1027, 6, 3, 1, TD, GLOBAL, 0.9),       # odd top-k width: scalar list loads; ragged last round of tokens
+    (1026, 6, 2, 1, TD, GLOBAL, 0.9),       # two entries per load
 ])
 def test_plan_edge_shapes(orc, n, e, k, g, mode, scope, gamma):
     rng = np.random.default_rng(n * 7 + e)
@@ -137,9 +143,12 @@ def test_plan_edge_shapes(orc, n, e, k, g, mode, scope, gamma):
     check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, "edge shape")
 
 
-@pytest.mark.parametrize("mode,scope,g", [(TD, GLOBAL, 1), (TD, LOCAL, 4), (ED, LOCAL, 4), (ED, GLOBAL, 8)])
-def test_plan_with_forced_ties(orc, mode, scope, g):
-    w = synth.scaled(W["olmoe"], n_tokens=2048, n_experts=32, top_k=4, device_groups=g)
+# 2048 tokens: the single-launch drop; 16384 tokens in one block of tokens: segments too long for it, so the
+# three-kernel chain runs with per-expert capacities as well
+@pytest.mark.parametrize("mode,scope,g,n", [(TD, GLOBAL, 1, 2048), (TD, LOCAL, 4, 2048), (ED, LOCAL, 4, 2048),
+                                            (ED, GLOBAL, 8, 2048), (TD, GLOBAL, 1, 16384), (ED, GLOBAL, 4, 16384)])
+def test_plan_with_forced_ties(orc, mode, scope, g, n):
+    w = synth.scaled(W["olmoe"], n_tokens=n, n_experts=32, top_k=4, device_groups=g)
     logits = synth.logits_with_ties(w)
     buf, ref = check_route_and_plan(orc, logits, w.n_tokens, w.n_experts, w.top_k, g, mode, scope, 1.0, "ties")
     # the input really ties at thresholds: some segment keeps only part of a run of equal scores
