@@ -100,7 +100,7 @@ def upload(w):
 
 
 def algorithmic_work(w, S, rows, active, elem):
-    """Bytes each kernel must move and flops it must do for `rows` surviving pairs."""
+    """Bytes each kernel must move and flops it must do for `rows` surviving pairs: inputs read once, outputs written once."""
     n, d, e, k, h = w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden
     m = S - k
     return {

@@ -8,9 +8,10 @@
 // static upper bound and surplus blocks exit at once.
 //
 // bf16: both operands are K-contiguous ("NT" GEMM), staged through LDS in 16-byte pieces with an
-// XOR swizzle, multiplied on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
-// The weight rows feed the MFMA's first operand and the activation rows the second, so a lane
-// ends up with 4 consecutive output columns of one row and stores them as one 8-byte piece.
+// XOR swizzle, multiplied on the matrix cores with fp32 accumulation: v_mfma_f32_16x16x32_bf16 in the
+// 256-row tiles (the bulk of the flops), v_mfma_f32_32x32x16_bf16 in the 64-row tiles (weight
+// streaming).  The weight rows feed the MFMA's first operand and the activation rows the second, so a
+// lane ends up with 4 consecutive output columns of one row and stores them as one 8-byte piece.
 #include <type_traits>
 
 #include "common.h"
