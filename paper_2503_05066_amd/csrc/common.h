@@ -58,18 +58,23 @@ struct RouteWorkspace {
 RouteWorkspace route_workspace(const moe_desc_t& d, void* base);
 
 // Workspace layout of moe_grouped_ffn.
+constexpr int kFfnMaxUnits = 1024;  // upper bound on compute units (short row tiles of a converted last round)
 struct TileList {
     int32_t* expert;  // [max_tiles]
     int32_t* row0;    // [max_tiles] first row of the tile
     int32_t* rows;    // [max_tiles] valid rows in the tile
     int32_t* count;   // [1]
-    int max_tiles;
+    int max_tiles;    // capacity of the arrays
+    int max_launch;   // most tiles a launch can find in the list, per column block, without a converted last
+                      // round (with one, a GEMM has at most one short item per compute unit)
     int tile_m;
 };
 struct FfnWorkspace {
     void* hidden;    // [P_max, h] activations silu(gate)*up in desc->dtype
     TileList big;    // full-height row tiles, and remainders above small_max rows
     TileList small;  // short row tiles covering remainders of at most small_max rows (bf16 only)
+    TileList big_down, small_down;  // the same for the second GEMM (bf16 only): a nearly empty last round of
+                                    // big items is cut into short tiles, and that depends on the GEMM's width
     int small_max;
     size_t bytes;
 };

@@ -27,57 +27,135 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // Expert e with c rows gets floor(c / big) full tiles; a remainder above small_max rows becomes one
 // more (partly filled) big tile, a smaller one is cut into ceil(remainder / small) short tiles, which
 // a kernel with a deeper load pipeline serves (few rows per weight byte: memory-bound work).
-__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E,
-                                                          int big, int small, int small_max,
-                                                          int32_t* __restrict__ b_expert, int32_t* __restrict__ b_row0,
-                                                          int32_t* __restrict__ b_rows, int32_t* __restrict__ b_count,
-                                                          int b_max, int32_t* __restrict__ s_expert,
-                                                          int32_t* __restrict__ s_row0, int32_t* __restrict__ s_rows,
-                                                          int32_t* __restrict__ s_count, int s_max) {
+//
+// A GEMM runs its big work items (row tiles x column blocks) in rounds of one item per compute unit.
+// When the last round would be nearly empty, its row tiles are handed to the short-tile kernel
+// instead, as 64-row pieces: a piece costs about 0.6 of a big item and all of them run at once, where
+// the few big items would have held the whole launch for a full item time.  The rule needs the
+// column-block count of the GEMM, so each of the two GEMMs gets its own pair of lists.
+struct TileListArgs {
+    int32_t *b_expert, *b_row0, *b_rows, *b_count, *s_expert, *s_row0, *s_rows, *s_count;
+    int b_max, s_max;
+    int ncol;  // column blocks of the GEMM's big items; 0: never convert
+};
+
+struct ExpertTiles {
+    int lo, rows, nb, ns;
+};
+__device__ inline ExpertTiles expert_tiles(const int32_t* __restrict__ expert_offset, int e, int E, int big,
+                                           int small, int small_max) {
+    ExpertTiles t;
+    t.lo = e < E ? expert_offset[e] : 0;
+    const int hi = e < E ? expert_offset[e + 1] : 0;
+    t.rows = hi - t.lo;
+    const int full = t.rows / big, rem = t.rows - full * big;
+    const bool rem_small = rem > 0 && rem <= small_max;
+    t.nb = full + (rem > 0 && !rem_small ? 1 : 0);
+    t.ns = rem_small ? (rem + small - 1) / small : 0;
+    return t;
+}
+
+// inclusive scan of three counters over the wave
+__device__ inline void wave_scan3(int& a, int& b, int& c) {
     const int lane = threadIdx.x;
-    int base_b = 0, base_s = 0;
-    for (int e0 = 0; e0 < E; e0 += kWave) {
-        const int e = e0 + lane;
-        const int lo = e < E ? expert_offset[e] : 0;
-        const int hi = e < E ? expert_offset[e + 1] : 0;
-        const int c = hi - lo;
-        const int full = c / big, rem = c - full * big;
-        const bool rem_small = rem > 0 && rem <= small_max;
-        const int nb = full + (rem > 0 && !rem_small ? 1 : 0);
-        const int ns = rem_small ? (rem + small - 1) / small : 0;
-        int incl_b = nb, incl_s = ns;  // inclusive scans over the wave
 #pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const int ob = __shfl_up(incl_b, off, kWave), os = __shfl_up(incl_s, off, kWave);
-            if (lane >= off) {
-                incl_b += ob;
-                incl_s += os;
-            }
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int oa = __shfl_up(a, off, kWave), ob = __shfl_up(b, off, kWave), oc = __shfl_up(c, off, kWave);
+        if (lane >= off) {
+            a += oa;
+            b += ob;
+            c += oc;
         }
-        for (int i = 0; i < nb; ++i) {
-            const int idx = base_b + incl_b - nb + i;
-            if (idx < b_max) {
-                b_expert[idx] = e;
-                b_row0[idx] = lo + i * big;
-                const int left = c - i * big;
-                b_rows[idx] = left < big ? left : big;
-            }
-        }
-        for (int i = 0; i < ns; ++i) {
-            const int idx = base_s + incl_s - ns + i;
-            if (idx < s_max) {
-                s_expert[idx] = e;
-                s_row0[idx] = lo + full * big + i * small;
-                const int left = rem - i * small;
-                s_rows[idx] = left < small ? left : small;
-            }
-        }
-        base_b += __shfl(incl_b, kWave - 1, kWave);
-        base_s += __shfl(incl_s, kWave - 1, kWave);
     }
-    if (lane == 0) {
-        *b_count = base_b < b_max ? base_b : b_max;
-        *s_count = base_s < s_max ? base_s : s_max;
+}
+
+__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big,
+                                                          int small, int small_max, int cus, TileListArgs first,
+                                                          TileListArgs second) {
+    const int lane = threadIdx.x;
+    // totals first: which big tiles are the last ones is only known then
+    int nt_b = 0, nt_s = 0;
+    for (int e0 = 0; e0 < E; e0 += kWave) {
+        const ExpertTiles t = expert_tiles(expert_offset, e0 + lane, E, big, small, small_max);
+        int ib = t.nb, is = t.ns, unused = 0;
+        wave_scan3(ib, is, unused);
+        nt_b += __shfl(ib, kWave - 1, kWave);
+        nt_s += __shfl(is, kWave - 1, kWave);
+    }
+    const int pieces = big / small;
+    for (int which = 0; which < 2; ++which) {
+        const TileListArgs& L = which == 0 ? first : second;
+        if (which == 1 && second.b_expert == first.b_expert) break;  // one pair of lists serves both GEMMs
+        // big row tiles of the nearly empty last round, if their pieces fit into one round of short items
+        int conv = 0;
+        if (L.ncol > 0 && cus > 0 && (long long)nt_b * L.ncol >= cus) {
+            const int rem = (int)(((long long)nt_b * L.ncol) % cus);
+            if (rem > 0) {
+                int c = (rem + L.ncol - 1) / L.ncol;
+                c = c > nt_b ? nt_b : c;
+                if ((long long)(nt_s + pieces * c) * L.ncol <= cus) conv = c;
+            }
+        }
+        const int first_conv = nt_b - conv;  // big tiles from this index on are cut into pieces
+        int base_b = 0, base_s = 0, base_p = 0;
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            const ExpertTiles t = expert_tiles(expert_offset, e, E, big, small, small_max);
+            int ib = t.nb, is = t.ns;
+            // pieces of this expert's converted tiles (they are the last tiles of the list, hence of the expert)
+            int ip = 0;
+            {
+                int ib_excl = t.nb, d1 = 0, d2 = 0;
+                wave_scan3(ib_excl, d1, d2);
+                const int start = base_b + ib_excl - t.nb;
+                for (int i = 0; i < t.nb; ++i)
+                    if (start + i >= first_conv) {
+                        const int left = t.rows - i * big;
+                        ip += ((left < big ? left : big) + small - 1) / small;
+                    }
+            }
+            const int np = ip;
+            wave_scan3(ib, is, ip);
+            const int start_b = base_b + ib - t.nb, start_s = base_s + is - t.ns, start_p = nt_s + base_p + ip - np;
+            int p = start_p;
+            for (int i = 0; i < t.nb; ++i) {
+                const int idx = start_b + i;
+                const int left = t.rows - i * big;
+                const int rows = left < big ? left : big;
+                if (idx < first_conv) {
+                    if (idx < L.b_max) {
+                        L.b_expert[idx] = e;
+                        L.b_row0[idx] = t.lo + i * big;
+                        L.b_rows[idx] = rows;
+                    }
+                } else {
+                    for (int r = 0; r < rows; r += small, ++p)
+                        if (p < L.s_max) {
+                            L.s_expert[p] = e;
+                            L.s_row0[p] = t.lo + i * big + r;
+                            L.s_rows[p] = rows - r < small ? rows - r : small;
+                        }
+                }
+            }
+            const int full = t.rows / big, rem = t.rows - full * big;
+            for (int i = 0; i < t.ns; ++i) {
+                const int idx = start_s + i;
+                if (idx < L.s_max) {
+                    L.s_expert[idx] = e;
+                    L.s_row0[idx] = t.lo + full * big + i * small;
+                    const int left = rem - i * small;
+                    L.s_rows[idx] = left < small ? left : small;
+                }
+            }
+            base_b += __shfl(ib, kWave - 1, kWave);
+            base_s += __shfl(is, kWave - 1, kWave);
+            base_p += __shfl(ip, kWave - 1, kWave);
+        }
+        if (lane == 0) {
+            const int nb = nt_b - conv, ns = nt_s + base_p;
+            *L.b_count = nb < L.b_max ? nb : L.b_max;
+            *L.s_count = ns < L.s_max ? ns : L.s_max;
+        }
     }
 }
 
@@ -742,7 +820,7 @@ static int column_group(int nb_total) {
 
 template <class Big, class Small, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const int32_t* gather,
-                        const FfnWorkspace& ws, int K, int Nout, hipStream_t st) {
+                        const TileList& big, const TileList& small, int K, int Nout, hipStream_t st) {
     constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
     auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
     static bool configured = false;
@@ -751,11 +829,12 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
         configured = true;
     }
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
-    // + 16: both lists are cut into eight whole chunks
-    const long long grid = (long long)nb_b * ws.big.max_tiles + (long long)nb_s * ws.small.max_tiles + 16;
+    // a converted last round adds at most one short item per compute unit; + 16: both lists are cut into
+    // eight whole chunks
+    const long long grid = (long long)nb_b * big.max_launch + (long long)nb_s * small.max_launch + kFfnMaxUnits + 16;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
-                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, ws.big.expert, ws.big.row0, ws.big.rows,
-                       ws.big.count, ws.small.expert, ws.small.row0, ws.small.rows, ws.small.count, K, Nout,
+                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, big.expert, big.row0, big.rows,
+                       big.count, small.expert, small.row0, small.rows, small.count, K, Nout,
                        column_group(nb_b), column_group(nb_s));
 }
 
@@ -765,30 +844,44 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
                               const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
                               const void* w_up, const void* w_down, void* yp, hipStream_t st) {
     (void)s;
-    {
-        ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts, ws.big.tile_m,
-                           ws.small.tile_m, ws.small_max, ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count,
-                           ws.big.max_tiles, ws.small.expert, ws.small.row0, ws.small.rows, ws.small.count,
-                           ws.small.max_tiles);
-    }
     const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
-    if (d.dtype == MOE_DTYPE_BF16) {
-        // big tiles: 256 x 256 x 64, two stages, software-pipelined; small tiles: 64 x 256 x 64, four stages
+    const bool bf16 = d.dtype == MOE_DTYPE_BF16;
+    const int bn_down = N2 % 256 == 0 ? 256 : 128;  // d is a multiple of 128 at least: output columns per block
+    {
+        auto args = [](const TileList& b, const TileList& sm, int ncol) {
+            return TileListArgs{b.expert, b.row0, b.rows, b.count, sm.expert, sm.row0, sm.rows, sm.count,
+                                b.max_tiles, sm.max_tiles, ncol};
+        };
+        static int cus = 0;
+        if (cus == 0) {
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+                cus = 256;
+        }
+        ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
+        // gate/up: a big item covers 128 hidden columns (gate and up rows of them); fp32: one pair of lists, as cut
+        const TileListArgs gu = args(ws.big, ws.small, bf16 ? N1 / 128 : 0);
+        const TileListArgs dn = bf16 ? args(ws.big_down, ws.small_down, N2 / bn_down) : gu;
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts, ws.big.tile_m,
+                           ws.small.tile_m, ws.small_max, cus, gu, dn);
+    }
+    if (bf16) {
+        // big tiles: 256 x 256 x 64 on four waves; small tiles: 64 x 256 x 64, four stages
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, true>,
-                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws, K1, N1, st);
+                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws.big, ws.small, K1, N1, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
-        if (N2 % 256 == 0)
+        if (bn_down == 256)
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, false>,
-                        TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
-                                                                                    K2, N2, st);
-        else  // d is a multiple of 128 only: 128 output columns per block
+                        TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
+                                                                                    ws.big_down, ws.small_down, K2, N2, st);
+        else
             launch_bf16<TileConfig16<kFfnTileM, 128, 2, 2, false>,
-                        TileConfig<kFfnTileSmall, 128, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr, ws,
-                                                                                    K2, N2, st);
+                        TileConfig<kFfnTileSmall, 128, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
+                                                                                    ws.big_down, ws.small_down, K2, N2, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
         {

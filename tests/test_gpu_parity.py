@@ -455,6 +455,27 @@ def test_ffn_ragged_expert_sizes(orc):
     assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "ragged")
 
 
+def test_ffn_nearly_empty_last_round(orc):
+    """67 full-height row tiles x 4 column blocks of the down GEMM = 268 work items on 256 compute units: the row
+    tiles of the 12-item last round (two full ones and a 100-row one) run as 64-row pieces instead.  The gate/up
+    GEMM (2 column blocks, 134 items) keeps its tiles: the two GEMMs walk different lists."""
+    counts = [40 * 256 + 30, 20 * 256, 6 * 256 + 100, 17]
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="tail", n_tokens=n, d_model=1024, n_experts=e, top_k=1, d_hidden=256,
+                     device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    np.random.default_rng(9).shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    buf = run_layer(layer, layer.desc(NONE, GLOBAL, 1.0), logits)
+    assert_plan_equal(buf, ref, "tail")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "tail")
+
+
 @pytest.mark.parametrize("trial", range(5))
 def test_ffn_random_expert_sizes(orc, trial):
     """Random row counts per expert (empty experts, 1 row, around every tile boundary, several tiles) and random
