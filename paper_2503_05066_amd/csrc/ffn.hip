@@ -19,7 +19,6 @@
 namespace capmoe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // ---------------------------------------------------------------------------------------------
 // tile schedule
@@ -244,244 +243,8 @@ struct Fills {
     }
 };
 
-// K loop of one wave.  A ring of STAGES LDS stages: while stage kt is multiplied, the fills of
-// the next STAGES-1 slabs are in flight (asynchronous, straight from global memory into LDS); one
-// barrier per slab separates the readers of a stage from its next fill.
-// LIVE = number of 32-row activation sub-tiles that are multiplied (the rest lie past the expert's
-// last row).
-template <int BM, int BN, int BK, int STAGES, int NW, int TM, int TN, int LOADS, class FillsT>
-struct MainLoop {
-    static constexpr int ROW_BYTES = BK * 2;
-    static constexpr int STAGE_BYTES = (BM + BN) * ROW_BYTES;
-    static constexpr int CPR = BK / 8;  // 16-byte pieces per row
-    uint8_t* smem;
-    const FillsT& fills;
-    const int* a_off;
-    const int* a_sw;
-    const int* b_off;
-    const int* b_sw;
-    int KT, wv, lk;
-
-    __device__ __forceinline__ void fill(int kt) const {
-        uint8_t* dst = smem + (kt % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) fills.one(i, dst + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
-    }
-
-    template <int LIVE>
-    __device__ __forceinline__ void run(f32x16 (&acc)[TN][TM]) const {
-#pragma unroll
-        for (int p = 0; p < STAGES - 1; ++p)
-            if (p < KT) fill(p);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // this wave's pieces of the first slabs have landed
-        __builtin_amdgcn_s_barrier();
-        for (int kt = 0; kt < KT; ++kt) {
-            const bool more = kt + STAGES - 1 < KT;
-            if (more) fill(kt + STAGES - 1);
-            const uint8_t* s = smem + (kt % STAGES) * STAGE_BYTES;
-            if (LIVE > 0) {
-#pragma unroll
-                for (int ks = 0; ks < BK / 16; ++ks) {
-                    const int kc = ks * 2 + lk;
-                    bf16x8 xa[LIVE > 0 ? LIVE : 1], wb[TN];
-#pragma unroll
-                    for (int j = 0; j < LIVE; ++j) xa[j] = *(const bf16x8*)(s + a_off[j] + ((kc ^ a_sw[j]) << 4));
-#pragma unroll
-                    for (int i = 0; i < TN; ++i) wb[i] = *(const bf16x8*)(s + b_off[i] + ((kc ^ b_sw[i]) << 4));
-#pragma unroll
-                    for (int i = 0; i < TN; ++i)
-#pragma unroll
-                        for (int j = 0; j < LIVE; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb[i], xa[j], acc[i][j], 0, 0, 0);
-                }
-            }
-            // slab kt+1 must have landed; younger fills may stay in flight (loads complete in order)
-            if (more)
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm((STAGES - 2) * LOADS));
-            else
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-            __builtin_amdgcn_s_barrier();
-        }
-    }
-};
-
-// Block tile: BM activation rows x BN weight rows, K slab BK (32 or 64); WAVES_M x WAVES_N waves.
-//
-// An LDS stage is (BM + BN) rows of BK bf16.  Rows are filled by direct global->LDS loads: one
-// wave-wide load writes 1 KB of consecutive LDS (64 lanes x 16 bytes = 8 or 16 rows), and each lane
-// chooses WHICH 16-byte piece of its row it fetches, so that piece kc of row r lands at position
-// kc ^ swz(r), swz(r) = (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows: with the 64
-// LDS banks of this chip, the 16 lanes that a 16-byte read serves per cycle then fall into 16
-// different bank groups, for the fill as well as for the MFMA operand reads.
-//
-// SWIGLU: weight rows [0,BN/2) of the tile come from W_gate, [BN/2,BN) from W_up, for the same
-// BN/2 hidden columns; a wave holds matching gate and up columns and applies silu(g)*u itself.
-//
-// Blocks are numbered so that each XCD (block id mod 8) walks a contiguous range of tiles, ordered
-// [column group][row tile][column in group]: blocks that run together share row and weight tiles in
-// their XCD's L2.
-// One output tile: rows [row0, row0+rows) of expert e times NCOLS output columns from n0.
-template <int BM, int BN, int BK, int STAGES, int WAVES_M, int WAVES_N, bool SWIGLU>
-struct TileConfig {
-    static constexpr int kBM = BM, kBN = BN;
-    static constexpr int kNCols = SWIGLU ? BN / 2 : BN;
-    static constexpr int kThreads = 64 * WAVES_M * WAVES_N;
-    static constexpr int kLdsBytes = STAGES * (BM + BN) * BK * 2;
-
-    static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
-                                               const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
-                                               const int32_t* __restrict__ gather, int e, int row0, int rows, int n0,
-                                               int K, int Nout, uint8_t* smem) {
-    constexpr int NW = WAVES_M * WAVES_N;
-    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
-    constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int ROW_BYTES = BK * 2, CPR = BK / 8;
-    constexpr int RPL = 1024 / ROW_BYTES;                         // rows per wave-wide load
-    constexpr int A_GROUPS = BM / RPL, GROUPS = (BM + BN) / RPL;  // row groups of a stage
-    constexpr int LOADS = GROUPS / NW;                            // wave-wide loads per wave per stage
-    static_assert(BK == 32 || BK == 64, "K slab");
-    static_assert(GROUPS % NW == 0, "loads must divide evenly over the waves");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-    static_assert(!SWIGLU || TN % 2 == 0, "a wave needs matching gate and up columns");
-    static_assert((STAGES - 2) * LOADS < 64, "vmcnt range");
-    static_assert(STAGES >= 2, "ring depth");
-
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int wm = wv / WAVES_N, wn = wv % WAVES_N;
-
-    // ---- sources of this lane's pieces ----
-    // Each descriptor opens the block's own window of a tensor (its activation rows, its weight rows), so
-    // 32-bit byte offsets suffice whatever the tensor size; with a gather list the window is the whole
-    // unpermuted input, whose size the host checks.
-    constexpr int A_LOADS = A_GROUPS / NW, B_LOADS = LOADS - A_LOADS;
-    constexpr int B1_FROM = SWIGLU ? A_LOADS + B_LOADS / 2 : LOADS;
-    static_assert(A_GROUPS % NW == 0 && (!SWIGLU || B_LOADS % 2 == 0), "a wave-wide load must not straddle two tensors");
-    constexpr int kRsrcFlags = 0x00020000;  // raw buffer of 32-bit words, no swizzle (gfx9 descriptor word 3)
-    using FillsT = Fills<LOADS, A_LOADS, B1_FROM>;
-    FillsT fills;
-    fills.a = __builtin_amdgcn_make_buffer_rsrc((void*)(gather ? A : A + (size_t)row0 * K), 0, -1, kRsrcFlags);
-    fills.b0 = __builtin_amdgcn_make_buffer_rsrc((void*)(B0 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags);
-    fills.b1 = SWIGLU ? __builtin_amdgcn_make_buffer_rsrc((void*)(B1 + ((size_t)e * Nout + n0) * K), 0, -1, kRsrcFlags)
-                      : fills.b0;
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int g = wv + NW * i;               // row group inside the stage (wave-uniform)
-        const int r = g * RPL + lane / CPR;      // row inside the stage: A rows first, then weight rows
-        const int kc = (lane % CPR) ^ (CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3);
-        if (i < A_LOADS) {
-            const int rr = r < rows ? r : rows - 1;  // rows past the expert's end repeat its last row
-            // with a gather list the activation rows are fetched from the unpermuted input
-            const uint32_t arow = gather ? (uint32_t)gather[row0 + rr] : (uint32_t)rr;
-            fills.voff[i] = (arow * (uint32_t)K + kc * 8) * 2u;
-        } else {
-            int rb = r - BM;
-            if (SWIGLU && rb >= BN / 2) rb -= BN / 2;  // the up-projection rows of the same hidden columns
-            fills.voff[i] = ((uint32_t)rb * (uint32_t)K + kc * 8) * 2u;
-        }
-    }
-
-    // ---- LDS offsets of this lane's operand pieces ----
-    const int lr = lane & 31, lk = lane >> 5;
-    int a_off[TM], a_sw[TM], b_off[TN], b_sw[TN];
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int r = wm * WTM + j * 32 + lr;
-        a_off[j] = r * ROW_BYTES;
-        a_sw[j] = CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3;
-    }
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-        int r;
-        if (SWIGLU) {
-            const int half = i / (TN / 2), idx = i % (TN / 2);
-            r = half * (BN / 2) + wn * (WTN / 2) + idx * 32 + lr;
-        } else {
-            r = wn * WTN + i * 32 + lr;
-        }
-        b_off[i] = (BM + r) * ROW_BYTES;
-        b_sw[i] = CPR == 8 ? (r >> 1) & 7 : (r >> 2) & 3;
-    }
-
-    f32x16 acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // 32-row sub-tiles of this wave that hold rows of the expert (wave-uniform); the main loop is
-    // specialised on it so that the common full tile carries no conditionals
-    int live = (rows - wm * WTM + 31) / 32;
-    live = __builtin_amdgcn_readfirstlane(live < 0 ? 0 : (live > TM ? TM : live));
-
-    using Loop = MainLoop<BM, BN, BK, STAGES, NW, TM, TN, LOADS, FillsT>;
-    // the wave id as a scalar: LDS destinations of the fills (M0) are then computed on the scalar unit
-    Loop loop{smem, fills, a_off, a_sw, b_off, b_sw, K / BK, __builtin_amdgcn_readfirstlane(wv), lk};
-    if (live == TM)
-        loop.template run<TM>(acc);
-    else if (TM > 2 && live == 3)
-        loop.template run<(TM > 2 ? 3 : TM)>(acc);
-    else if (TM > 1 && live == 2)
-        loop.template run<(TM > 1 ? 2 : TM)>(acc);
-    else if (live == 1)
-        loop.template run<1>(acc);
-    else
-        loop.template run<0>(acc);
-
-    // ---- epilogue ----
-    // A lane holds, for activation row (lane & 31) of each 32-row sub-tile, output columns
-    // 8*q + 4*(lane/32) + v (q, v = 0..3) of each 32-column sub-tile: 8-byte runs scattered over 32 rows.
-    // Stored like that, a wave instruction touches 64 different cache lines, which costs up to a
-    // third of a short GEMM.  The tile is therefore transposed through LDS (free after the K loop: its
-    // last barrier follows the last operand read): bf16 rows of OUT_COLS columns, 16-byte piece p of
-    // row r at position p ^ (r mod PIECES) so that neither side has bank conflicts beyond the access
-    // width, then every row leaves as consecutive 16-byte pieces of consecutive lanes.
-    constexpr int TNO = SWIGLU ? TN / 2 : TN;
-    constexpr int OUT_COLS = kNCols, ROWB = OUT_COLS * 2, PIECES = ROWB / 16;
-    static_assert(BM * ROWB <= kLdsBytes, "the output tile must fit in the operand stages");
-    static_assert((PIECES & (PIECES - 1)) == 0, "piece swizzle");
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int r = wm * WTM + j * 32 + lr;
-        uint8_t* lrow = smem + r * ROWB + lk * 8;
-        const int sw = r & (PIECES - 1);
-#pragma unroll
-        for (int i = 0; i < TNO; ++i) {
-            const int piece0 = ((SWIGLU ? wn * (WTN / 2) : wn * WTN) + i * 32) / 8;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float g = acc[i][j][q * 4 + v];
-                    if (SWIGLU) {
-                        const float u = acc[i + TN / 2][j][q * 4 + v];
-                        o[v] = g * u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
-                    } else {
-                        o[v] = g;
-                    }
-                }
-                uint2 pk;
-                pk.x = pack_bf16x2(o[0], o[1]);
-                pk.y = pack_bf16x2(o[2], o[3]);
-                *(uint2*)(lrow + (((piece0 + q) ^ sw) << 4)) = pk;
-            }
-        }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < BM * PIECES; idx += kThreads) {
-        const int r = idx / PIECES, pc = idx % PIECES;
-        if (r < rows) {
-            const uint4 v = *(const uint4*)(smem + r * ROWB + ((pc ^ (r & (PIECES - 1))) << 4));
-            *(uint4*)(C + (size_t)(row0 + r) * Nout + n0 + pc * 8) = v;
-        }
-    }
-}
-};
-
 // ---------------------------------------------------------------------------------------------
-// Big tiles: 16x16x32 matrix instructions, four waves
+// tiles on 16x16x32 matrix instructions, four waves
 // ---------------------------------------------------------------------------------------------
 // Under sustained load the chip is power-limited, so what a kernel reaches is set by the energy it spends
 // per flop.  Measured on this part with random operands: the 16x16x32 instruction sustains about 10 % more
@@ -562,7 +325,8 @@ struct PipelinedLoop16 {
         constexpr int NMFMA = TN * NL, NREAD = NL + TN;
         // reads go out in the first half of a k-step, so that they have returned long before the barrier
         constexpr int READ_EVERY = NMFMA / 2 / NREAD > 0 ? NMFMA / 2 / NREAD : 1;
-        constexpr int B_EVERY = NMFMA / B_LOADS, A_EVERY = NMFMA / 2 / A_LOADS > 0 ? NMFMA / 2 / A_LOADS : 1;
+        constexpr int B_EVERY = NMFMA / B_LOADS > 0 ? NMFMA / B_LOADS : 1;
+        constexpr int A_EVERY = NMFMA / 2 / A_LOADS > 0 ? NMFMA / 2 / A_LOADS : 1;
         static_assert(LIVE == 0 || (NMFMA >= NREAD * READ_EVERY && NMFMA >= B_LOADS && NMFMA >= A_LOADS * A_EVERY), "k-step too short");
         bf16x8 xa[2][NL], wb[2][TN];
 
@@ -640,10 +404,21 @@ struct PipelinedLoop16 {
     }
 };
 
-// Block tile of BM activation rows x BN weight rows, WAVES_M x WAVES_N waves, on the loop above.  Same LDS
-// row layout and the same requests as TileConfig with 64-wide slabs; only the lane-to-piece mapping of the
-// operand reads and of the accumulators differs: lane l reads row (l & 15), piece (l >> 4) of a k-step and
-// ends with output columns 4*(l >> 4) .. +3 of activation row (l & 15) of each 16 x 16 sub-tile.
+// Block tile of BM activation rows x BN weight rows over 64-wide K slabs, WAVES_M x WAVES_N waves, on the
+// loop above.  One output tile: rows [row0, row0+rows) of expert e times kNCols output columns from n0.
+//
+// LDS rows are 128 bytes (64 bf16).  They are filled by direct global->LDS loads: one wave-wide load writes
+// 1 KB of consecutive LDS (64 lanes x 16 bytes = 8 rows), and each lane chooses WHICH 16-byte piece of its
+// row it fetches, so that piece kc of row r lands at position kc ^ ((r >> 1) & 7): with the 64 LDS banks of
+// this chip, the 16 lanes that a 16-byte read serves per cycle then fall into 16 different bank groups, for
+// the fill as well as for the operand reads.  Lane l reads row (l & 15), piece (l >> 4) of a k-step and ends
+// with output columns 4*(l >> 4) .. +3 of activation row (l & 15) of each 16 x 16 sub-tile.
+//
+// SWIGLU: weight rows [0,BN/2) of the tile come from W_gate, [BN/2,BN) from W_up, for the same BN/2 hidden
+// columns; a wave holds matching gate and up columns and applies silu(g)*u itself.
+//
+// Two shapes are used: 256 x 256 with 2 x 2 waves (128 x 128 per wave) for full-height row tiles, and
+// 64 x 256 with 1 x 4 waves (64 x 64 per wave) for the short remainders, where the work is weight streaming.
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool SWIGLU>
 struct TileConfig16 {
     static constexpr int kBM = BM, kBN = BN;
@@ -669,7 +444,10 @@ struct TileConfig16 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int wm = wv / WAVES_N, wn = wv % WAVES_N;
 
-    // ---- sources of this lane's pieces (as in TileConfig) ----
+    // ---- sources of this lane's pieces ----
+    // Each descriptor opens the block's own window of a tensor (its activation rows, its weight rows), so
+    // 32-bit byte offsets suffice whatever the tensor size; with a gather list the window is the whole
+    // unpermuted input, whose size the host checks.
     constexpr int kRsrcFlags = 0x00020000;  // raw buffer of 32-bit words, no swizzle (gfx9 descriptor word 3)
     using FillsT = Fills<LOADS, A_LOADS, B1_FROM>;
     FillsT fills;
@@ -730,7 +508,8 @@ struct TileConfig16 {
 
     // ---- epilogue ----
     // The tile is transposed through LDS (free after the K loop: its last barrier follows the last operand
-    // read) exactly as in TileConfig: bf16 rows of OUT_COLS columns, 16-byte piece p of row r at position
+    // read), because a lane holds 8-byte runs scattered over 16 rows and a wave store of those touches 64
+    // cache lines: bf16 rows of OUT_COLS columns, 16-byte piece p of row r at position
     // p ^ (r mod PIECES), then every row leaves as consecutive 16-byte pieces of consecutive lanes.
     constexpr int TNO = SWIGLU ? TN / 2 : TN;
     constexpr int OUT_COLS = kNCols, ROWB = OUT_COLS * 2, PIECES = ROWB / 16;
@@ -867,20 +646,20 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
                            ws.small.tile_m, ws.small_max, cus, gu, dn);
     }
     if (bf16) {
-        // big tiles: 256 x 256 x 64 on four waves; small tiles: 64 x 256 x 64, four stages
+        // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
-            launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, true>,
+            launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig16<kFfnTileSmall, 256, 1, 4, true>,
                         true>(xp, w_gate, w_up, ws.hidden, row_token, ws.big, ws.small, K1, N1, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         if (bn_down == 256)
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, false>,
-                        TileConfig<kFfnTileSmall, 256, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
+                        TileConfig16<kFfnTileSmall, 256, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
                                                                                     ws.big_down, ws.small_down, K2, N2, st);
         else
             launch_bf16<TileConfig16<kFfnTileM, 128, 2, 2, false>,
-                        TileConfig<kFfnTileSmall, 128, 64, 4, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
+                        TileConfig16<kFfnTileSmall, 128, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
                                                                                     ws.big_down, ws.small_down, K2, N2, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
