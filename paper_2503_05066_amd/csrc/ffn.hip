@@ -41,12 +41,10 @@ struct TileListArgs {
 struct ExpertTiles {
     int lo, rows, nb, ns;
 };
-__device__ inline ExpertTiles expert_tiles(const int32_t* __restrict__ expert_offset, int e, int E, int big,
-                                           int small, int small_max) {
+__device__ inline ExpertTiles expert_tiles(int lo, int hi, int big, int small, int small_max) {
     ExpertTiles t;
-    t.lo = e < E ? expert_offset[e] : 0;
-    const int hi = e < E ? expert_offset[e + 1] : 0;
-    t.rows = hi - t.lo;
+    t.lo = lo;
+    t.rows = hi - lo;
     const int full = t.rows / big, rem = t.rows - full * big;
     const bool rem_small = rem > 0 && rem <= small_max;
     t.nb = full + (rem > 0 && !rem_small ? 1 : 0);
@@ -72,14 +70,32 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
                                                           int small, int small_max, int cus, TileListArgs first,
                                                           TileListArgs second) {
     const int lane = threadIdx.x;
-    // totals first: which big tiles are the last ones is only known then
+    // Every lane's experts, fetched once, and one scan per 64 experts: the kernel is a chain of latencies
+    // (a dependent global load costs a microsecond, a wave scan half of one), so nothing is done twice.
+    constexpr int kChunks = kMaxExperts / kWave;
+    ExpertTiles t[kChunks];
+    int start_b[kChunks], start_s[kChunks];  // index of the lane's first tile in either list
     int nt_b = 0, nt_s = 0;
-    for (int e0 = 0; e0 < E; e0 += kWave) {
-        const ExpertTiles t = expert_tiles(expert_offset, e0 + lane, E, big, small, small_max);
-        int ib = t.nb, is = t.ns, unused = 0;
-        wave_scan3(ib, is, unused);
-        nt_b += __shfl(ib, kWave - 1, kWave);
-        nt_s += __shfl(is, kWave - 1, kWave);
+    {
+        int lo[kChunks], hi[kChunks];
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) {
+            const int e = c * kWave + lane;
+            lo[c] = e < E ? expert_offset[e] : 0;
+            hi[c] = e < E ? expert_offset[e + 1] : 0;
+        }
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) {
+            t[c] = expert_tiles(lo[c], hi[c], big, small, small_max);
+            start_b[c] = start_s[c] = 0;
+            if (c * kWave >= E) continue;  // the same for every lane
+            int ib = t[c].nb, is = t[c].ns, unused = 0;
+            wave_scan3(ib, is, unused);
+            start_b[c] = nt_b + ib - t[c].nb;
+            start_s[c] = nt_s + is - t[c].ns;
+            nt_b += __shfl(ib, kWave - 1, kWave);
+            nt_s += __shfl(is, kWave - 1, kWave);
+        }
     }
     const int pieces = big / small;
     for (int which = 0; which < 2; ++which) {
@@ -96,62 +112,57 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
             }
         }
         const int first_conv = nt_b - conv;  // big tiles from this index on are cut into pieces
-        int base_b = 0, base_s = 0, base_p = 0;
-        for (int e0 = 0; e0 < E; e0 += kWave) {
-            const int e = e0 + lane;
-            const ExpertTiles t = expert_tiles(expert_offset, e, E, big, small, small_max);
-            int ib = t.nb, is = t.ns;
-            // pieces of this expert's converted tiles (they are the last tiles of the list, hence of the expert)
-            int ip = 0;
-            {
-                int ib_excl = t.nb, d1 = 0, d2 = 0;
-                wave_scan3(ib_excl, d1, d2);
-                const int start = base_b + ib_excl - t.nb;
-                for (int i = 0; i < t.nb; ++i)
-                    if (start + i >= first_conv) {
-                        const int left = t.rows - i * big;
+        int base_p = nt_s;                   // the pieces follow the regular short tiles
+#pragma unroll
+        for (int ch = 0; ch < kChunks; ++ch) {
+            if (ch * kWave >= E) continue;
+            const int e = ch * kWave + lane;
+            const ExpertTiles& x = t[ch];
+            int p = 0;
+            if (conv > 0) {  // where this expert's pieces go: a scan over the pieces of the converted tiles
+                int ip = 0, d1 = 0, d2 = 0;
+                for (int i = 0; i < x.nb; ++i)
+                    if (start_b[ch] + i >= first_conv) {
+                        const int left = x.rows - i * big;
                         ip += ((left < big ? left : big) + small - 1) / small;
                     }
+                const int np = ip;
+                wave_scan3(ip, d1, d2);
+                p = base_p + ip - np;
+                base_p += __shfl(ip, kWave - 1, kWave);
             }
-            const int np = ip;
-            wave_scan3(ib, is, ip);
-            const int start_b = base_b + ib - t.nb, start_s = base_s + is - t.ns, start_p = nt_s + base_p + ip - np;
-            int p = start_p;
-            for (int i = 0; i < t.nb; ++i) {
-                const int idx = start_b + i;
-                const int left = t.rows - i * big;
+            for (int i = 0; i < x.nb; ++i) {
+                const int idx = start_b[ch] + i;
+                const int left = x.rows - i * big;
                 const int rows = left < big ? left : big;
                 if (idx < first_conv) {
                     if (idx < L.b_max) {
                         L.b_expert[idx] = e;
-                        L.b_row0[idx] = t.lo + i * big;
+                        L.b_row0[idx] = x.lo + i * big;
                         L.b_rows[idx] = rows;
                     }
                 } else {
                     for (int r = 0; r < rows; r += small, ++p)
                         if (p < L.s_max) {
                             L.s_expert[p] = e;
-                            L.s_row0[p] = t.lo + i * big + r;
+                            L.s_row0[p] = x.lo + i * big + r;
                             L.s_rows[p] = rows - r < small ? rows - r : small;
                         }
                 }
             }
-            const int full = t.rows / big, rem = t.rows - full * big;
-            for (int i = 0; i < t.ns; ++i) {
-                const int idx = start_s + i;
+            const int full = x.rows / big, rem = x.rows - full * big;
+            for (int i = 0; i < x.ns; ++i) {
+                const int idx = start_s[ch] + i;
                 if (idx < L.s_max) {
                     L.s_expert[idx] = e;
-                    L.s_row0[idx] = t.lo + full * big + i * small;
+                    L.s_row0[idx] = x.lo + full * big + i * small;
                     const int left = rem - i * small;
                     L.s_rows[idx] = left < small ? left : small;
                 }
             }
-            base_b += __shfl(ib, kWave - 1, kWave);
-            base_s += __shfl(is, kWave - 1, kWave);
-            base_p += __shfl(ip, kWave - 1, kWave);
         }
         if (lane == 0) {
-            const int nb = nt_b - conv, ns = nt_s + base_p;
+            const int nb = nt_b - conv, ns = base_p;
             *L.b_count = nb < L.b_max ? nb : L.b_max;
             *L.s_count = ns < L.s_max ? ns : L.s_max;
         }
