@@ -41,20 +41,22 @@ struct TileListArgs {
 struct ExpertTiles {
     int lo, rows, nb, ns;
 };
-__device__ inline ExpertTiles expert_tiles(int lo, int hi, int big, int small, int small_max) {
+// Tile heights are powers of two (big = 1 << big_sh, small = 1 << small_sh): a single wave runs this kernel,
+// every dependent instruction counts, and a division by a run-time value is forty of them.
+__device__ inline ExpertTiles expert_tiles(int lo, int hi, int big_sh, int small_sh, int small_max) {
     ExpertTiles t;
     t.lo = lo;
     t.rows = hi - lo;
-    const int full = t.rows / big, rem = t.rows - full * big;
+    const int full = t.rows >> big_sh, rem = t.rows - (full << big_sh);
     const bool rem_small = rem > 0 && rem <= small_max;
     t.nb = full + (rem > 0 && !rem_small ? 1 : 0);
-    t.ns = rem_small ? (rem + small - 1) / small : 0;
+    t.ns = rem_small ? (rem + (1 << small_sh) - 1) >> small_sh : 0;
     return t;
 }
 
 // inclusive scan of three counters over the wave
 __device__ inline void wave_scan3(int& a, int& b, int& c) {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
         const int oa = __shfl_up(a, off, kWave), ob = __shfl_up(b, off, kWave), oc = __shfl_up(c, off, kWave);
@@ -66,10 +68,12 @@ __device__ inline void wave_scan3(int& a, int& b, int& c) {
     }
 }
 
-__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big,
-                                                          int small, int small_max, int cus, TileListArgs first,
+__global__ __launch_bounds__(128) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big_sh,
+                                                          int small_sh, int small_max, int cus, TileListArgs first,
                                                           TileListArgs second) {
-    const int lane = threadIdx.x;
+    // two waves: each builds the pair of lists of one GEMM (both need the same counts and compute them alike)
+    const int lane = threadIdx.x & (kWave - 1), which = threadIdx.x >> 6;
+    const int big = 1 << big_sh, small = 1 << small_sh;
     // Every lane's experts, fetched once, and one scan per 64 experts: the kernel is a chain of latencies
     // (a dependent global load costs a microsecond, a wave scan half of one), so nothing is done twice.
     constexpr int kChunks = kMaxExperts / kWave;
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
         }
 #pragma unroll
         for (int c = 0; c < kChunks; ++c) {
-            t[c] = expert_tiles(lo[c], hi[c], big, small, small_max);
+            t[c] = expert_tiles(lo[c], hi[c], big_sh, small_sh, small_max);
             start_b[c] = start_s[c] = 0;
             if (c * kWave >= E) continue;  // the same for every lane
             int ib = t[c].nb, is = t[c].ns, unused = 0;
@@ -97,16 +101,17 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
             nt_s += __shfl(is, kWave - 1, kWave);
         }
     }
-    const int pieces = big / small;
-    for (int which = 0; which < 2; ++which) {
+    const int pieces = 1 << (big_sh - small_sh);
+    {
         const TileListArgs& L = which == 0 ? first : second;
-        if (which == 1 && second.b_expert == first.b_expert) break;  // one pair of lists serves both GEMMs
+        if (which == 1 && second.b_expert == first.b_expert) return;  // one pair of lists serves both GEMMs
         // big row tiles of the nearly empty last round, if their pieces fit into one round of short items
         int conv = 0;
-        if (L.ncol > 0 && cus > 0 && (long long)nt_b * L.ncol >= cus) {
-            const int rem = (int)(((long long)nt_b * L.ncol) % cus);
+        const long long items = (long long)nt_b * L.ncol;
+        if (L.ncol > 0 && cus > 0 && items >= cus && items < (1ll << 31)) {
+            const unsigned rem = (unsigned)items % (unsigned)cus;
             if (rem > 0) {
-                int c = (rem + L.ncol - 1) / L.ncol;
+                int c = (int)((rem + (unsigned)L.ncol - 1u) / (unsigned)L.ncol);
                 c = c > nt_b ? nt_b : c;
                 if ((long long)(nt_s + pieces * c) * L.ncol <= cus) conv = c;
             }
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
                 for (int i = 0; i < x.nb; ++i)
                     if (start_b[ch] + i >= first_conv) {
                         const int left = x.rows - i * big;
-                        ip += ((left < big ? left : big) + small - 1) / small;
+                        ip += ((left < big ? left : big) + small - 1) >> small_sh;
                     }
                 const int np = ip;
                 wave_scan3(ip, d1, d2);
@@ -150,7 +155,7 @@ __global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restr
                         }
                 }
             }
-            const int full = x.rows / big, rem = x.rows - full * big;
+            const int full = x.rows >> big_sh, rem = x.rows - (full << big_sh);
             for (int i = 0; i < x.ns; ++i) {
                 const int idx = start_s[ch] + i;
                 if (idx < L.s_max) {
@@ -653,8 +658,13 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
         // gate/up: a big item covers 128 hidden columns (gate and up rows of them); fp32: one pair of lists, as cut
         const TileListArgs gu = args(ws.big, ws.small, bf16 ? N1 / 128 : 0);
         const TileListArgs dn = bf16 ? args(ws.big_down, ws.small_down, N2 / bn_down) : gu;
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts, ws.big.tile_m,
-                           ws.small.tile_m, ws.small_max, cus, gu, dn);
+        auto log2i = [](int v) {
+            int sh = 0;
+            while ((1 << sh) < v) ++sh;
+            return sh;
+        };
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(128), 0, st, expert_offset, d.n_experts,
+                           log2i(ws.big.tile_m), log2i(ws.small.tile_m), ws.small_max, cus, gu, dn);
     }
     if (bf16) {
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each

@@ -19,29 +19,36 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-__device__ inline uint16_t bf16_rne_bits(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
 constexpr int kRmTokens = 128;  // tokens per block
 constexpr int kRmSlab = 32;     // k per LDS stage
+
+// two floats -> two bf16 (round to nearest even) in one word, the first in the low half: the hardware conversion
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ inline uint32_t bf16_pair(float a, float b) {
+    const f32x2_t v = {a, b};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    return *(const uint32_t*)&r;
+}
 
 // 8 fp32 router weights -> the three bf16 planes (w = hi + mid + lo exactly), 16 bytes each
 __device__ inline void split_planes(const float4& a, const float4& b, uint4& hi, uint4& mid, uint4& lo) {
     const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    uint32_t h[8], m[8], l[8];
+    uint32_t h[4], m[4], l[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        h[i] = bf16_rne_bits(v[i]);
-        const float r1 = v[i] - __uint_as_float(h[i] << 16);
-        m[i] = bf16_rne_bits(r1);
-        const float r2 = r1 - __uint_as_float(m[i] << 16);
-        l[i] = bf16_rne_bits(r2);
+    for (int i = 0; i < 4; ++i) {
+        // a pair at a time; the bf16 of the even element is the word's low half, of the odd one its high half
+        h[i] = bf16_pair(v[2 * i], v[2 * i + 1]);
+        const float r0 = v[2 * i] - __uint_as_float(h[i] << 16);
+        const float r1 = v[2 * i + 1] - __uint_as_float(h[i] & 0xffff0000u);
+        m[i] = bf16_pair(r0, r1);
+        const float q0 = r0 - __uint_as_float(m[i] << 16);
+        const float q1 = r1 - __uint_as_float(m[i] & 0xffff0000u);
+        l[i] = bf16_pair(q0, q1);
     }
-    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    mid = make_uint4(m[0] | (m[1] << 16), m[2] | (m[3] << 16), m[4] | (m[5] << 16), m[6] | (m[7] << 16));
-    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    mid = make_uint4(m[0], m[1], m[2], m[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // TN = 32-expert tiles (E padded to 32*TN).  out: [ksplit, N, E] partial sums (or the logits
