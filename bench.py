@@ -26,7 +26,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 # HBM bytes per launch of the gate/up GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
 # 1 GiB device copy (profiles/olmoe_token_drop_gamma1_layer.md); keyed by (workload, mode, scope, gamma)
-MEASURED_TRAFFIC = {("olmoe", "token", "local", 1.0): 680.7e6 + 28.6e6}
+MEASURED_TRAFFIC = {("olmoe", "token", "local", 1.0): 680.5e6 + 28.6e6}
 
 MODES = {"none": 0, "token": 1, "expanded": 2}
 SCOPES = {"local": 0, "global": 1, "local_device": 2, "global_device": 3}
