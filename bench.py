@@ -55,6 +55,10 @@ def parse():
                    help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
+    p.add_argument("--ffn-uniform", default="mixtral",
+                   help="comma list of workloads whose expert FFN is also timed alone on experts of equal size "
+                        "(N*k/E rows each, no router, no drop) with the vendor library's dense GEMM of the same "
+                        "dimensions beside it ('' for none; skipped with --no-peaks)")
     p.add_argument("--others", default="olmoe:none,finegrained:expanded,finegrained:token,finegrained:none,decode:token,decode:expanded,decode:none,mixtral:none,mixtral:expanded,mixtral:token:local_device,mixtral:token",
                    help="comma list of workload:mode[:scope] measured after the main line ('' for none)")
     return p.parse_args()
@@ -303,6 +307,67 @@ def measured_peaks():
                    "1 GiB device copies (read + written bytes)"}
 
 
+def ffn_uniform(w, reps=7):
+    """The grouped FFN alone on experts of equal size (N*k/E rows each): what the two GEMM kernels sustain when no
+    tile is ragged, and torch.matmul (the vendor library) on one dense GEMM of the same M, N, K for comparison."""
+    import torch
+
+    from paper_2503_05066_amd import capmoe
+
+    e, d, h = w.n_experts, w.d_model, w.d_hidden
+    m = max(1, w.n_tokens * w.top_k // e)
+    rows = m * e
+    t = upload(w)
+    desc = capmoe.make_desc(rows, d, e, 1, h, 1, MODES["none"], SCOPES["local"], 1.0, w.dtype)
+    _, _, max_rows, wsb = capmoe.moe_query(desc)
+    assert max_rows == rows
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    xp = torch.randn(rows, d, device="cuda", generator=gen).to(torch.bfloat16)
+    off = torch.arange(0, rows + 1, m, dtype=torch.int32, device="cuda")
+    yp = torch.empty(rows, d, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+
+    def run():
+        capmoe.moe_grouped_ffn(desc, xp, off, t["w_gate"], t["w_up"], t["w_down"], yp, ws)
+
+    run()
+    torch.cuda.synchronize()
+    out = {"workload": w.name, "experts": e, "rows_per_expert": m, "d": d, "h": h}
+    for name, flops in (("ffn_gate_up", 4 * d * h * rows), ("ffn_down", 2 * d * h * rows)):
+        kid = capmoe.KERNELS.index(name)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for s0, s1 in evs:
+            s0.record()
+            s1.record()
+        torch.cuda.synchronize()
+        for s0, s1 in evs:
+            capmoe.moe_profile_attach(kid, s0, s1)
+            run()
+        torch.cuda.synchronize()
+        capmoe.moe_profile_attach(kid, None, None)
+        ms = sorted(s0.elapsed_time(s1) for s0, s1 in evs)[reps // 2]
+        out[name] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1),
+                     "frac_of_peak": round(flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    # the same dimensions as one dense NT GEMM each, through the vendor library
+    for name, (mm, nn, kk) in (("vendor_dense_gate_up", (rows, 2 * h, d)), ("vendor_dense_down", (rows, d, h))):
+        a_ = torch.randn(mm, kk, device="cuda", generator=gen).to(torch.bfloat16)
+        b_ = torch.randn(nn, kk, device="cuda", generator=gen).to(torch.bfloat16)
+        for _ in range(2):
+            c_ = a_ @ b_.T
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for s0, s1 in evs:
+            s0.record()
+            c_ = a_ @ b_.T
+            s1.record()
+        torch.cuda.synchronize()
+        ms = sorted(s0.elapsed_time(s1) for s0, s1 in evs)[reps // 2]
+        out[name] = {"ms": round(ms, 4), "TFLOP/s": round(2 * mm * nn * kk / ms / 1e9, 1)}
+        del a_, b_, c_
+    out["note"] = ("vendor_dense_*: torch.matmul on ONE dense NT GEMM with the same M, N, K (a single weight matrix, "
+                   "so E times less weight traffic than the grouped GEMM: comparable where the matrix cores bind)")
+    return out
+
+
 def roofline_of(work, ms):
     """The binding roof of a kernel: the larger of its MFMA time and its HBM time at peak."""
     t_mfma = work["flops"] / (MFMA_BF16_PEAK_TFLOPS * 1e12)
@@ -457,6 +522,9 @@ def main():
                        "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
     if others:
         out["other_workloads"] = others
+    uniform = [] if a.no_peaks else [ffn_uniform(synth.WORKLOADS[n]) for n in a.ffn_uniform.split(",") if n]
+    if uniform:
+        out["ffn_uniform_experts"] = uniform
     if not a.no_straggler and w.device_groups == 1:
         # the default workload has one device; show the latency model on the Mixtral-shaped one (4 devices x 2 experts)
         names = {o["workload"] for o in others}
