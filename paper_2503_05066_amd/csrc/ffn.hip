@@ -230,7 +230,6 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     return *(const uint32_t*)&b;
 }
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 // s_waitcnt immediate for "at most n vector-memory operations outstanding, LDS/scalar counter
@@ -248,10 +247,6 @@ struct Fills {
     static constexpr int kALoads = A_LOADS;
     __amdgpu_buffer_rsrc_t a, b0, b1;
     uint32_t voff[LOADS];
-    template <int I>
-    __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc() const {
-        return I < A_LOADS ? a : (I >= B1_FROM ? b1 : b0);
-    }
     __device__ __forceinline__ void one(int i, uint8_t* lds_dst, uint32_t k_bytes) const {
         // i is a compile-time constant after unrolling
         const __amdgpu_buffer_rsrc_t r = i < A_LOADS ? a : (i >= B1_FROM ? b1 : b0);
