@@ -476,6 +476,28 @@ def test_ffn_nearly_empty_last_round(orc):
     assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "tail")
 
 
+def test_ffn_many_experts(orc):
+    """200 experts (the tile schedule walks them 64 at a time), most with a handful of rows, some empty, a few with
+    several tiles."""
+    rng = np.random.default_rng(77)
+    counts = [int(c) for c in rng.choice([0, 1, 3, 17, 40, 64, 65, 130, 300, 520], size=200,
+                                         p=[0.1, 0.1, 0.2, 0.2, 0.15, 0.05, 0.05, 0.05, 0.05, 0.05])]
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="many", n_tokens=n, d_model=128, n_experts=e, top_k=1, d_hidden=128,
+                     device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    rng.shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 9.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    buf = run_layer(layer, layer.desc(NONE, GLOBAL, 1.0), logits)
+    assert_plan_equal(buf, ref, "many experts")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "many experts")
+
+
 @pytest.mark.parametrize("trial", range(5))
 def test_ffn_random_expert_sizes(orc, trial):
     """Random row counts per expert (empty experts, 1 row, around every tile boundary, several tiles) and random
