@@ -177,6 +177,7 @@ int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* exper
  * moe_dispatch followed by moe_grouped_ffn in one call, without materialising xp: the first GEMM
  * fetches row r of the plan from x[row_token[r],:] directly (same arithmetic, bit-identical yp).
  *   x [N,d] in desc->dtype, row_token [P_max] and expert_offset [E+1] from moe_capacity_drop.
+ *   bf16: x must be smaller than 4 GiB (N*d < 2^31), else MOE_ERR_UNSUPPORTED (use the two separate calls).
  */
 int moe_dispatch_ffn(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
                      const void* w_gate, const void* w_up, const void* w_down, void* yp, void* workspace,

@@ -124,8 +124,12 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
 
 ProfileSlot g_profile[MOE_KERNEL_COUNT] = {};
 
-static int ffn_shape_supported(const moe_desc_t& d) {
-    if (d.dtype == MOE_DTYPE_BF16 && (d.d_model % 128 != 0 || d.d_hidden % 128 != 0)) return MOE_ERR_UNSUPPORTED;
+// gathered: the first GEMM fetches its rows from the unpermuted x (moe_dispatch_ffn): the bf16 kernels address x
+// through one buffer descriptor with 32-bit byte offsets, so x must stay below 4 GiB
+static int ffn_shape_supported(const moe_desc_t& d, bool gathered) {
+    if (d.dtype != MOE_DTYPE_BF16) return MOE_OK;
+    if (d.d_model % 128 != 0 || d.d_hidden % 128 != 0) return MOE_ERR_UNSUPPORTED;
+    if (gathered && (uint64_t)d.n_tokens * (uint64_t)d.d_model >= (1ull << 31)) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 
@@ -257,7 +261,7 @@ static int grouped_ffn_impl(const moe_desc_t* desc, const void* a, const int32_t
     if (!a || !expert_offset || !w_gate || !w_up || !w_down || !yp || !workspace) return MOE_ERR_INVALID_ARG;
     if (misaligned16(a) || misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
         return MOE_ERR_INVALID_ARG;
-    const int sh = ffn_shape_supported(*desc);
+    const int sh = ffn_shape_supported(*desc, row_token != nullptr);
     if (sh != MOE_OK) return sh;
     const Sizes s = derive(*desc);
     const FfnWorkspace ws = ffn_workspace(*desc, s, workspace);
@@ -322,7 +326,7 @@ int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_rout
         if (!row_token || !row_weight || !w_gate || !w_up || !w_down || !yp) return MOE_ERR_INVALID_ARG;
         if (misaligned16(w_gate) || misaligned16(w_up) || misaligned16(w_down) || misaligned16(yp))
             return MOE_ERR_INVALID_ARG;
-        const int sh = ffn_shape_supported(*desc);
+        const int sh = ffn_shape_supported(*desc, true);
         if (sh != MOE_OK) return sh;
         const size_t need_ffn = ffn_workspace(*desc, s, nullptr).bytes;
         if (need_ffn > need) need = need_ffn;

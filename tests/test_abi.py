@@ -118,3 +118,9 @@ def test_bad_arguments_are_refused_on_the_host():
     assert lib.moe_combine(ctypes.byref(ok), z, z, z, z, z) == 1
     assert lib.moe_layer_forward(ctypes.byref(ok), *([z] * 7), 0, *([z] * 13), 0, z) == 1
     assert lib.moe_query(None, None, None, None, None) == 1
+    # x of 4 GiB or more: the gathered form of the bf16 FFN refuses (it addresses x with 32-bit byte offsets), the
+    # form on permuted rows does not (it stops at the workspace check here; nothing is launched either way)
+    big = capmoe.make_desc(1 << 21, 1024, 8, 2, 1024, dtype=1)
+    f = ctypes.c_void_p(0x1000)
+    assert lib.moe_dispatch_ffn(ctypes.byref(big), f, f, f, f, f, f, f, f, 0, z) == 2
+    assert lib.moe_grouped_ffn(ctypes.byref(big), f, f, f, f, f, f, f, 0, z) == 3
