@@ -533,13 +533,13 @@ __global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* _
 // block gets by counting the candidates of every segment itself from the top-k lists (read from L2
 // by every block: small next to a launch as long as the lists are short).
 constexpr int kFusedThreads = 1024;
-constexpr int kFusedWaves = kFusedThreads / kWave;
-constexpr int kFusedMaxTokens = 8192;  // tokens of a segment: its keys and slots live in LDS
+constexpr int kFusedMaxTokens = 8 * kFusedThreads;  // tokens of a segment: its keys and slots live in LDS
 constexpr int kFusedMaxSegs = 2048;    // capacity segments (one candidate counter each)
 constexpr int kFusedCounters = 4096;   // counters in LDS: as many private copies of the segment counters as fit
 constexpr long long kFusedMaxWork = 8ll << 20;  // segments x top-k list entries: above it, three launches are cheaper
 
-// exclusive prefix sum of v over the block's 1024 threads; *total gets the block sum
+// exclusive prefix sum of v over the block's NT threads; *total gets the block sum
+template <int NT>
 __device__ inline int fused_exclusive_scan(int v, int* red, int* total) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     int incl = v;
@@ -553,7 +553,7 @@ __device__ inline int fused_exclusive_scan(int v, int* red, int* total) {
     __syncthreads();
     int before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < kFusedWaves; ++w) {
+    for (int w = 0; w < NT / kWave; ++w) {
         const int r = red[w];
         before += w < wv ? r : 0;
         all += r;
@@ -564,22 +564,24 @@ __device__ inline int fused_exclusive_scan(int v, int* red, int* total) {
 
 // EXPANDED: Expanded Drop; ONE_BLOCK: a single capacity block (every token belongs to the block's segment
 // list); VW: entries of a top-k list fetched per load (divides k).  The pass over the lists is the bulk of
-// the kernel's instructions, so it is specialised.
-template <bool EXPANDED, bool ONE_BLOCK, int VW>
-__global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
+// the kernel's instructions, so it is specialised.  NT: threads of the block, a segment holds at most 8 * NT
+// tokens (short segments of short batches take small blocks: several per CU).
+template <bool EXPANDED, bool ONE_BLOCK, int VW, int NT>
+__global__ __launch_bounds__(NT) void drop_fused_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ topk_idx, const uint8_t* __restrict__ token_class,
     uint32_t seed, int32_t* __restrict__ expert_count, int32_t* __restrict__ seg_count,
     int32_t* __restrict__ expert_offset, int32_t* __restrict__ row_token, float* __restrict__ row_weight,
     int32_t* __restrict__ pair_row, int N, int E, int k, int S, int group_tokens, int group_experts, int metric,
     int seg_tokens, int n_blocks, int cap, int weight_from_key) {
+    constexpr int kWaves = NT / kWave, kMaxTok = NT * 8;
     // a thread owns a run of consecutive tokens of the segment; one padding word per 16 keeps the runs of
     // neighbouring threads on different LDS banks
-    __shared__ uint32_t key_s[kFusedMaxTokens + kFusedMaxTokens / 16];
-    __shared__ uint8_t slot_s[kFusedMaxTokens];
+    __shared__ uint32_t key_s[kMaxTok + kMaxTok / 16];
+    __shared__ uint8_t slot_s[kMaxTok];
     __shared__ int cand[kFusedCounters];
     __shared__ int hist[256];
-    __shared__ int red[kFusedWaves];
-    __shared__ int red3[kFusedWaves][3];
+    __shared__ int red[kWaves];
+    __shared__ int red3[kWaves][3];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_rem;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -592,7 +594,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
     const int copies = kFusedCounters / pitch < kWave ? kFusedCounters / pitch : kWave;  // >= 1
     auto pad = [](int i) { return i + (i >> 4); };
 
-    for (int i = tid; i < copies * pitch; i += kFusedThreads) cand[i] = 0;
+    for (int i = tid; i < copies * pitch; i += NT) cand[i] = 0;
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
 
@@ -606,13 +608,14 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
         int* mine = cand + (lane % copies) * pitch;
         constexpr int kTok = 4;        // tokens per thread and round
         constexpr int kVec = 8 / VW;   // loads per token and chunk of eight entries
-        for (int t0 = tid; t0 < N; t0 += kFusedThreads * kTok) {
+        const int t_end = N;
+        for (int t0 = tid; t0 < t_end; t0 += NT * kTok) {
             uint32_t info[kTok] = {0u, 0u, 0u, 0u};
             int tq[kTok];
 #pragma unroll
             for (int q = 0; q < kTok; ++q) {
-                const int t = t0 + kFusedThreads * q;
-                tq[q] = t < N ? t : N - 1;  // a token past the end re-reads the last one and is ignored below
+                const int t = t0 + NT * q;
+                tq[q] = t < t_end ? t : t_end - 1;  // a token past the end re-reads the last one and is ignored below
             }
             for (int j0 = 0; j0 < k; j0 += 8) {
                 vec_t x[kTok][kVec];  // independent loads, all issued before anything waits
@@ -625,7 +628,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
                     }
 #pragma unroll
                 for (int q = 0; q < kTok; ++q) {
-                    if (t0 + kFusedThreads * q >= N) continue;
+                    if (t0 + NT * q >= t_end) continue;
                     const int t = tq[q];
                     const int bb = ONE_BLOCK ? 0 : t / seg_tokens;
                     const int g0 = EXPANDED ? (t / group_tokens) * group_experts : 0;
@@ -645,8 +648,8 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
             }
 #pragma unroll
             for (int q = 0; q < kTok; ++q) {
-                const int t = t0 + kFusedThreads * q;
-                if (t < N && (ONE_BLOCK || t / seg_tokens == b)) key_s[pad(t - b * seg_tokens)] = info[q];
+                const int t = t0 + NT * q;
+                if (t < t_end && (ONE_BLOCK || t / seg_tokens == b)) key_s[pad(t - b * seg_tokens)] = info[q];
             }
         }
     }
@@ -654,13 +657,13 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
 
     // ---- keys and slots of this block's segment ----
     {
-        constexpr int kPer = kFusedMaxTokens / kFusedThreads;
+        constexpr int kPer = 8;
         const int g_e = e / group_experts;  // device of this expert
         uint32_t info[kPer], rank[kPer];
         bool c[kPer];
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
-            const int tl = tid + kFusedThreads * j;
+            const int tl = tid + NT * j;
             const int t = b * seg_tokens + tl;
             info[j] = tl < seg_tokens ? key_s[pad(tl)] : 0u;
             c[j] = tl < seg_tokens && ((info[j] >> 20) != 0u || (EXPANDED && t / group_tokens == g_e));
@@ -680,7 +683,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
         }
 #pragma unroll
         for (int j = 0; j < kPer; ++j) {
-            const int tl = tid + kFusedThreads * j;
+            const int tl = tid + NT * j;
             if (tl >= seg_tokens) continue;
             const int t = b * seg_tokens + tl;
             int below = (int)(info[j] & 1023u);
@@ -703,7 +706,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
 
     // ---- kept rows of every segment: this block's first row, its expert's total ----
     int before = 0, own_total = 0, n_cand = 0;
-    for (int i = tid; i < segs; i += kFusedThreads) {
+    for (int i = tid; i < segs; i += NT) {
         int c = 0;
         for (int r = 0; r < copies; ++r) c += cand[r * pitch + i];
         const int bb = i / E, ee = i - bb * E;
@@ -734,7 +737,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
     int row0 = 0, total;
     own_total = n_cand = 0;
 #pragma unroll
-    for (int w = 0; w < kFusedWaves; ++w) {
+    for (int w = 0; w < kWaves; ++w) {
         row0 += red3[w][0];
         own_total += red3[w][1];
         n_cand += red3[w][2];
@@ -763,7 +766,7 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
                 if (tid < 256) hist[tid] = 0;
                 __syncthreads();
                 const uint32_t hi_mask = 0xffffffffu << (shift + 8);
-                for (int tl = tid; tl < seg_tokens; tl += kFusedThreads) {
+                for (int tl = tid; tl < seg_tokens; tl += NT) {
                     const uint32_t kx = key_s[pad(tl)];
                     if (kx != 0u && (kx & hi_mask) == prefix) atomicAdd(&hist[(kx >> shift) & 255u], 1);
                 }
@@ -803,20 +806,20 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
     }
 
     // ---- ordered compaction: rows in ascending token order, ties at the threshold to the lower tokens ----
-    const int run = (seg_tokens + kFusedThreads - 1) / kFusedThreads;  // at most 8
+    const int run = (seg_tokens + NT - 1) / NT;  // at most 8
     const int tb = tid * run;
-    uint32_t kx[kFusedMaxTokens / kFusedThreads];
+    uint32_t kx[8];
     int eq_cnt = 0;
 #pragma unroll
-    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+    for (int j = 0; j < 8; ++j) {
         kx[j] = j < run && tb + j < seg_tokens ? key_s[pad(tb + j)] : 0u;
         eq_cnt += kx[j] != 0u && kx[j] == tau;
     }
-    int eq_rank = fused_exclusive_scan(eq_cnt, red, &total);
+    int eq_rank = fused_exclusive_scan<NT>(eq_cnt, red, &total);
     uint32_t keep_bits = 0;
     int keep_cnt = 0;
 #pragma unroll
-    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+    for (int j = 0; j < 8; ++j) {
         const bool c = kx[j] != 0u;
         const bool eq = c && kx[j] == tau;
         const bool keep = c && (kx[j] > tau || (eq && eq_rank < need));
@@ -824,9 +827,9 @@ __global__ __launch_bounds__(kFusedThreads) void drop_fused_kernel(
         keep_cnt += keep;
         keep_bits |= (uint32_t)keep << j;
     }
-    int pos = row0 + fused_exclusive_scan(keep_cnt, red, &total);
+    int pos = row0 + fused_exclusive_scan<NT>(keep_cnt, red, &total);
 #pragma unroll
-    for (int j = 0; j < kFusedMaxTokens / kFusedThreads; ++j) {
+    for (int j = 0; j < 8; ++j) {
         if (kx[j] == 0u) continue;
         const int t = b * seg_tokens + tb + j;
         const bool keep = (keep_bits >> j) & 1u;
@@ -848,26 +851,36 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     const int N = d.n_tokens, E = d.n_experts;
     {
         const int segs_all = s.n_blocks * E;
-        const bool fused = s.span == 1 && !(d.max_experts && s.slots > d.top_k) && N > 0 && s.seg_tokens <= kFusedMaxTokens &&
-                           segs_all + 1 <= kFusedCounters && segs_all <= kFusedMaxSegs &&
-                           (long long)segs_all * N * s.list_k <= kFusedMaxWork;
+        constexpr int kSmallBlock = 256;  // threads of a block for short segments of short batches
+        const bool fused = s.span == 1 && !(d.max_experts && s.slots > d.top_k) && N > 0 &&
+                           s.seg_tokens <= kFusedMaxTokens && segs_all + 1 <= kFusedCounters &&
+                           segs_all <= kFusedMaxSegs && (long long)segs_all * N * s.list_k <= kFusedMaxWork;
         if (fused) {
-            ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
+            // every block reads all N lists: small blocks only where that is a single round for them too
+            const bool small = s.seg_tokens <= 8 * kSmallBlock && N <= 8 * kSmallBlock;
             const bool ex = d.mode == MOE_MODE_EXPANDED_DROP, one = s.n_blocks == 1;
-            auto launch = [&](auto kern) {
-                hipLaunchKernelGGL(kern, dim3(segs_all), dim3(kFusedThreads), 0, st, scores, topk_idx, token_class, seed,
+            auto launch = [&](auto kern, int threads) {
+                ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
+                hipLaunchKernelGGL(kern, dim3(segs_all), dim3(threads), 0, st, scores, topk_idx, token_class, seed,
                                    expert_count, seg_count, expert_offset, row_token, row_weight, pair_row, N, E, s.list_k,
                                    s.slots, s.group_tokens, s.group_experts, d.metric, s.seg_tokens, s.n_blocks, s.cap,
                                    d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
             };
-            auto by_width = [&](auto ex_c, auto one_c) {
+            auto by_size = [&](auto ex_c, auto one_c, auto vw_c) {
                 constexpr bool EX = decltype(ex_c)::value, ONE = decltype(one_c)::value;
-                if (s.list_k % 4 == 0)
-                    launch(drop_fused_kernel<EX, ONE, 4>);
-                else if (s.list_k % 2 == 0)
-                    launch(drop_fused_kernel<EX, ONE, 2>);
+                constexpr int VW = decltype(vw_c)::value;
+                if (small)
+                    launch(drop_fused_kernel<EX, ONE, VW, kSmallBlock>, kSmallBlock);
                 else
-                    launch(drop_fused_kernel<EX, ONE, 1>);
+                    launch(drop_fused_kernel<EX, ONE, VW, kFusedThreads>, kFusedThreads);
+            };
+            auto by_width = [&](auto ex_c, auto one_c) {
+                if (s.list_k % 4 == 0)
+                    by_size(ex_c, one_c, std::integral_constant<int, 4>{});
+                else if (s.list_k % 2 == 0)
+                    by_size(ex_c, one_c, std::integral_constant<int, 2>{});
+                else
+                    by_size(ex_c, one_c, std::integral_constant<int, 1>{});
             };
             if (ex && one)
                 by_width(std::true_type{}, std::true_type{});
