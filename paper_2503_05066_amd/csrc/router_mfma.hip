@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void router_mfma_kernel(const uint16_t* __rest
     // Register ring of D slabs: the fp32 weights and the token fragments of slab s + D are requested
     // while slab s is multiplied, so that a block keeps D slabs of loads in flight (the kernel is
     // bound by load latency: a slab is only 6 * TN MFMAs of work per wave).
-    constexpr int D = TN <= 2 ? 4 : (TN <= 4 ? 2 : 1);
+    constexpr int D = TN <= 4 ? 4 : 2;
     float4 wreg[D][NP][2];
     bf16x8 xreg[D][2];
 
