@@ -88,6 +88,33 @@ def test_router_logits(orc, name, n):
     assert np.abs(buf.logits.cpu().numpy() - ref0).max() <= 1e-4 * np.abs(ref0).max()
 
 
+@pytest.mark.parametrize("n,d,e", [
+    (300, 96, 100),     # three k-slabs in all: the shallowest request ring; two expert chunks, the second ragged
+    (257, 192, 200),    # seven expert tiles in chunks of 4 + 3
+    (129, 256, 250),    # E not a multiple of 4: scalar stores
+    (1000, 512, 160),   # five expert tiles in chunks of 3 + 2
+    (64, 128, 3),
+    (5000, 64, 33),
+    (40000, 64, 8),     # enough token tiles for a single K slice: the bias is added in the kernel
+    (33000, 128, 128),  # the same with two expert chunks
+])
+def test_router_logits_shapes(orc, n, d, e):
+    w = synth.scaled(W["olmoe"], n_tokens=n, d_model=d, n_experts=e, top_k=min(8, e), d_hidden=128, device_groups=1)
+    note("router logits, odd shapes", w)
+    x = synth.tokens(w)
+    wr, b = synth.router_weight(w), synth.router_bias(w)
+    ref = orc.router_logits(x.f32, wr, b)
+    desc = capmoe.make_desc(n, d, e, w.top_k, w.d_hidden, 1, TD, LOCAL, 1.0, w.dtype)
+    buf = capmoe.LayerBuffers(desc)
+    from gpu_util import to_device
+    capmoe.moe_route_topk(desc, to_device(x), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(), 0, buf.logits,
+                          buf.scores, buf.topk_idx, buf.topk_score, buf.workspace)
+    torch.cuda.synchronize()
+    got = buf.logits.cpu().numpy()
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() <= 1e-4 * np.abs(ref).max()
+
+
 # ------------------------------------------------------------------------------------------------
 # scores, top-k and the dispatch plan, bit-exact from identical logits
 # ------------------------------------------------------------------------------------------------
