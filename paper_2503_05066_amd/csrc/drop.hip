@@ -112,19 +112,25 @@ __global__ __launch_bounds__(256) void drop_prepare_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// block-wide helpers (256 threads)
+// block-wide helpers (NT threads, a multiple of the wave width)
 // ---------------------------------------------------------------------------------------------
-__device__ inline int block_sum_256(int v, int* red) {
+template <int NT>
+__device__ inline int block_sum(int v, int* red) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < NT / kWave; ++w) total += red[w];
+    return total;
 }
+__device__ inline int block_sum_256(int v, int* red) { return block_sum<256>(v, red); }
 
 // exclusive prefix sum of v over the block's threads; *total gets the block sum
-__device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
+template <int NT>
+__device__ inline int block_exclusive_scan(int v, int* red, int* total) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     int incl = v;
 #pragma unroll
@@ -135,10 +141,17 @@ __device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
     __syncthreads();
     if (lane == 63) red[wv] = incl;
     __syncthreads();
-    int before = 0;
-    for (int w = 0; w < wv; ++w) before += red[w];
-    *total = red[0] + red[1] + red[2] + red[3];
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < NT / kWave; ++w) {
+        if (w < wv) before += red[w];
+        all += red[w];
+    }
+    *total = all;
     return before + incl - v;
+}
+__device__ inline int block_exclusive_scan_256(int v, int* red, int* total) {
+    return block_exclusive_scan<256>(v, red, total);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -151,15 +164,19 @@ constexpr int kSelectCache = 32768;  // keys of a segment kept in LDS (up to 128
 // Outputs, per (block, expert): the threshold, how many keys equal to it survive, the kept count.
 // Several experts under one budget share the threshold; the keys equal to it are granted to the
 // lower tokens first and, inside a token, to the lower expert ids.
-__global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __restrict__ key_t,
+// NT threads: 256 for short segments, 1024 for long ones (a segment is one block's work, and its
+// passes over the keys are chains of load latencies that only more loads in flight shorten).
+// VEC keys per load: 4 when every run starts on a 16-byte boundary (N and seg_tokens multiples of 4).
+template <int NT, int VEC>
+__global__ __launch_bounds__(NT) void drop_select_kernel(const uint32_t* __restrict__ key_t,
                                                           uint32_t* __restrict__ seg_tau,
                                                           int32_t* __restrict__ seg_need,
                                                           int32_t* __restrict__ seg_count, int N, int E, int seg_tokens,
                                                           int span, int cap) {
-    extern __shared__ uint32_t cache[];
+    extern __shared__ __attribute__((aligned(16))) uint32_t cache[];
     __shared__ int hist[256];
     __shared__ int gt_s[kMaxExperts], eq_s[kMaxExperts];
-    __shared__ int red[4];
+    __shared__ int red[NT / kWave];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_rem;
     const int groups = E / span;
@@ -169,30 +186,53 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
     const int n_keys = span * seg_tokens;
     const bool cached = n_keys <= kSelectCache;
 
+    // Every pass walks all keys of the segment, key i = run i / seg_tokens, token i % seg_tokens: a thread
+    // requests kBatch loads of VEC keys before it uses any, then calls f(run, token, key) key by key (in
+    // ascending i per thread).
+    constexpr int kBatch = NT > 256 ? 16 : 8;
+    struct alignas(4 * VEC) KeyVec {
+        uint32_t c[VEC];
+    };
+    auto for_each_key = [&](bool from_cache, auto&& f) {
+        for (int i0 = tid * VEC; i0 < n_keys; i0 += NT * VEC * kBatch) {
+            KeyVec kx[kBatch];
+            int run[kBatch], tok[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + NT * VEC * u;  // VEC divides seg_tokens: the keys of a load share a run
+                run[u] = span == 1 ? 0 : i / seg_tokens;  // (a division is as much work as four keys)
+                tok[u] = i - run[u] * seg_tokens;
+                if (i >= n_keys) {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) kx[u].c[c] = 0u;
+                } else if (from_cache) {
+                    kx[u] = *(const KeyVec*)(cache + i);
+                } else {
+                    kx[u] = *(const KeyVec*)(keys + (size_t)run[u] * N + tok[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                if (i0 + NT * VEC * u < n_keys) {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) f(run[u], tok[u] + c, kx[u].c[c]);
+                }
+        }
+    };
+
     // load the keys; the histogram of their top byte (the first radix pass) is taken on the way
-    hist[tid] = 0;
-    for (int r = tid; r < span; r += 256) gt_s[r] = eq_s[r] = 0;
+    if (tid < 256) hist[tid] = 0;
+    for (int r = tid; r < span; r += NT) gt_s[r] = eq_s[r] = 0;
     __syncthreads();
     int mine = 0;
-    for (int i0 = tid; i0 < n_keys; i0 += 256 * 8) {
-        uint32_t kx[8];  // eight independent loads in flight before anything waits
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = i0 + 256 * u;
-            const int r = i / seg_tokens;
-            kx[u] = i < n_keys ? keys[(size_t)r * N + (i - r * seg_tokens)] : 0u;
+    for_each_key(false, [&](int r, int tl, uint32_t key) {
+        if (cached) cache[r * seg_tokens + tl] = key;
+        if (key != 0u) {  // non-candidates (key 0) never matter
+            ++mine;
+            atomicAdd(&hist[key >> 24], 1);
         }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = i0 + 256 * u;
-            if (cached && i < n_keys) cache[i] = kx[u];
-            if (kx[u] != 0u) {
-                ++mine;
-                atomicAdd(&hist[kx[u] >> 24], 1);
-            }
-        }
-    }
-    const int n_cand = block_sum_256(mine, red);  // its barriers also order the LDS writes before the reads
+    });
+    const int n_cand = block_sum<NT>(mine, red);  // its barriers also order the LDS writes before the reads
 
     // threshold: keys above tau are kept, `rem` of the keys equal to tau are kept
     uint32_t tau = 0;  // every candidate (key >= 1) passes
@@ -205,37 +245,22 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         rem = cap;
         for (int shift = 24; shift >= 0; shift -= 8) {
             if (shift != 24) {
-                hist[tid] = 0;
+                if (tid < 256) hist[tid] = 0;
                 __syncthreads();
                 const uint32_t hi_mask = 0xffffffffu << (shift + 8);
-                for (int i0 = tid; i0 < n_keys; i0 += 256 * 8) {
-                    uint32_t kx[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        const int i = i0 + 256 * u;
-                        if (i >= n_keys) {
-                            kx[u] = 0u;
-                        } else if (cached) {
-                            kx[u] = cache[i];
-                        } else {
-                            const int r = i / seg_tokens;
-                            kx[u] = keys[(size_t)r * N + (i - r * seg_tokens)];
-                        }
-                    }
-                    // non-candidates (key 0) never matter
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (kx[u] != 0u && (kx[u] & hi_mask) == prefix) atomicAdd(&hist[(kx[u] >> shift) & 255u], 1);
-                }
+                auto count_digit = [&](int, int, uint32_t key) {
+                    if (key != 0u && (key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+                };
+                for_each_key(cached, count_digit);
                 __syncthreads();
             }
-            // thread i owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
+            // thread i < 256 owns digit 255 - i: an exclusive scan over threads counts the keys with a larger
             // digit; the digit where that count first reaches `rem` holds the cap-th key
             const int mine_d = 255 - tid;
-            const int h = hist[mine_d];
+            const int h = tid < 256 ? hist[mine_d] : 0;
             int total;
-            const int above = block_exclusive_scan_256(h, red, &total);
-            if (above + h >= rem && above < rem) {  // exactly one thread
+            const int above = block_exclusive_scan<NT>(h, red, &total);
+            if (tid < 256 && above + h >= rem && above < rem) {  // exactly one thread
                 sh_prefix = prefix | ((uint32_t)mine_d << shift);
                 sh_rem = rem - above;
             }
@@ -257,18 +282,16 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
     // per expert: keys above the threshold and keys equal to it (a thread's keys change run rarely)
     auto count_runs = [&](int tie_token, int tie_run) {
         int run = -1, gt = 0, eq = 0;
-        for (int i = tid; i < n_keys; i += 256) {
-            const int r = i / seg_tokens, tl = i - r * seg_tokens;
-            const uint32_t kx = cached ? cache[i] : keys[(size_t)r * N + tl];
+        for_each_key(cached, [&](int r, int tl, uint32_t key) {
             if (r != run) {
                 if (gt) atomicAdd(&gt_s[run], gt);
                 if (eq) atomicAdd(&eq_s[run], eq);
                 run = r;
                 gt = eq = 0;
             }
-            gt += kx > tau;
-            eq += kx == tau && kx != 0u && (tl < tie_token || (tl == tie_token && r <= tie_run));
-        }
+            gt += key > tau;
+            eq += key == tau && key != 0u && (tl < tie_token || (tl == tie_token && r <= tie_run));
+        });
         if (gt) atomicAdd(&gt_s[run], gt);
         if (eq) atomicAdd(&eq_s[run], eq);
     };
@@ -281,7 +304,7 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         // (token, expert) order.  A thread owns a run of consecutive tokens; the thread in whose
         // run the budget ends finds the last granted pair (token tie_token, expert run tie_run).
         __shared__ int sh_tie_token, sh_tie_run;
-        const int per = (seg_tokens + 255) / 256;
+        const int per = (seg_tokens + NT - 1) / NT;
         const int tb = tid * per < seg_tokens ? tid * per : seg_tokens;
         const int te = tb + per < seg_tokens ? tb + per : seg_tokens;
         auto key_at = [&](int r, int tl) { return cached ? cache[r * seg_tokens + tl] : keys[(size_t)r * N + tl]; };
@@ -289,7 +312,7 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         for (int tl = tb; tl < te; ++tl)
             for (int r = 0; r < span; ++r) c += key_at(r, tl) == tau;
         int total;
-        const int before = block_exclusive_scan_256(c, red, &total);
+        const int before = block_exclusive_scan<NT>(c, red, &total);
         if (before < rem && rem <= before + c) {  // exactly one thread: 1 <= rem < eq_total = total
             int left = rem - before;
             for (int tl = tb; tl < te && left > 0; ++tl)
@@ -301,7 +324,7 @@ __global__ __launch_bounds__(256) void drop_select_kernel(const uint32_t* __rest
         }
         __syncthreads();
         const int tie_token = sh_tie_token, tie_run = sh_tie_run;
-        for (int r = tid; r < span; r += 256) gt_s[r] = eq_s[r] = 0;
+        for (int r = tid; r < span; r += NT) gt_s[r] = eq_s[r] = 0;
         __syncthreads();
         count_runs(tie_token, tie_run);
         __syncthreads();
@@ -336,19 +359,20 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
     __shared__ uint32_t key_s[kEmitChunk + 256];
     __shared__ uint8_t slot_s[kEmitChunk];
     __shared__ int red[4];
-    const int seg = blockIdx.x;
+    // a block owns one chunk of kEmitChunk tokens of one segment; what the chunks before it keep it counts itself
+    const int parts = seg_tokens > kEmitChunk ? (seg_tokens + kEmitChunk - 1) / kEmitChunk : 1;
+    const int seg = blockIdx.x / parts;
+    const int c0 = (blockIdx.x - seg * parts) * kEmitChunk;
     const int b = seg / E, e = seg - b * E;
     const int tid = threadIdx.x;
 
     const uint32_t* keys = key_t + (size_t)e * N + (size_t)b * seg_tokens;
     const uint8_t* slots = slot_t + (size_t)e * N + (size_t)b * seg_tokens;
-    // first chunk of keys and slots: issued before anything waits
-    {
-        const int n = seg_tokens < kEmitChunk ? seg_tokens : kEmitChunk;
-        for (int i = tid; i < n; i += 256) {
-            key_s[i + i / kEmitRun] = keys[i];
-            slot_s[i] = slots[i];
-        }
+    // this chunk's keys and slots: issued before anything waits
+    const int n = seg_tokens - c0 < kEmitChunk ? seg_tokens - c0 : kEmitChunk;
+    for (int i = tid; i < n; i += 256) {
+        key_s[i + i / kEmitRun] = keys[c0 + i];
+        slot_s[i] = slots[c0 + i];
     }
     // first row of this segment: all segments of lower experts, then lower blocks of this expert
     int before = 0, own = 0;
@@ -360,7 +384,7 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
     }
     const int row0 = block_sum_256(before, red);
     const int own_total = block_sum_256(own, red);
-    if (b == 0 && tid == 0) {
+    if (b == 0 && c0 == 0 && tid == 0) {
         expert_count[e] = own_total;
         expert_offset[e] = row0;
         if (e == E - 1) expert_offset[E] = row0 + own_total;
@@ -368,55 +392,76 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
     const uint32_t tau = seg_tau[seg];
     const int need = seg_need[seg];
 
-    int kept_base = 0, eq_base = 0;  // counts over the chunks already done
-    for (int c0 = 0; c0 < seg_tokens; c0 += kEmitChunk) {
-        const int n = seg_tokens - c0 < kEmitChunk ? seg_tokens - c0 : kEmitChunk;
-        if (c0 > 0) {
-            __syncthreads();
-            for (int i = tid; i < n; i += 256) {
-                key_s[i + i / kEmitRun] = keys[c0 + i];
-                slot_s[i] = slots[c0 + i];
+    // the segment's tokens before this chunk: keys above the threshold, and keys equal to it (the first
+    // `need` of those, in token order, are kept)
+    int kept_base = 0, eq_base = 0;
+    if (c0 > 0) {
+        int gt = 0, eq = 0;
+        if (((N | seg_tokens) & 3) == 0) {  // every run starts on a 16-byte boundary
+            const uint4* k4 = (const uint4*)keys;
+            for (int i0 = tid; i0 < c0 / 4; i0 += 256 * 8) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = i0 + 256 * u < c0 / 4 ? k4[i0 + 256 * u] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    gt += (v[u].x > tau) + (v[u].y > tau) + (v[u].z > tau) + (v[u].w > tau);
+                    eq += (v[u].x == tau) + (v[u].y == tau) + (v[u].z == tau) + (v[u].w == tau);
+                }
+            }
+        } else {
+            for (int i0 = tid; i0 < c0; i0 += 256 * 8) {
+                uint32_t v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = i0 + 256 * u < c0 ? keys[i0 + 256 * u] : 0u;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    gt += v[u] > tau;
+                    eq += v[u] == tau;
+                }
             }
         }
-        __syncthreads();
-        uint32_t kx[kEmitRun];
-        int eq_cnt = 0;
+        if (tau == 0u) eq = 0;  // key 0 is "not a candidate", never an equal key
+        const int gt_total = block_sum_256(gt, red);
+        eq_base = block_sum_256(eq, red);
+        kept_base = gt_total + (eq_base < need ? eq_base : need);
+    }
+    __syncthreads();
+    uint32_t kx[kEmitRun];
+    int eq_cnt = 0;
 #pragma unroll
-        for (int j = 0; j < kEmitRun; ++j) {
-            const int i = tid * kEmitRun + j;
-            kx[j] = i < n ? key_s[tid * (kEmitRun + 1) + j] : 0u;
-            eq_cnt += kx[j] != 0u && kx[j] == tau;
-        }
-        int eq_total, keep_total;
-        int eq_rank = eq_base + block_exclusive_scan_256(eq_cnt, red, &eq_total);
-        uint32_t keep_bits = 0;
-        int keep_cnt = 0;
+    for (int j = 0; j < kEmitRun; ++j) {
+        const int i = tid * kEmitRun + j;
+        kx[j] = i < n ? key_s[tid * (kEmitRun + 1) + j] : 0u;
+        eq_cnt += kx[j] != 0u && kx[j] == tau;
+    }
+    int eq_total, keep_total;
+    int eq_rank = eq_base + block_exclusive_scan_256(eq_cnt, red, &eq_total);
+    uint32_t keep_bits = 0;
+    int keep_cnt = 0;
 #pragma unroll
-        for (int j = 0; j < kEmitRun; ++j) {
-            const bool cand = kx[j] != 0u;
-            const bool eq = cand && kx[j] == tau;
-            const bool keep = cand && (kx[j] > tau || (eq && eq_rank < need));
-            eq_rank += eq;
-            keep_cnt += keep;
-            keep_bits |= (uint32_t)keep << j;
-        }
-        int pos = row0 + kept_base + block_exclusive_scan_256(keep_cnt, red, &keep_total);
+    for (int j = 0; j < kEmitRun; ++j) {
+        const bool cand = kx[j] != 0u;
+        const bool eq = cand && kx[j] == tau;
+        const bool keep = cand && (kx[j] > tau || (eq && eq_rank < need));
+        eq_rank += eq;
+        keep_cnt += keep;
+        keep_bits |= (uint32_t)keep << j;
+    }
+    int pos = row0 + kept_base + block_exclusive_scan_256(keep_cnt, red, &keep_total);
 #pragma unroll
-        for (int j = 0; j < kEmitRun; ++j) {
-            if (kx[j] == 0u) continue;
-            const int i = tid * kEmitRun + j;
-            const int t = b * seg_tokens + c0 + i;
-            const bool keep = (keep_bits >> j) & 1u;
-            if (keep) {
-                row_token[pos] = t;
-                // the gating score, whatever ranked the pair (under the Score metric it is the key itself)
-                row_weight[pos] = weight_from_key ? __uint_as_float(kx[j] - 1u) : scores[(size_t)t * E + e];
-            }
-            pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
-            pos += keep;
+    for (int j = 0; j < kEmitRun; ++j) {
+        if (kx[j] == 0u) continue;
+        const int i = tid * kEmitRun + j;
+        const int t = b * seg_tokens + c0 + i;
+        const bool keep = (keep_bits >> j) & 1u;
+        if (keep) {
+            row_token[pos] = t;
+            // the gating score, whatever ranked the pair (under the Score metric it is the key itself)
+            row_weight[pos] = weight_from_key ? __uint_as_float(kx[j] - 1u) : scores[(size_t)t * E + e];
         }
-        kept_base += keep_total;
-        eq_base += eq_total;
+        pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
+        pos += keep;
     }
 }
 
@@ -911,16 +956,22 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         const size_t lds = (n_keys <= (size_t)kSelectCache ? n_keys : 0) * 4;
         static bool configured = false;
         if (!configured) {  // up to 128 KB of keys plus the kernel's own few kilobytes
-            (void)hipFuncSetAttribute((const void*)drop_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kSelectCache * 4);
+            for (const void* k : {(const void*)drop_select_kernel<256, 1>, (const void*)drop_select_kernel<256, 4>,
+                                  (const void*)drop_select_kernel<1024, 1>, (const void*)drop_select_kernel<1024, 4>})
+                (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kSelectCache * 4);
             configured = true;
         }
-        hipLaunchKernelGGL(drop_select_kernel, dim3(segs / s.span), dim3(256), lds, st, ws.key_t, ws.seg_tau,
+        const bool wide = n_keys > 4096;                          // threads per block
+        const bool vec = N % 4 == 0 && s.seg_tokens % 4 == 0;     // 16-byte loads of four keys
+        auto kern = wide ? (vec ? drop_select_kernel<1024, 4> : drop_select_kernel<1024, 1>)
+                         : (vec ? drop_select_kernel<256, 4> : drop_select_kernel<256, 1>);
+        hipLaunchKernelGGL(kern, dim3(segs / s.span), dim3(wide ? 1024 : 256), lds, st, ws.key_t, ws.seg_tau,
                            ws.seg_need, seg_count, N, E, s.seg_tokens, s.span, s.cap);
     }
     auto emit = [&]() {
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
-        hipLaunchKernelGGL(drop_emit_kernel, dim3(segs), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
+        const int parts = s.seg_tokens > kEmitChunk ? (s.seg_tokens + kEmitChunk - 1) / kEmitChunk : 1;
+        hipLaunchKernelGGL(drop_emit_kernel, dim3(segs * parts), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
                            ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
                            s.n_blocks, s.seg_tokens, s.slots, d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
     };

@@ -170,6 +170,26 @@ def test_plan_edge_shapes(orc, n, e, k, g, mode, scope, gamma):
     check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, "edge shape")
 
 
+# Segments longer than what a block keeps in LDS (32768 keys): the selection re-reads its keys (or keeps the
+# candidates only) and the compaction of a segment is spread over one block per 4096 tokens.
+@pytest.mark.parametrize("n,e,k,g,mode,scope,gamma,flat", [
+    (70001, 8, 2, 1, TD, GLOBAL, 1.0, False),     # token count not a multiple of 4: scalar key loads
+    (65536, 4, 1, 1, TD, GLOBAL, 0.7, False),     # 16-byte key loads
+    (65536, 4, 2, 1, TD, GLOBAL, 0.5, True),      # every score equal: the threshold is a tie of 32768 keys
+    (49152, 16, 4, 4, ED, GLOBAL, 1.0, False),
+    (40000, 16, 2, 4, TD, 3, 1.0, False),         # device budgets over 4 x 40000 keys
+    (40000, 16, 2, 4, ED, 3, 0.6, True),
+    (36864, 6, 6, 1, TD, GLOBAL, 0.5, False),     # every expert is a candidate of every token: more candidates than LDS holds
+])
+def test_plan_long_segments(orc, n, e, k, g, mode, scope, gamma, flat):
+    rng = np.random.default_rng(n + e)
+    if flat:
+        logits = np.zeros((n, e), np.float32)
+    else:
+        logits = (rng.standard_normal((n, e)) * 2 + rng.standard_normal(e)[None, :] * 1.5).astype(np.float32)
+    check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, "long segments")
+
+
 # 2048 tokens: the single-launch drop; 16384 tokens in one block of tokens: segments too long for it, so the
 # three-kernel chain runs with per-expert capacities as well
 @pytest.mark.parametrize("mode,scope,g,n", [(TD, GLOBAL, 1, 2048), (TD, LOCAL, 4, 2048), (ED, LOCAL, 4, 2048),
