@@ -468,91 +468,90 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
 // ---------------------------------------------------------------------------------------------
 // 4. at most k experts per token (optional; appendix "Maximum Number of Selected Experts")
 // ---------------------------------------------------------------------------------------------
-constexpr int kLimitTokens = 64;
+constexpr int kLimitTokens = 64;        // tokens of a block
+constexpr int kLimitPitch = kLimitTokens + 1;  // words per expert row of the block's key tile in LDS
 
-// Runs after a first emit.  A thread owns a token: it lists the token's surviving pairs, ranks them
-// by gating score (equal scores: lower expert id first) and removes those ranked k-th or worse.
-// Keys of every pair that does not survive (dropped by capacity, or removed here) become 0, the
-// per-segment counts are lowered, and thresholds are reset so that a second emit keeps exactly the
-// non-zero keys.
-__global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* __restrict__ scores,
-                                                                  uint32_t* __restrict__ key_t,
-                                                                  int32_t* __restrict__ pair_row,
-                                                                  uint32_t* __restrict__ seg_tau,
-                                                                  int32_t* __restrict__ seg_need,
-                                                                  int32_t* __restrict__ seg_count, int N, int E, int S,
-                                                                  int k, int seg_tokens, int segs) {
-    // per thread (token): [S] score bits, [S] expert | slot << 16 of the surviving pairs, [S] bytes "slot kept";
-    // entry i of lane l sits at i * 64 + l: no bank conflicts
-    extern __shared__ uint32_t lim[];
-    uint32_t* sc = lim;
-    uint32_t* es = lim + (size_t)S * kLimitTokens;
-    uint8_t* kept = (uint8_t*)(lim + (size_t)2 * S * kLimitTokens);
-    __shared__ int removed[kMaxExperts];  // pairs this block removes per expert (one global atomic each at the end)
-    const int lane = threadIdx.x;
-    const int gtid = blockIdx.x * kLimitTokens + lane;
-    for (int i = gtid; i < segs; i += gridDim.x * kLimitTokens) {
+// Runs after a first emit.  For every token: its surviving pairs are listed, ranked by gating score
+// (equal scores: lower expert id first), and those ranked k-th or worse are removed.  Keys of every pair
+// that does not survive (dropped by capacity, or removed here) become 0, the per-segment counts are
+// lowered, and thresholds are reset so that a second emit keeps exactly the non-zero keys.
+// A block moves the keys of 64 tokens and all experts through LDS (the key matrix is expert-major: rows of
+// consecutive tokens go in and out as whole cache lines); then a wave takes a token at a time, lanes
+// over experts: the c-th candidate in ascending expert id owns slot c of the token (ballot prefix counts).
+// EPL = experts per lane (E <= 64 * EPL).  Nothing in the per-token loop waits for global memory: the
+// tokens' slot rows are staged in LDS beside the keys and their score rows are requested up front.
+template <int EPL>
+__global__ __launch_bounds__(256) void drop_limit_kernel(const float* __restrict__ scores, uint32_t* __restrict__ key_t,
+                                                         int32_t* __restrict__ pair_row,
+                                                         uint32_t* __restrict__ seg_tau, int32_t* __restrict__ seg_need,
+                                                         int32_t* __restrict__ seg_count, int N, int E, int S, int k,
+                                                         int seg_tokens, int segs) {
+    extern __shared__ uint32_t tile[];            // [E][kLimitPitch] keys, then [kLimitTokens][S] rows of pair_row
+    __shared__ uint2 survivors[4][256];           // per wave: (score bits, expert | slot << 16), ascending expert
+    __shared__ int removed[kMaxExperts];          // pairs this block removes per expert (one global atomic each at the end)
+    int32_t* rows = (int32_t*)(tile + (size_t)E * kLimitPitch);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    constexpr int kPerWave = kLimitTokens / 4;    // tokens of a wave: wv, wv + 4, ...
+    const int t_first = blockIdx.x * kLimitTokens;
+    const int t_last = t_first + kLimitTokens - 1 < N ? t_first + kLimitTokens - 1 : N - 1;
+    float sc[kPerWave][EPL];
+#pragma unroll
+    for (int q = 0; q < kPerWave; ++q)
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            const int t = t_first + wv + 4 * q, e = lane + kWave * i;
+            sc[q][i] = t < N && e < E ? scores[(size_t)t * E + e] : 0.0f;
+        }
+    for (int i = blockIdx.x * 256 + tid; i < segs; i += gridDim.x * 256) {
         seg_tau[i] = 0u;
         seg_need[i] = 0;
     }
-    for (int e = lane; e < E; e += kLimitTokens) removed[e] = 0;
-    __syncthreads();
-    const int t = gtid;
+    for (int e = tid; e < E; e += 256) removed[e] = 0;
     // the block's tokens lie in one capacity block when its first and last do
-    const int t_first = blockIdx.x * kLimitTokens;
-    const int t_last = t_first + kLimitTokens - 1 < N ? t_first + kLimitTokens - 1 : N - 1;
     const bool one_block = t_first / seg_tokens == t_last / seg_tokens;
-    if (t < N) {
-        // which candidate slots survived the capacity (loads in batches of independent ones: a chain of
-        // dependent loads costs about a microsecond per link)
-        for (int s0 = 0; s0 < S; s0 += 8) {
-            int32_t pr[8];
+    for (int i = tid; i < E * kLimitTokens; i += 256) {
+        const int e = i / kLimitTokens, tl = i - e * kLimitTokens;
+        tile[e * kLimitPitch + tl] = t_first + tl < N ? key_t[(size_t)e * N + t_first + tl] : 0u;
+    }
+    const int n_rows = (t_last - t_first + 1) * S;  // the block's rows of pair_row are consecutive in memory
+    for (int i = tid; i < n_rows; i += 256) rows[i] = pair_row[(size_t)t_first * S + i];
+    __syncthreads();
+    const uint64_t below = (1ull << lane) - 1ull;
+    uint2* list = &survivors[wv][0];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) pr[u] = s0 + u < S ? pair_row[(size_t)t * S + s0 + u] : -1;
+    for (int q = 0; q < kPerWave; ++q) {
+        const int tl = wv + 4 * q, t = t_first + tl;
+        if (t >= N) break;  // wave-uniform
+        int slot_base = 0, n = 0;
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < S) kept[(s0 + u) * kLimitTokens + lane] = pr[u] >= 0;
+        for (int i = 0; i < EPL; ++i) {
+            const int e = lane + kWave * i;
+            const uint32_t key = e < E ? tile[e * kLimitPitch + tl] : 0u;
+            const bool cand = key != 0u;
+            const uint64_t cand_mask = __ballot(cand);
+            const int slot = slot_base + __popcll(cand_mask & below);
+            slot_base += __popcll(cand_mask);
+            const bool kept = cand && rows[tl * S + slot] >= 0;  // survived the capacity
+            if (cand && !kept) tile[e * kLimitPitch + tl] = 0u;
+            const uint64_t kept_mask = __ballot(kept);
+            if (kept)
+                list[n + __popcll(kept_mask & below)] =
+                    make_uint2(__float_as_uint(sc[q][i]), (uint32_t)e | ((uint32_t)slot << 16));
+            n += __popcll(kept_mask);
         }
-        // walk the experts in ascending id: the c-th candidate of the token owns slot c
-        int n = 0, slot = 0;
-        for (int e0 = 0; e0 < E; e0 += 32) {
-            uint32_t kx[32];
-#pragma unroll
-            for (int u = 0; u < 32; ++u) kx[u] = e0 + u < E ? key_t[(size_t)(e0 + u) * N + t] : 0u;
-#pragma unroll
-            for (int u = 0; u < 32; ++u) {
-                if (kx[u] == 0u) continue;
-                if (kept[slot * kLimitTokens + lane]) {
-                    es[n * kLimitTokens + lane] = (uint32_t)(e0 + u) | ((uint32_t)slot << 16);
-                    ++n;
-                } else {
-                    key_t[(size_t)(e0 + u) * N + t] = 0u;  // dropped by the capacity
-                }
-                ++slot;
-            }
-        }
+        __builtin_amdgcn_wave_barrier();  // LDS operations of one wave complete in order
         if (n > k) {
-            for (int i0 = 0; i0 < n; i0 += 8) {
-                float v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v[u] = i0 + u < n ? scores[(size_t)t * E + (es[(i0 + u) * kLimitTokens + lane] & 0xffffu)] : 0.0f;
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (i0 + u < n) sc[(i0 + u) * kLimitTokens + lane] = __float_as_uint(v[u]);
-            }
             const int b = t / seg_tokens;
-            for (int i = 0; i < n; ++i) {
-                const uint32_t si = sc[i * kLimitTokens + lane];
-                int better = 0;  // survivors ahead of pair i: higher score, or equal score and lower expert id
-                for (int j = 0; j < n; ++j) {
-                    const uint32_t sj = sc[j * kLimitTokens + lane];
-                    better += sj > si || (sj == si && j < i);
+            for (int j = lane; j < n; j += kWave) {
+                const uint2 mine = list[j];
+                int better = 0;  // survivors ahead of pair j: higher score, or equal score and lower expert id
+                for (int i = 0; i < n; ++i) {
+                    const uint32_t si = list[i].x;  // same address in every lane
+                    better += si > mine.x || (si == mine.x && i < j);
                 }
                 if (better >= k) {
-                    const uint32_t v = es[i * kLimitTokens + lane];
-                    const int e = (int)(v & 0xffffu), sl = (int)(v >> 16);
-                    key_t[(size_t)e * N + t] = 0u;
+                    const int e = (int)(mine.y & 0xffffu), sl = (int)(mine.y >> 16);
+                    tile[e * kLimitPitch + tl] = 0u;
                     pair_row[(size_t)t * S + sl] = -1;
                     if (one_block)
                         atomicAdd(&removed[e], 1);
@@ -561,10 +560,15 @@ __global__ __launch_bounds__(kLimitTokens) void drop_limit_kernel(const float* _
                 }
             }
         }
+        __builtin_amdgcn_wave_barrier();  // the list is rewritten for the wave's next token only after these reads
     }
     __syncthreads();
+    for (int i = tid; i < E * kLimitTokens; i += 256) {
+        const int e = i / kLimitTokens, tl = i - e * kLimitTokens;
+        if (t_first + tl < N) key_t[(size_t)e * N + t_first + tl] = tile[e * kLimitPitch + tl];
+    }
     if (one_block)
-        for (int e = lane; e < E; e += kLimitTokens)
+        for (int e = tid; e < E; e += 256)
             if (removed[e]) atomicSub(&seg_count[(t_first / seg_tokens) * E + e], removed[e]);
 }
 
@@ -978,15 +982,15 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
     emit();
     if (d.max_experts && s.slots > d.top_k && N > 0) {
         // the first plan tells which pairs survive the capacity; trim every token to k of them, emit again
-        const size_t lds = (size_t)s.slots * kLimitTokens * 9;  // two words and a byte per slot and token
-        if (lds > 64 * 1024)
-            (void)hipFuncSetAttribute((const void*)drop_limit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)lds);
+        // the key tile of 64 tokens and their rows of pair_row: at most 256 * 65 + 64 * 255 words
+        const size_t lds = ((size_t)E * kLimitPitch + (size_t)kLimitTokens * s.slots) * 4;
+        auto kern = E <= 64 ? drop_limit_kernel<1> : (E <= 128 ? drop_limit_kernel<2> : drop_limit_kernel<4>);
+        if (lds > 48 * 1024)
+            (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         {
             ProfileScope prof(MOE_KERNEL_DROP_LIMIT, st);
-            hipLaunchKernelGGL(drop_limit_kernel, dim3((N + kLimitTokens - 1) / kLimitTokens), dim3(kLimitTokens), lds,
-                               st, scores, ws.key_t, pair_row, ws.seg_tau, ws.seg_need, seg_count, N, E, s.slots,
-                               d.top_k, s.seg_tokens, segs);
+            hipLaunchKernelGGL(kern, dim3((N + kLimitTokens - 1) / kLimitTokens), dim3(256), lds, st, scores, ws.key_t,
+                               pair_row, ws.seg_tau, ws.seg_need, seg_count, N, E, s.slots, d.top_k, s.seg_tokens, segs);
         }
         emit();
     }
