@@ -9,8 +9,9 @@
 //                     Order) or a hashed draw (Random), below an optional 2-bit token class.
 //   2. drop_select    per segment: the cap-th largest key by a 4-pass radix select over LDS
 //                     histograms (the threshold tau of Eq. 8) and how many keys equal to it survive.
-//   3. drop_emit      per segment: ordered compaction of the survivors, which yields rows in
-//                     ascending token order and gives ties at the threshold to the lower token index.
+//   3. drop_emit      per segment (a block per 4096 tokens of it): ordered compaction of the survivors,
+//                     which yields rows in ascending token order and gives ties at the threshold to
+//                     the lower token index.
 // Every kernel first pulls what it needs from global memory in one batch of independent loads
 // (these kernels are latency-bound: a dependent load per loop iteration costs a microsecond each).
 // Small problems with per-expert capacities run all three steps in one launch (drop_fused, below),
