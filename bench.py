@@ -36,8 +36,8 @@ METRICS = {"score": 0, "order": 1, "reverse_order": 2, "random": 3}
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
-    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--workload", default="olmoe", help="tiny | olmoe | mixtral | finegrained | decode")
     p.add_argument("--mode", default="token", choices=list(MODES))
     p.add_argument("--scope", default="local", choices=list(SCOPES))
