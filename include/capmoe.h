@@ -18,6 +18,9 @@
  *     launch; on a non-zero status nothing was enqueued.  MOE_ERR_HIP reports a failed launch.
  *   - `workspace` is scratch device memory of at least the size moe_query reports, 256-byte
  *     aligned, reusable between calls (its content has no meaning after a call completes).
+ *   - One host thread at a time, one device per process: the library keeps what it learns on its
+ *     first calls (kernel attributes it has set, the compute-unit count) for the device that was
+ *     current then, without locks.
  *
  * Simulated expert parallelism: with G = device_groups, token t lives on device t / (N/G) and
  * device b hosts experts [b*E/G, (b+1)*E/G) (data parallel = expert parallel, as in the paper's
