@@ -94,6 +94,7 @@ def test_router_logits(orc, name, n):
     (129, 256, 250),    # E not a multiple of 4: scalar stores
     (1000, 512, 160),   # five expert tiles in chunks of 3 + 2
     (64, 128, 3),
+    (17, 64, 1),        # a single expert
     (5000, 64, 33),
     (40000, 64, 8),     # enough token tiles for a single K slice: the bias is added in the kernel
     (33000, 128, 128),  # the same with two expert chunks
