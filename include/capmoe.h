@@ -41,7 +41,9 @@ typedef enum {
     MOE_ERR_INVALID_ARG = 1,         /* null pointer, size out of range, N or E not a multiple of G   */
     MOE_ERR_UNSUPPORTED = 2,         /* valid but not implemented (shape granularity, dtype)          */
     MOE_ERR_WORKSPACE_TOO_SMALL = 3, /* workspace_bytes below what moe_query reports                  */
-    MOE_ERR_HIP = 4                  /* the HIP runtime refused a launch                              */
+    MOE_ERR_HIP = 4,                 /* the HIP runtime refused a launch                              */
+    MOE_ERR_SCRATCH_LIMIT = 5        /* moe_route_topk_static: the problem needs more scratch memory
+                                        than the library's built-in buffer holds                      */
 } moe_status_t;
 
 enum { MOE_MODE_NONE = 0, MOE_MODE_TOKEN_DROP = 1, MOE_MODE_EXPANDED_DROP = 2 };
@@ -118,6 +120,27 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
 int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
                    int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * moe_route_topk for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the workspace, same
+ * results bit for bit.  The split-K partial sums of the router GEMM go to a buffer built into the library
+ * (16 MiB of device memory per GPU, held from the moment the library is loaded there until the process
+ * ends); the call allocates and frees nothing.
+ *   - A descriptor whose router needs more than 16 MiB of partial sums (moe_query reports more for the
+ *     routing step) is refused with MOE_ERR_SCRATCH_LIMIT before anything is enqueued.  All five
+ *     workloads of the benchmark fit (at most 8 MiB).
+ *   - The buffer belongs to the device that is current at the call.  Every call on a GPU shares that
+ *     GPU's buffer: two calls that overlap on one GPU (different streams, different threads) race; calls
+ *     on one stream are safe, and nothing in the buffer needs clearing between calls (every partial sum
+ *     that is read was written by the same call).
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress), which is when the HIP
+ *     runtime places the buffer in that device's memory; make that one call outside a graph capture.  No
+ *     later call changes the amount of free device memory.
+ */
+int moe_route_topk_static(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                          int use_given_logits, float* logits, float* scores, int32_t* topk_idx,
+                          float* topk_score, void* stream);
 
 /*
  * Capacity enforcement: Token Drop (Eqs. 8-10, Alg. 1) or Expanded Drop (Alg. 2), or none.

@@ -56,6 +56,7 @@ def load():
         lib.moe_query.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32),
                                   ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
         lib.moe_route_topk.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_route_topk_static.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
         lib.moe_capacity_drop.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_capacity_drop_ranked.argtypes = [dp, vp, vp, vp, ctypes.c_uint32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch.argtypes = [dp, vp, vp, vp, vp, vp]
@@ -68,7 +69,7 @@ def load():
         lib.moe_profile_attach.restype = i32
         lib.moe_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
         lib.moe_probe_mfma_bf16.restype = i32
-        for f in ("moe_query", "moe_route_topk", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
+        for f in ("moe_query", "moe_route_topk", "moe_route_topk_static", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
                   "moe_grouped_ffn",
                   "moe_dispatch_ffn", "moe_combine"):
             getattr(lib, f).restype = i32
@@ -119,6 +120,12 @@ def moe_route_topk(desc, x, w_router, bias, use_given_logits, logits, scores, to
                                  _ptr(logits), _ptr(scores), _ptr(topk_idx), _ptr(topk_score), _ptr(workspace),
                                  workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                  _stream(stream)), "moe_route_topk")
+
+
+def moe_route_topk_static(desc, x, w_router, bias, use_given_logits, logits, scores, topk_idx, topk_score, stream=None):
+    _check(load().moe_route_topk_static(ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(bias),
+                                        int(use_given_logits), _ptr(logits), _ptr(scores), _ptr(topk_idx),
+                                        _ptr(topk_score), _stream(stream)), "moe_route_topk_static")
 
 
 def moe_capacity_drop(desc, scores, topk_idx, expert_count, seg_count, expert_offset, row_token, row_weight,

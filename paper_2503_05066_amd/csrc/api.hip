@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, static sizes, workspace layout, entry points.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
@@ -139,6 +140,64 @@ using namespace capmoe;
 
 static bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
 
+// Scratch memory of moe_route_topk_static: the split-K partial sums of the router GEMM, for callers that can
+// neither allocate nor pass a workspace.  One copy per GPU, held from the moment the library is loaded on it.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// the current device's copy of `scratch` (looked up once per device, with that device current)
+static int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOE_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOE_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+
+static int route_topk_impl(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                   int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (desc->n_tokens == 0) return MOE_OK;  // nothing to route; empty arrays may be null
+    if (!logits || !scores || !topk_idx || !topk_score) return MOE_ERR_INVALID_ARG;
+    if (!use_given_logits && (!x || !w_router)) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const float* partial = nullptr;
+    int ksplit = 1;
+    if (!use_given_logits) {
+        const RouteWorkspace ws = route_workspace(*desc, workspace);
+        if (ws.use_mfma) {
+            if (ws.bytes > 0) {
+                if (!workspace) return MOE_ERR_INVALID_ARG;
+                if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+                if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+            }
+            if (misaligned16(x) || misaligned16(w_router)) return MOE_ERR_INVALID_ARG;
+            if (launch_router_mfma(*desc, ws, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
+            if (ws.ksplit > 1) {
+                partial = ws.partial;
+                ksplit = ws.ksplit;
+            }
+        } else if (launch_router_logits(*desc, x, w_router, bias, logits, st) != hipSuccess) {
+            return MOE_ERR_HIP;
+        }
+    }
+    if (launch_softmax_topk(*desc, logits, partial, ksplit, bias, scores, topk_idx, topk_score, st) != hipSuccess)
+        return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
 extern "C" {
 
 const char* moe_status_string(int status) {
@@ -148,6 +207,7 @@ const char* moe_status_string(int status) {
         case MOE_ERR_UNSUPPORTED: return "unsupported shape or type";
         case MOE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MOE_ERR_HIP: return "HIP launch failed";
+        case MOE_ERR_SCRATCH_LIMIT: return "problem needs more scratch memory than the built-in buffer holds";
         default: return "unknown status";
     }
 }
@@ -181,35 +241,22 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
 int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
                    int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
                    void* workspace, size_t workspace_bytes, void* stream) {
+    return route_topk_impl(desc, x, w_router, bias, use_given_logits, logits, scores, topk_idx, topk_score, workspace,
+                           workspace_bytes, stream);
+}
+
+int moe_route_topk_static(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
+                          int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
+                          void* stream) {
     const int v = validate(desc);
     if (v != MOE_OK) return v;
-    if (desc->n_tokens == 0) return MOE_OK;  // nothing to route; empty arrays may be null
-    if (!logits || !scores || !topk_idx || !topk_score) return MOE_ERR_INVALID_ARG;
-    if (!use_given_logits && (!x || !w_router)) return MOE_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
-    const float* partial = nullptr;
-    int ksplit = 1;
-    if (!use_given_logits) {
-        const RouteWorkspace ws = route_workspace(*desc, workspace);
-        if (ws.use_mfma) {
-            if (ws.bytes > 0) {
-                if (!workspace) return MOE_ERR_INVALID_ARG;
-                if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
-                if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
-            }
-            if (misaligned16(x) || misaligned16(w_router)) return MOE_ERR_INVALID_ARG;
-            if (launch_router_mfma(*desc, ws, x, w_router, bias, logits, st) != hipSuccess) return MOE_ERR_HIP;
-            if (ws.ksplit > 1) {
-                partial = ws.partial;
-                ksplit = ws.ksplit;
-            }
-        } else if (launch_router_logits(*desc, x, w_router, bias, logits, st) != hipSuccess) {
-            return MOE_ERR_HIP;
-        }
-    }
-    if (launch_softmax_topk(*desc, logits, partial, ksplit, bias, scores, topk_idx, topk_score, st) != hipSuccess)
-        return MOE_ERR_HIP;
-    return MOE_OK;
+    // the size check comes before anything touches the device: a refusal enqueues nothing
+    if (!use_given_logits && route_workspace(*desc, nullptr).bytes > kStaticScratchBytes) return MOE_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    const int st = static_scratch(&ptr);
+    if (st != MOE_OK) return st;
+    return route_topk_impl(desc, x, w_router, bias, use_given_logits, logits, scores, topk_idx, topk_score, ptr,
+                           kStaticScratchBytes, stream);
 }
 
 int moe_capacity_drop_ranked(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,

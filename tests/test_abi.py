@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_dispatch_ffn", "moe_combine",
             "moe_query", "moe_profile_attach", "moe_layer_forward", "moe_probe_mfma_bf16", "moe_capacity_drop_ranked",
-            "moe_status_string"} <= set(names)
+            "moe_status_string", "moe_route_topk_static"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
     assert capmoe.status_string(0) == "ok" and "workspace" in capmoe.status_string(3)
