@@ -2,19 +2,27 @@
 """Benchmark of the capacity-aware MoE layer forward on one MI355X.
 
 A step is one pass of the whole hot path (route+top-k, capacity drop, dispatch, grouped FFN,
-combine: the five C-ABI calls back to back on one stream) over one batch of synthetic,
-skew-routed input that is already resident in HBM.  Prints ONE JSON line:
-  value            tokens/s of the layer (N * steps / wall time between two device syncs)
-  roofline         the dominant kernel (gate/up GEMM with the SwiGLU epilogue), timed per launch
-                   with HIP events recorded by the library around that kernel inside the timed loop
+combine: the C-ABI calls back to back on one stream) over one batch of synthetic, skew-routed
+input that is already resident in HBM.  The headline workload is the Mixtral-shaped layer (the
+largest configuration, the one the matrix cores bind).  Prints ONE JSON line:
+  value            tokens/s of the layer with Token Drop at gamma = 1 (N * steps / wall time between
+                   two device syncs)
+  expanded_drop    the same workload and step count with Expanded Drop (its own value, rooflines,
+                   cpu_baseline)
+  roofline         the dominant kernel (gate/up GEMM with the SwiGLU epilogue), timed per launch with
+                   HIP events the library records around that kernel inside the timed loop;
+                   roofline_down: the second GEMM, timed the same way
   cpu_baseline     the CPU oracle on a bounded sample of the same workload, on the host cores
-  stages / other_workloads   per-kernel times and further configurations, for context
+  stages / other_workloads / gamma_sweep / straggler   per-kernel times, the other configurations,
+                   the capacity-factor curve and the per-device FFN times of the latency model
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
@@ -24,9 +32,9 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 matrix peak
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
-# HBM bytes per launch of the gate/up GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
-# 1 GiB device copy (profiles/olmoe_token_drop_gamma1_layer.md); keyed by (workload, mode, scope, gamma)
-MEASURED_TRAFFIC = {("olmoe", "token", "local", 1.0): 680.5e6 + 28.6e6}
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, recorded beside the kernel source they were measured on
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_of_the_expert_gemms.md")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2503_05066_amd", "csrc", "ffn.hip")
 
 MODES = {"none": 0, "token": 1, "expanded": 2}
 SCOPES = {"local": 0, "global": 1, "local_device": 2, "global_device": 3}
@@ -38,7 +46,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=200)
     p.add_argument("--warmup", type=int, default=20)
-    p.add_argument("--workload", default="olmoe", help="tiny | olmoe | mixtral | finegrained | decode")
+    p.add_argument("--workload", default="mixtral", help="tiny | olmoe | mixtral | finegrained | decode")
     p.add_argument("--mode", default="token", choices=list(MODES))
     p.add_argument("--scope", default="local", choices=list(SCOPES))
     p.add_argument("--gamma", type=float, default=1.0)
@@ -46,7 +54,9 @@ def parse():
     p.add_argument("--overselect", type=int, default=0, help="m: candidate lists are top-(k+m) instead of top-k")
     p.add_argument("--max-experts", action="store_true", help="at most k surviving experts per token (w/ max)")
     p.add_argument("--tokens", type=int, default=0, help="override the workload's token count (batch x length sweeps)")
-    p.add_argument("--sweep-gamma", default="", help="comma list of capacity factors measured after the main line")
+    p.add_argument("--sweep-gamma", default="0.5,1.0,1.5,2.0,inf",
+                   help="comma list of capacity factors measured after the main line ('' for none)")
+    p.add_argument("--no-expanded", action="store_true", help="skip the Expanded Drop line of the same workload")
     p.add_argument("--no-straggler", action="store_true",
                    help="skip the per-device FFN timing (the one-GPU stand-in for the latency model of Eq. 4)")
     p.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling probes (MFMA loop, device copy)")
@@ -59,18 +69,22 @@ def parse():
                    help="comma list of workloads whose expert FFN is also timed alone on experts of equal size "
                         "(N*k/E rows each, no router, no drop) with the vendor library's dense GEMM of the same "
                         "dimensions beside it ('' for none; skipped with --no-peaks)")
-    p.add_argument("--others", default="olmoe:none,finegrained:expanded,finegrained:token,finegrained:none,decode:token,decode:expanded,decode:none,mixtral:none,mixtral:expanded,mixtral:token:local_device,mixtral:token",
+    p.add_argument("--others", default="mixtral:none,mixtral:token:local_device,olmoe:token,olmoe:none,"
+                                       "finegrained:expanded,finegrained:token,finegrained:none,decode:token,"
+                                       "decode:expanded,decode:none",
                    help="comma list of workload:mode[:scope] measured after the main line ('' for none)")
     return p.parse_args()
 
 
 _uploaded = {}
+_host_weights = {}
 
 
-def upload(w):
+def upload(w, keep_host=False):
     """Synthetic inputs of a workload as device tensors (storage type of the workload).
 
-    The last workload stays resident, so that several modes of one workload share one upload."""
+    The last workload stays resident, so that several modes of one workload share one upload.  keep_host: also
+    keep the fp32-valued host copies of the expert weights (the CPU baseline reads them)."""
     import numpy as np
     import torch
 
@@ -78,6 +92,7 @@ def upload(w):
     if key in _uploaded:
         return _uploaded[key]
     _uploaded.clear()
+    _host_weights.clear()
     torch.cuda.empty_cache()
 
     from paper_2503_05066_amd import synth
@@ -94,11 +109,14 @@ def upload(w):
          "w_gate": torch.empty((e, h, d), dtype=act, device="cuda"),
          "w_up": torch.empty((e, h, d), dtype=act, device="cuda"),
          "w_down": torch.empty((e, d, h), dtype=act, device="cuda")}
-    for j in range(e):
-        g, u, dn = synth.expert_weights(w, j, keep_f32=False)
-        t["w_gate"][j].copy_(dev(g))
-        t["w_up"][j].copy_(dev(u))
-        t["w_down"][j].copy_(dev(dn))
+    # every expert has a random stream of its own: draw them on a few host threads, copy from this one
+    with ThreadPoolExecutor(max_workers=min(8, e)) as ex:
+        for j, (g, u, dn) in enumerate(ex.map(lambda j: synth.expert_weights(w, j, keep_f32=keep_host), range(e))):
+            t["w_gate"][j].copy_(dev(g))
+            t["w_up"][j].copy_(dev(u))
+            t["w_down"][j].copy_(dev(dn))
+            if keep_host:
+                _host_weights[j] = (g.f32, u.f32, dn.f32)
     _uploaded[key] = t
     return t
 
@@ -118,76 +136,20 @@ def algorithmic_work(w, S, rows, active, elem):
     }
 
 
-def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0, overselect=0, max_experts=0, per_kernel=True):
+def event_pairs(n):
     import torch
 
-    from paper_2503_05066_amd import capmoe, synth
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
 
-    t = upload(w)
-    desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
-                            gamma, w.dtype, metric, overselect, max_experts)
-    buf = capmoe.LayerBuffers(desc)
-    K_GU = capmoe.KERNELS.index("ffn_gate_up")
 
-    def step():
-        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
-                             fused_dispatch=fused)
-
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for a, b in pairs:      # materialise the events before the timed region
-        a.record()
-        b.record()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for a, b in pairs:
-        capmoe.moe_profile_attach(K_GU, a, b)
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    capmoe.moe_profile_attach(K_GU, None, None)
-    gu_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
-
-    # per-step durations (event pairs around whole steps), outside the timed region
-    for a, b in pairs:
-        a.record()
-        step()
-        b.record()
-    torch.cuda.synchronize()
-    step_ms = sorted(a.elapsed_time(b) for a, b in pairs)
-
-    # per-kernel durations, one kernel at a time, outside the timed region
-    kernel_ms = {}
-    reps = max(5, min(steps, 20))
-    for kid, name in enumerate(capmoe.KERNELS):
-        if not per_kernel or (name == "drop_limit" and not max_experts):
-            kernel_ms[name] = 0.0
-            continue
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for a, b in evs:
-            a.record()
-            b.record()
-        torch.cuda.synchronize()
-        for a, b in evs:
-            capmoe.moe_profile_attach(kid, a, b)
-            step()
-        torch.cuda.synchronize()
-        capmoe.moe_profile_attach(kid, None, None)
-        kernel_ms[name] = sum(a.elapsed_time(b) for a, b in evs) / reps
-
-    rows = int(buf.expert_offset[-1])
-    counts = buf.expert_count.cpu().numpy()
-    active = int((counts > 0).sum())
-    elem = 2 if w.dtype == synth.DTYPE_BF16 else 4
-    work = algorithmic_work(w, buf.slots, rows, active, elem)
-    if fused:   # the permuted copy is never written: the first GEMM reads x through row_token
-        work["dispatch"]["bytes"] = 0
-        kernel_ms["dispatch"] = 0.0
-    nbar = w.n_tokens * w.top_k / w.n_experts
-    # load statistics of the paper's latency model (Eq. 4: the most loaded expert / device sets the pace)
+def load_statistics(w, buf, gamma, mode):
+    """The paper's load statistics of one plan: loads before and after the drop (Sec. 3.1 and Sec. 4), the dropped
+    share, and Eq. (11) evaluated on the loads before the drop with the per-expert capacity gamma * N_bar."""
     import numpy as np
+
+    counts = buf.expert_count.cpu().numpy()
+    rows = int(buf.expert_offset[-1])
+    nbar = w.n_tokens * w.top_k / w.n_experts
     before = np.bincount(buf.topk_idx[:, :w.top_k].cpu().numpy().ravel(), minlength=w.n_experts)
     g = w.device_groups
     dev_before = before.reshape(g, -1).sum(1)
@@ -196,23 +158,116 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0, oversele
              "max_expert_load_over_mean_kept": float(counts.max() / nbar),
              "max_device_load_over_mean_topk": float(dev_before.max() / dev_before.mean()),
              "max_device_load_over_mean_kept": float(dev_after.max() / max(dev_after.mean(), 1e-9))}
-    pairs_topk = w.n_tokens * w.top_k
     per_token = (buf.pair_row >= 0).sum(1)
-    # Eq. (11) evaluated on the loads before the drop, with the per-expert capacity gamma * N_bar
     dt_eq11 = float(np.maximum(before - gamma * nbar, 0.0).sum() / before.sum()) if mode != 0 else 0.0
-    res = {
+    return {"rows": rows, "active_experts": int((counts > 0).sum()), "dropped_ratio": 1.0 - rows / (w.n_tokens * w.top_k),
+            "dt_eq11": dt_eq11, "experts_per_token_mean": rows / max(w.n_tokens, 1),
+            "experts_per_token_max": int(per_token.max()), "tokens_without_expert": int((per_token == 0).sum()),
+            "max_load_over_mean": float(counts.max() / nbar), "max_segment_load": int(buf.seg_count.max()),
+            "kept_fraction": rows / (w.n_tokens * w.top_k), "loads": {k: round(v, 3) for k, v in loads.items()}}
+
+
+def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0, overselect=0, max_experts=0, per_kernel=True,
+            keep_host=False):
+    import torch
+
+    from paper_2503_05066_amd import capmoe, synth
+
+    t = upload(w, keep_host)
+    desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
+                            gamma, w.dtype, metric, overselect, max_experts)
+    buf = capmoe.LayerBuffers(desc)
+    K_GU, K_DN = capmoe.KERNELS.index("ffn_gate_up"), capmoe.KERNELS.index("ffn_down")
+
+    def step():
+        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
+                             fused_dispatch=fused)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    gu, dn = event_pairs(steps), event_pairs(steps)
+    tab = capmoe.MoeProfile()
+    for a, b in gu + dn:      # materialise the events before the timed region
+        tab.set_events(K_GU, a, b)
+    torch.cuda.synchronize()
+    capmoe.moe_profile_attach(tab)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        tab.set_events(K_GU, *gu[i])
+        tab.set_events(K_DN, *dn[i])
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    capmoe.moe_profile_attach(None)
+    launched = {capmoe.KERNELS[k]: int(tab.launches[k]) for k in range(len(capmoe.KERNELS))}
+    gu_ms = sum(a.elapsed_time(b) for a, b in gu) / steps if launched["ffn_gate_up"] else None
+    dn_ms = sum(a.elapsed_time(b) for a, b in dn) / steps if launched["ffn_down"] else None
+
+    # per-step durations (event pairs around whole steps), outside the timed region
+    pairs = event_pairs(steps)
+    for a, b in pairs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    step_ms = sorted(a.elapsed_time(b) for a, b in pairs)
+
+    # per-kernel durations: every kernel's event pair in one table, a few steps, outside the timed region.
+    # A kernel id the call sequence never launched (the library counts launches) reports None.
+    kernel_ms = {name: None for name in capmoe.KERNELS}
+    if per_kernel:
+        reps = max(5, min(steps, 20))
+        evs = {k: event_pairs(reps) for k in range(len(capmoe.KERNELS))}
+        tab = capmoe.MoeProfile()
+        for k, prs in evs.items():
+            for a, b in prs:
+                tab.set_events(k, a, b)
+        torch.cuda.synchronize()
+        capmoe.moe_profile_attach(tab)
+        for i in range(reps):
+            for k, prs in evs.items():
+                tab.set_events(k, *prs[i])
+            step()
+        torch.cuda.synchronize()
+        capmoe.moe_profile_attach(None)
+        for k, name in enumerate(capmoe.KERNELS):
+            if tab.launches[k] > 0:
+                kernel_ms[name] = sum(a.elapsed_time(b) for a, b in evs[k]) / reps
+
+    stats = load_statistics(w, buf, gamma, mode)
+    elem = 2 if w.dtype == synth.DTYPE_BF16 else 4
+    work = algorithmic_work(w, buf.slots, stats["rows"], stats["active_experts"], elem)
+    if fused:   # the permuted copy is never written: the first GEMM reads x through row_token
+        work["dispatch"]["bytes"] = 0
+    res = dict(stats)
+    res.update({
         "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0],
-        "dropped_ratio": 1.0 - rows / pairs_topk, "dt_eq11": dt_eq11,
-        "experts_per_token_mean": rows / max(w.n_tokens, 1), "experts_per_token_max": int(per_token.max()),
-        "tokens_without_expert": int((per_token == 0).sum()),
         "wall_s": wall, "ms_per_step": 1e3 * wall / steps, "tokens_per_s": w.n_tokens * steps / wall,
-        "gate_up_ms": gu_ms, "kernel_ms": kernel_ms, "rows": rows, "active_experts": active, "cap": buf.cap,
-        "max_rows": buf.max_rows, "work": work, "max_load_over_mean": float(counts.max() / nbar),
-        "max_segment_load": int(buf.seg_count.max()), "kept_fraction": rows / (w.n_tokens * w.top_k),
-        "loads": {k: round(v, 3) for k, v in loads.items()},
-    }
+        "gate_up_ms": gu_ms, "down_ms": dn_ms, "kernel_ms": kernel_ms, "launches_in_timed_loop": launched,
+        "cap": buf.cap, "max_rows": buf.max_rows, "work": work,
+    })
     del buf
     return res
+
+
+def device_slices(w, buf, t):
+    """One simulated device's share of a plan as a layer call of its own: for every device the descriptor (its
+    E/G experts, any of the N tokens may hold a row at each), the row range of the plan and the arguments of
+    moe_dispatch_ffn without the workspace.  Yields (device, r0, r1, desc, args)."""
+    from paper_2503_05066_amd import capmoe, synth
+
+    g, e = w.device_groups, w.n_experts
+    m = e // g
+    offs = buf.expert_offset.cpu().numpy()
+    sub = capmoe.make_desc(w.n_tokens, w.d_model, m, m, w.d_hidden, 1, synth.MODE_NONE, synth.SCOPE_GLOBAL, 1.0,
+                           w.dtype)
+    for dev in range(g):
+        r0, r1 = int(offs[dev * m]), int(offs[(dev + 1) * m])
+        local_offset = (buf.expert_offset[dev * m:(dev + 1) * m + 1] - r0).contiguous()   # the device's own row numbering
+        args = (sub, t["x"], local_offset, buf.row_token[r0:], t["w_gate"][dev * m:(dev + 1) * m],
+                t["w_up"][dev * m:(dev + 1) * m], t["w_down"][dev * m:(dev + 1) * m], buf.yp[r0:])
+        yield dev, r0, r1, sub, args
 
 
 def per_device_ffn(w, mode, scope, gamma, reps=5, overselect=0, max_experts=0):
@@ -222,38 +277,30 @@ def per_device_ffn(w, mode, scope, gamma, reps=5, overselect=0, max_experts=0):
     this plan would cause, and the maximum is what the drop shortens."""
     import torch
 
-    from paper_2503_05066_amd import capmoe, synth
+    from paper_2503_05066_amd import capmoe
 
     t = upload(w)
-    g, e = w.device_groups, w.n_experts
-    m = e // g
-    desc = capmoe.make_desc(w.n_tokens, w.d_model, e, w.top_k, w.d_hidden, g, mode, scope, gamma, w.dtype, 0,
-                            overselect, max_experts)
+    desc = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, mode, scope,
+                            gamma, w.dtype, 0, overselect, max_experts)
     buf = capmoe.LayerBuffers(desc)
     capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
                          fused_dispatch=True)
     torch.cuda.synchronize()
-    offs = buf.expert_offset.cpu().numpy()
-    # one device's share as a layer of its own: m experts, any of the N tokens may hold a row at each
-    sub = capmoe.make_desc(w.n_tokens, w.d_model, m, m, w.d_hidden, 1, synth.MODE_NONE, synth.SCOPE_GLOBAL, 1.0,
-                           w.dtype)
-    ws = torch.empty(max(capmoe.moe_query(sub)[3], 256), dtype=torch.uint8, device="cuda")
+    ws = None
     rows, ms = [], []
-    for dev in range(g):
-        r0, r1 = int(offs[dev * m]), int(offs[(dev + 1) * m])
+    for dev, r0, r1, sub, args in device_slices(w, buf, t):
+        if ws is None:
+            ws = torch.empty(max(capmoe.moe_query(sub)[3], 256), dtype=torch.uint8, device="cuda")
         rows.append(r1 - r0)
         if r1 == r0:
             ms.append(0.0)
             continue
-        local_offset = (buf.expert_offset[dev * m:(dev + 1) * m + 1] - r0).contiguous()   # the device's own row numbering
-        args = (sub, t["x"], local_offset, buf.row_token[r0:], t["w_gate"][dev * m:(dev + 1) * m],
-                t["w_up"][dev * m:(dev + 1) * m], t["w_down"][dev * m:(dev + 1) * m], buf.yp[r0:], ws)
         for _ in range(2):
-            capmoe.moe_dispatch_ffn(*args)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            capmoe.moe_dispatch_ffn(*args, ws)
+        evs = event_pairs(reps)
         for a, b in evs:
             a.record()
-            capmoe.moe_dispatch_ffn(*args)
+            capmoe.moe_dispatch_ffn(*args, ws)
             b.record()
         torch.cuda.synchronize()
         ms.append(sorted(a.elapsed_time(b) for a, b in evs)[reps // 2])
@@ -307,7 +354,7 @@ def measured_peaks():
                    "1 GiB device copies (read + written bytes)"}
 
 
-def ffn_uniform(w, reps=7):
+def ffn_uniform(w, reps=9):
     """The grouped FFN alone on experts of equal size (N*k/E rows each): what the two GEMM kernels sustain when no
     tile is ragged, and torch.matmul (the vendor library) on one dense GEMM of the same M, N, K for comparison."""
     import torch
@@ -330,22 +377,26 @@ def ffn_uniform(w, reps=7):
     def run():
         capmoe.moe_grouped_ffn(desc, xp, off, t["w_gate"], t["w_up"], t["w_down"], yp, ws)
 
-    run()
+    for _ in range(2):
+        run()
     torch.cuda.synchronize()
     out = {"workload": w.name, "experts": e, "rows_per_expert": m, "d": d, "h": h}
+    kids = {name: capmoe.KERNELS.index(name) for name in ("ffn_gate_up", "ffn_down")}
+    evs = {name: event_pairs(reps) for name in kids}
+    tab = capmoe.MoeProfile()
+    for name, prs in evs.items():
+        for s0, s1 in prs:
+            tab.set_events(kids[name], s0, s1)
+    torch.cuda.synchronize()
+    capmoe.moe_profile_attach(tab)
+    for i in range(reps):
+        for name, prs in evs.items():
+            tab.set_events(kids[name], *prs[i])
+        run()
+    torch.cuda.synchronize()
+    capmoe.moe_profile_attach(None)
     for name, flops in (("ffn_gate_up", 4 * d * h * rows), ("ffn_down", 2 * d * h * rows)):
-        kid = capmoe.KERNELS.index(name)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for s0, s1 in evs:
-            s0.record()
-            s1.record()
-        torch.cuda.synchronize()
-        for s0, s1 in evs:
-            capmoe.moe_profile_attach(kid, s0, s1)
-            run()
-        torch.cuda.synchronize()
-        capmoe.moe_profile_attach(kid, None, None)
-        ms = sorted(s0.elapsed_time(s1) for s0, s1 in evs)[reps // 2]
+        ms = sorted(s0.elapsed_time(s1) for s0, s1 in evs[name])[reps // 2]
         out[name] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1),
                      "frac_of_peak": round(flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
     # the same dimensions as one dense NT GEMM each, through the vendor library
@@ -354,13 +405,13 @@ def ffn_uniform(w, reps=7):
         b_ = torch.randn(nn, kk, device="cuda", generator=gen).to(torch.bfloat16)
         for _ in range(2):
             c_ = a_ @ b_.T
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for s0, s1 in evs:
+        prs = event_pairs(reps)
+        for s0, s1 in prs:
             s0.record()
             c_ = a_ @ b_.T
             s1.record()
         torch.cuda.synchronize()
-        ms = sorted(s0.elapsed_time(s1) for s0, s1 in evs)[reps // 2]
+        ms = sorted(s0.elapsed_time(s1) for s0, s1 in prs)[reps // 2]
         out[name] = {"ms": round(ms, 4), "TFLOP/s": round(2 * mm * nn * kk / ms / 1e9, 1)}
         del a_, b_, c_
     out["note"] = ("vendor_dense_*: torch.matmul on ONE dense NT GEMM with the same M, N, K (a single weight matrix, "
@@ -381,7 +432,25 @@ def roofline_of(work, ms):
     return (mfma, hbm) if t_mfma >= t_hbm else (hbm, mfma)
 
 
-def cpu_baseline(w, mode, scope, gamma):
+def recorded_traffic(workload, mode, scope, gamma, kernel):
+    """HBM bytes per launch of one of the expert GEMMs from the tracked table of rocprofv3 --pmc runs
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain device copy), or None.
+
+    The table names the kernel source it was measured on (first 12 hex digits of the SHA-1 of ffn.hip): a row
+    recorded for another version of the kernel is not reported."""
+    try:
+        text = open(TRAFFIC_TABLE).read()
+        sha = hashlib.sha1(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:12]
+    except OSError:
+        return None
+    for line in text.splitlines():
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 8 and cells[:5] == [workload, mode, scope, f"{gamma:g}", kernel] and cells[7] == sha:
+            return float(cells[5]) + float(cells[6])
+    return None
+
+
+def cpu_baseline(w, mode, scope, gamma, budget_s=4.0):
     """The oracle, as it stands, on the host cores: routing on the full batch, FFN on a token sample."""
     import numpy as np
 
@@ -397,7 +466,7 @@ def cpu_baseline(w, mode, scope, gamma):
     rng = np.random.default_rng(1)
     # grow the sample until the FFN leg takes a few seconds
     sample = 16
-    weights = {}
+    weights = dict(_host_weights) if (w.name, w.n_tokens) in _uploaded else {}
     while True:
         toks = np.sort(rng.choice(w.n_tokens, size=min(sample, w.n_tokens), replace=False)).astype(np.int32)
         need = np.flatnonzero(ref.keep[toks].sum(0))
@@ -408,7 +477,7 @@ def cpu_baseline(w, mode, scope, gamma):
         t0 = time.perf_counter()
         oracle.layer_output(x, ref.scores, ref.keep, tabs[0], tabs[1], tabs[2], token_list=toks)
         t_ffn = time.perf_counter() - t0
-        if t_ffn > 4.0 or len(toks) >= w.n_tokens or sample >= 4096:
+        if t_ffn > budget_s or len(toks) >= w.n_tokens or sample >= 4096:
             break
         sample *= 4
     n_s = len(toks)
@@ -425,9 +494,84 @@ def cpu_baseline(w, mode, scope, gamma):
     single = len(one) / (t_route * len(one) / w.n_tokens + t_one)
     return {"value": n_s / est, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "single_thread_tokens_per_s": round(single, 1),
-            "sample": f"routing+drop on all {w.n_tokens} tokens ({t_route:.2f} s, prorated), expert FFN+combine on "
-                      f"{n_s} sampled tokens ({t_ffn:.2f} s); single thread: FFN+combine on {len(one)} of them "
-                      f"({t_one:.2f} s)"}
+            "sample": f"extrapolated from a subset: routing+drop on all {w.n_tokens} tokens ({t_route:.2f} s, prorated), "
+                      f"expert FFN+combine on {n_s} sampled tokens ({t_ffn:.2f} s); single thread: FFN+combine on "
+                      f"{len(one)} of them ({t_one:.2f} s)"}
+
+
+def rounded(d):
+    return {k: (round(v, 4) if isinstance(v, float) else v) for k, v in d.items()}
+
+
+def line_of(w, a, mode_name, scope_name, r):
+    """The reported objects of one measured (workload, mode): rooflines of both GEMMs, stages, statistics."""
+    out = {}
+    for key, kernel, ms, label in (("roofline", "ffn_gate_up", r["gate_up_ms"],
+                                    "ffn_gemm_bf16_kernel<..., SWIGLU> (gate/up GEMM + SwiGLU epilogue)"),
+                                   ("roofline_down", "ffn_down", r["down_ms"], "ffn_gemm_bf16_kernel<...> (down GEMM)")):
+        if ms is None:
+            out[key] = None
+            continue
+        primary, other = roofline_of(r["work"][kernel], ms)
+        plain = not (a.tokens or a.overselect or a.max_experts or a.metric != "score" or a.unfused)
+        tr = recorded_traffic(w.name, mode_name, scope_name, a.gamma, kernel) if plain else None
+        primary["traffic"] = other["traffic"] = tr
+        primary["traffic_source"] = (os.path.relpath(TRAFFIC_TABLE, ROOT) + " (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE "
+                                     "of this command, recorded for this version of the kernel source)") if tr else \
+            "none recorded for this command and this version of the kernel source"
+        primary["kernel"] = label
+        primary["ms_per_launch"] = round(ms, 5)
+        primary["other_roof"] = {k: other[k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+        out[key] = primary
+    stages = {}
+    km = r["kernel_ms"]
+    drop_ids = [k for k in ("drop_prepare", "drop_select", "drop_emit", "drop_limit") if km[k] is not None]
+    merged = dict(km)
+    merged["drop"] = sum(km[k] for k in drop_ids) if drop_ids else None
+    for name in ("router_logits", "softmax_topk", "drop", "dispatch", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"):
+        ms = merged[name]
+        if ms is None:
+            stages[name] = {"ms": None, "note": "fused into ffn_gate_up" if name == "dispatch" else "not launched"}
+            continue
+        stages[name] = {"ms": round(ms, 4)}
+        wk = r["work"].get(name)
+        if wk:
+            stages[name].update({"GB/s": round(wk["bytes"] / ms / 1e6, 1),
+                                 "hbm_frac": round(wk["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4)})
+            if wk["flops"]:
+                stages[name]["TFLOP/s"] = round(wk["flops"] / ms / 1e9, 2)
+        if name == "drop":
+            stages[name]["kernels"] = drop_ids
+    out["stages"] = stages
+    out["kernel_ms"] = {k: (round(v, 4) if v is not None else None) for k, v in km.items()}
+    out["step_ms_median"] = round(r["step_ms_median"], 4)
+    out["step_ms_min"] = round(r["step_ms_min"], 4)
+    out["config"] = {
+        "workload": f"{w.name}: N={w.n_tokens} d={w.d_model} E={w.n_experts} k={w.top_k} h={w.d_hidden} "
+                    f"G={w.device_groups}, {mode_name} drop, gamma={a.gamma}, {scope_name} capacity, {a.metric} metric"
+                    + (f", top-(k+{a.overselect}) candidates" if a.overselect else "")
+                    + (", at most k experts per token" if a.max_experts else ""),
+        "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
+        "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
+        "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3), "loads": r["loads"],
+        "dropped_ratio": round(r["dropped_ratio"], 4), "DT_eq11": round(r["dt_eq11"], 4),
+        "experts_per_token_mean": round(r["experts_per_token_mean"], 3),
+        "experts_per_token_max": r["experts_per_token_max"], "tokens_without_expert": r["tokens_without_expert"],
+        "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
+                 "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"}
+    return out
+
+
+def gamma_sweep(w, mode, scope, gammas, steps, warmup, fused=True, metric=0, overselect=0, max_experts=0):
+    """Throughput, dropped share and Eq. (11) over capacity factors (inf = no drop)."""
+    sweep = []
+    for gm in gammas:
+        o = measure(w, mode if gm != float("inf") else MODES["none"], scope, gm if gm != float("inf") else 1.0, steps,
+                    warmup, fused=fused, metric=metric, overselect=overselect, max_experts=max_experts, per_kernel=False)
+        sweep.append({"gamma": gm if gm != float("inf") else "inf", "tokens_per_s": round(o["tokens_per_s"], 1),
+                      "ms_per_step": round(o["ms_per_step"], 4), "dropped_ratio": round(o["dropped_ratio"], 4),
+                      "DT_eq11": round(o["dt_eq11"], 4), "surviving_pairs": o["rows"], "loads": o["loads"]})
+    return sweep
 
 
 def main():
@@ -447,100 +591,72 @@ def main():
     if a.tokens:
         w = synth.scaled(w, n_tokens=a.tokens)
     mode, scope = MODES[a.mode], SCOPES[a.scope]
-    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, fused=not a.unfused, metric=METRICS[a.metric],
-                overselect=a.overselect, max_experts=int(a.max_experts))
-    primary, other = roofline_of(r["work"]["ffn_gate_up"], r["gate_up_ms"])
-    primary["kernel"] = other["kernel"] = "ffn_gemm_bf16_kernel<..., SWIGLU> (gate/up GEMM + SwiGLU epilogue)"
-    plain = not (a.tokens or a.overselect or a.max_experts or a.metric != "score" or a.unfused)
-    primary["traffic"] = other["traffic"] = (MEASURED_TRAFFIC.get((a.workload, a.mode, a.scope, a.gamma))
-                                             if plain else None)
-    stages = {}
-    km = r["kernel_ms"]
-    drop_ms = km["drop_prepare"] + km["drop_select"] + km["drop_emit"] + km["drop_limit"]
-    for name, ms in [("router_logits", km["router_logits"]), ("softmax_topk", km["softmax_topk"]), ("drop", drop_ms),
-                     ("dispatch", km["dispatch"]), ("ffn_gate_up", km["ffn_gate_up"]), ("ffn_down", km["ffn_down"]),
-                     ("combine", km["combine"])]:
-        wk = r["work"][name]
-        if ms <= 0.0:
-            stages[name] = {"ms": 0.0, "note": "fused into ffn_gate_up"}
-            continue
-        stages[name] = {"ms": round(ms, 4), "GB/s": round(wk["bytes"] / ms / 1e6, 1),
-                        "hbm_frac": round(wk["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4)}
-        if wk["flops"]:
-            stages[name]["TFLOP/s"] = round(wk["flops"] / ms / 1e9, 2)
+    common = dict(fused=not a.unfused, metric=METRICS[a.metric], overselect=a.overselect,
+                  max_experts=int(a.max_experts))
+    keep_host = not a.no_cpu_baseline
+    r = measure(w, mode, scope, a.gamma, a.steps, a.warmup, keep_host=keep_host, **common)
+    main_line = line_of(w, a, a.mode, a.scope, r)
     out = {
         "metric": "MoE-layer tokens/sec at gamma=1.0 (Token & Expanded Drop); % MFMA/HBM roofline",
         "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: N={w.n_tokens} d={w.d_model} E={w.n_experts} k={w.top_k} h={w.d_hidden} "
-                               f"G={w.device_groups}, {a.mode} drop, gamma={a.gamma}, {a.scope} capacity, "
-                               f"{a.metric} metric"
-                               + (f", top-(k+{a.overselect}) candidates" if a.overselect else "")
-                               + (", at most k experts per token" if a.max_experts else ""),
-                   "cap": r["cap"], "surviving_pairs": r["rows"], "kept_fraction": round(r["kept_fraction"], 4),
-                   "active_experts": r["active_experts"], "max_segment_load": r["max_segment_load"],
-                   "max_load_over_mean_after_drop": round(r["max_load_over_mean"], 3), "loads": r["loads"],
-                   "dropped_ratio": round(r["dropped_ratio"], 4), "DT_eq11": round(r["dt_eq11"], 4),
-                   "experts_per_token_mean": round(r["experts_per_token_mean"], 3),
-                   "experts_per_token_max": r["experts_per_token_max"],
-                   "tokens_without_expert": r["tokens_without_expert"],
-                   "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
-                            "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"},
-        "roofline": primary, "roofline_other_roof": other, "stages": stages,
-        "kernel_ms": {k: round(v, 4) for k, v in km.items()},
-        "step_ms_median": round(r["step_ms_median"], 4), "step_ms_min": round(r["step_ms_min"], 4),
     }
+    out.update(main_line)
     if not a.no_peaks:
         pk = measured_peaks()
         out["measured_peaks"] = pk
-        for rf in (primary, other):
-            ceiling = pk["mfma_bf16_TFLOPs"] if rf["bound"] == "mfma" else pk["copy_GBs"]
-            rf["frac_of_measured_ceiling"] = round(rf["achieved"] / ceiling, 4)
-    if not a.no_straggler and w.device_groups > 1:
-        out["straggler"] = straggler(w, mode, scope, a.gamma, a.overselect, int(a.max_experts))
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, mode, scope, a.gamma)
+    # Expanded Drop on the same workload, same step count (the metric names both policies)
+    if not a.no_expanded and a.mode == "token" and w.device_groups > 1:
+        re_ = measure(w, MODES["expanded"], scope, a.gamma, a.steps, a.warmup, **common)
+        ed = {"value": re_["tokens_per_s"], "unit": "tokens/s", "steps": a.steps, "warmup": a.warmup,
+              "ms_per_step": re_["ms_per_step"]}
+        ed.update(line_of(w, a, "expanded", a.scope, re_))
+        if not a.no_cpu_baseline:
+            ed["cpu_baseline"] = cpu_baseline(w, MODES["expanded"], scope, a.gamma)
+        out["expanded_drop"] = ed
+    if not a.no_peaks:
+        for line in (out, out.get("expanded_drop") or {}):
+            for key in ("roofline", "roofline_down"):
+                rf = line.get(key)
+                if rf:
+                    ceiling = pk["mfma_bf16_TFLOPs"] if rf["bound"] == "mfma" else pk["copy_GBs"]
+                    rf["frac_of_measured_ceiling"] = round(rf["achieved"] / ceiling, 4)
+    if a.sweep_gamma:
+        gammas = [float(g) for g in a.sweep_gamma.split(",")]
+        out["gamma_sweep"] = {"mode": a.mode, "scope": a.scope, "steps": max(20, a.steps // 10),
+                              "points": gamma_sweep(w, mode, scope, gammas, max(20, a.steps // 10),
+                                                    max(5, a.warmup // 4), **common)}
+    if not a.no_straggler and w.device_groups > 1:
+        out["straggler"] = straggler(w, mode, scope, a.gamma, a.overselect, int(a.max_experts))
+    uniform = [] if a.no_peaks else [ffn_uniform(synth.WORKLOADS[n]) for n in a.ffn_uniform.split(",") if n]
+    if uniform:
+        out["ffn_uniform_experts"] = uniform
     others = []
+    o_steps, o_warm = max(20, a.steps // 4), max(5, a.warmup // 4)
     for item in [s for s in a.others.split(",") if s]:
         parts = item.split(":")
         name, m = parts[0], parts[1]
         osc = parts[2] if len(parts) > 2 else a.scope
-        if name == a.workload and m == a.mode and osc == a.scope:
+        if name == a.workload and m in (a.mode, "expanded") and osc == a.scope:
             continue
         ow = synth.WORKLOADS[name]
-        o = measure(ow, MODES[m], SCOPES[osc], a.gamma, max(5, a.steps // 5), max(2, a.warmup // 5),
-                    fused=not a.unfused, metric=METRICS[a.metric])
-        p1, p2 = roofline_of(o["work"]["ffn_gate_up"], o["gate_up_ms"])
-        d1, _ = roofline_of(o["work"]["ffn_down"], o["kernel_ms"]["ffn_down"])
-        others.append({"workload": name, "mode": m, "scope": osc, "gamma": a.gamma, "tokens_per_s": o["tokens_per_s"],
-                       "ms_per_step": o["ms_per_step"], "step_ms_median": round(o["step_ms_median"], 4),
-                       "step_ms_min": round(o["step_ms_min"], 4), "dropped_ratio": round(o["dropped_ratio"], 4),
-                       "experts_per_token_mean": round(o["experts_per_token_mean"], 3),
-                       "surviving_pairs": o["rows"], "cap": o["cap"],
-                       "max_segment_load": o["max_segment_load"], "loads": o["loads"], "ffn_gate_up": p1, "ffn_down": d1,
-                       "kernel_ms": {k: round(v, 4) for k, v in o["kernel_ms"].items()}})
+        o = measure(ow, MODES[m], SCOPES[osc], a.gamma, o_steps, o_warm, fused=not a.unfused, metric=METRICS[a.metric])
+        entry = {"workload": name, "mode": m, "scope": osc, "gamma": a.gamma, "steps": o_steps,
+                 "tokens_per_s": o["tokens_per_s"], "ms_per_step": o["ms_per_step"],
+                 "step_ms_median": round(o["step_ms_median"], 4), "step_ms_min": round(o["step_ms_min"], 4),
+                 "dropped_ratio": round(o["dropped_ratio"], 4),
+                 "experts_per_token_mean": round(o["experts_per_token_mean"], 3), "surviving_pairs": o["rows"],
+                 "cap": o["cap"], "max_segment_load": o["max_segment_load"], "loads": o["loads"],
+                 "kernel_ms": {k: (round(v, 4) if v is not None else None) for k, v in o["kernel_ms"].items()}}
+        for key, kernel, ms in (("ffn_gate_up", "ffn_gate_up", o["gate_up_ms"]), ("ffn_down", "ffn_down", o["down_ms"])):
+            if ms is not None:
+                entry[key] = rounded(roofline_of(o["work"][kernel], ms)[0])
+        others.append(entry)
     if others:
         out["other_workloads"] = others
-    uniform = [] if a.no_peaks else [ffn_uniform(synth.WORKLOADS[n]) for n in a.ffn_uniform.split(",") if n]
-    if uniform:
-        out["ffn_uniform_experts"] = uniform
-    if not a.no_straggler and w.device_groups == 1:
-        # the default workload has one device; show the latency model on the Mixtral-shaped one (4 devices x 2 experts)
-        names = {o["workload"] for o in others}
-        if "mixtral" in names:
-            out["straggler_mixtral"] = straggler(synth.WORKLOADS["mixtral"], MODES["token"], SCOPES["local"], a.gamma)
-    if a.sweep_gamma:
-        sweep = []
-        for gs in a.sweep_gamma.split(","):
-            gm = float(gs)
-            o = measure(w, mode if gm != float("inf") else MODES["none"], scope, gm, max(5, a.steps // 5),
-                        max(2, a.warmup // 5), fused=not a.unfused, metric=METRICS[a.metric], overselect=a.overselect,
-                        max_experts=int(a.max_experts), per_kernel=False)
-            sweep.append({"gamma": gm, "tokens_per_s": round(o["tokens_per_s"], 1), "ms_per_step": round(o["ms_per_step"], 4),
-                          "dropped_ratio": round(o["dropped_ratio"], 4), "DT_eq11": round(o["dt_eq11"], 4),
-                          "surviving_pairs": o["rows"], "loads": o["loads"]})
-        out["gamma_sweep"] = sweep
     if a.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)

@@ -18,9 +18,9 @@
  *     launch; on a non-zero status nothing was enqueued.  MOE_ERR_HIP reports a failed launch.
  *   - `workspace` is scratch device memory of at least the size moe_query reports, 256-byte
  *     aligned, reusable between calls (its content has no meaning after a call completes).
- *   - One host thread at a time, one device per process: the library keeps what it learns on its
- *     first calls (kernel attributes it has set, the compute-unit count) for the device that was
- *     current then, without locks.
+ *   - Calls act on the current device.  The library holds no state of a call; what it remembers is per
+ *     device and written atomically (which kernel attributes it has set there, the compute-unit count, the
+ *     address of the built-in buffer of moe_route_topk_static), so any host thread may call on any device.
  *
  * Simulated expert parallelism: with G = device_groups, token t lives on device t / (N/G) and
  * device b hosts experts [b*E/G, (b+1)*E/G) (data parallel = expert parallel, as in the paper's
@@ -232,11 +232,12 @@ int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_rout
                       size_t workspace_bytes, void* stream);
 
 /*
- * Profiling hook (instrumentation, not part of the method).  While a pair of hipEvent_t (passed as
- * void*) is attached to a kernel id, every launch of that kernel records `start` before and `stop`
- * after it on the launch stream; hipEventElapsedTime(start, stop) is then that launch's duration.
- * Pass NULL events to detach.  The table is process-wide and not thread-safe: attach from the
- * thread that enqueues the layer.
+ * Profiling hook (instrumentation, not part of the method).  The table is the caller's (host memory); the
+ * library keeps only a pointer to it, per host thread, between moe_profile_attach(table) and
+ * moe_profile_attach(NULL).  While a table is attached to the calling thread, every launch of kernel id k by
+ * that thread increments launches[k] and, where start[k] / stop[k] are not NULL, records those hipEvent_t
+ * (passed as void*) before / after the launch on the launch stream: hipEventElapsedTime(start, stop) is then
+ * that launch's duration, and launches[k] == 0 tells that the call sequence never ran the kernel.
  */
 enum {
     MOE_KERNEL_ROUTER_LOGITS = 0,
@@ -252,7 +253,12 @@ enum {
     MOE_KERNEL_DROP_LIMIT = 10, /* only launched with max_experts */
     MOE_KERNEL_COUNT = 11
 };
-int moe_profile_attach(int kernel, void* start_event, void* stop_event);
+typedef struct {
+    void* start[MOE_KERNEL_COUNT];
+    void* stop[MOE_KERNEL_COUNT];
+    int64_t launches[MOE_KERNEL_COUNT];
+} moe_profile_t;
+int moe_profile_attach(moe_profile_t* table);
 
 /*
  * Matrix-core ceiling probe (instrumentation, not part of the method): launches `blocks` workgroups of

@@ -32,6 +32,28 @@ class MoeDesc(ctypes.Structure):
     ]
 
 
+KERNELS = ("router_logits", "softmax_topk", "drop_prepare", "drop_select", "drop_emit", "dispatch", "ffn_schedule",
+           "ffn_gate_up", "ffn_down", "combine", "drop_limit")
+
+
+class MoeProfile(ctypes.Structure):
+    """moe_profile_t of include/capmoe.h: event handles per kernel id and the library's launch counts."""
+
+    _fields_ = [("start", ctypes.c_void_p * len(KERNELS)), ("stop", ctypes.c_void_p * len(KERNELS)),
+                ("launches", ctypes.c_int64 * len(KERNELS))]
+
+    def set_events(self, kernel: int, start_event, stop_event):
+        """torch.cuda.Event pair (created with enable_timing) for one kernel id, or None, None."""
+        def handle(ev):
+            if ev is None:
+                return None
+            if not ev.cuda_event:      # torch creates the hipEvent lazily; recording once materialises it
+                ev.record()
+            return ev.cuda_event
+        self.start[kernel] = handle(start_event)
+        self.stop[kernel] = handle(stop_event)
+
+
 class CapMoeError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
@@ -65,7 +87,7 @@ def load():
         lib.moe_combine.argtypes = [dp, vp, vp, vp, vp, vp]
         lib.moe_layer_forward.argtypes = [dp] + [vp] * 7 + [ctypes.c_uint32] + [vp] * 13 + [sz, vp]
         lib.moe_layer_forward.restype = i32
-        lib.moe_profile_attach.argtypes = [i32, vp, vp]
+        lib.moe_profile_attach.argtypes = [ctypes.POINTER(MoeProfile)]
         lib.moe_profile_attach.restype = i32
         lib.moe_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
         lib.moe_probe_mfma_bf16.restype = i32
@@ -179,19 +201,9 @@ def moe_layer_forward(desc, x, w_router, bias, w_gate, w_up, w_down, token_class
     return buf.y
 
 
-KERNELS = ("router_logits", "softmax_topk", "drop_prepare", "drop_select", "drop_emit", "dispatch", "ffn_schedule",
-           "ffn_gate_up", "ffn_down", "combine", "drop_limit")
-
-
-def moe_profile_attach(kernel: int, start_event=None, stop_event=None):
-    """Attach a pair of recorded-on-launch events (torch.cuda.Event, created with enable_timing) or detach."""
-    def handle(ev):
-        if ev is None:
-            return None
-        if not ev.cuda_event:      # torch creates the hipEvent lazily; recording once materialises it
-            ev.record()
-        return ctypes.c_void_p(ev.cuda_event)
-    _check(load().moe_profile_attach(int(kernel), handle(start_event), handle(stop_event)), "moe_profile_attach")
+def moe_profile_attach(table: "MoeProfile | None"):
+    """Attach the caller's profile table to this thread (None detaches).  The caller keeps the table alive."""
+    _check(load().moe_profile_attach(ctypes.byref(table) if table is not None else None), "moe_profile_attach")
 
 
 def moe_probe_mfma_bf16(blocks: int, iterations: int, sink, stream=None) -> int:

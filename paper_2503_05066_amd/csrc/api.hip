@@ -123,7 +123,18 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
     return w;
 }
 
-ProfileSlot g_profile[MOE_KERNEL_COUNT] = {};
+thread_local moe_profile_t* t_profile = nullptr;
+
+int compute_units() {
+    static std::atomic<int> cus[kMaxDevices] = {};
+    const int dev = current_device();
+    int c = cus[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        if (hipDeviceGetAttribute(&c, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || c <= 0) c = 256;
+        cus[dev].store(c, std::memory_order_relaxed);
+    }
+    return c;
+}
 
 // gathered: the first GEMM fetches its rows from the unpermuted x (moe_dispatch_ffn): the bf16 kernels address x
 // through one buffer descriptor with 32-bit byte offsets, so x must stay below 4 GiB
@@ -146,7 +157,6 @@ static bool misaligned16(const void* p) { return ((uintptr_t)p & 15) != 0; }
 constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-constexpr int kMaxDevices = 64;
 static void* g_scratch_ptr[kMaxDevices] = {};
 static std::mutex g_scratch_mutex;
 
@@ -212,11 +222,8 @@ const char* moe_status_string(int status) {
     }
 }
 
-int moe_profile_attach(int kernel, void* start_event, void* stop_event) {
-    if (kernel < 0 || kernel >= MOE_KERNEL_COUNT) return MOE_ERR_INVALID_ARG;
-    if ((start_event == nullptr) != (stop_event == nullptr)) return MOE_ERR_INVALID_ARG;
-    g_profile[kernel].start = (hipEvent_t)start_event;
-    g_profile[kernel].stop = (hipEvent_t)stop_event;
+int moe_profile_attach(moe_profile_t* table) {
+    t_profile = table;
     return MOE_OK;
 }
 

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "capmoe.h"
 
 namespace capmoe {
@@ -80,21 +82,42 @@ struct FfnWorkspace {
 };
 FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base);
 
-// Event pairs attached by moe_profile_attach; ProfileScope records them around one launch.
-struct ProfileSlot {
-    hipEvent_t start, stop;
-};
-extern ProfileSlot g_profile[MOE_KERNEL_COUNT];
+// The caller's profile table (moe_profile_attach), per host thread; ProfileScope records the table's events
+// around one launch and counts the launch.  The library keeps only this pointer, never the table.
+extern thread_local moe_profile_t* t_profile;
 struct ProfileScope {
     int id;
     hipStream_t st;
     ProfileScope(int id_, hipStream_t st_) : id(id_), st(st_) {
-        if (g_profile[id].start) (void)hipEventRecord(g_profile[id].start, st);
+        if (t_profile) {
+            if (t_profile->start[id]) (void)hipEventRecord((hipEvent_t)t_profile->start[id], st);
+            t_profile->launches[id] += 1;
+        }
     }
     ~ProfileScope() {
-        if (g_profile[id].stop) (void)hipEventRecord(g_profile[id].stop, st);
+        if (t_profile && t_profile->stop[id]) (void)hipEventRecord((hipEvent_t)t_profile->stop[id], st);
     }
 };
+
+// What the library remembers per device (kernel attributes already set, the compute-unit count): one bit or
+// one slot per device ordinal, written with atomics, so that any thread may call on any device.
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+    return dev;
+}
+// Runs `configure` on the first call for the current device (twice at worst, when two threads race: setting a
+// kernel attribute again is harmless); `seen` is one word per kernel, one bit per device.
+template <class F>
+inline void once_per_device(std::atomic<uint64_t>& seen, F&& configure) {
+    const uint64_t bit = 1ull << current_device();
+    if (!(seen.load(std::memory_order_acquire) & bit)) {
+        configure();
+        seen.fetch_or(bit, std::memory_order_release);
+    }
+}
+int compute_units();  // of the current device
 
 // Launchers (each returns a hipError_t from hipGetLastError after its launches).
 hipError_t launch_router_logits(const moe_desc_t& d, const void* x, const float* w, const float* bias, float* logits,

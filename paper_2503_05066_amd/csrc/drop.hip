@@ -959,13 +959,12 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         ProfileScope prof(MOE_KERNEL_DROP_SELECT, st);
         const size_t n_keys = (size_t)s.seg_tokens * s.span;
         const size_t lds = (n_keys <= (size_t)kSelectCache ? n_keys : 0) * 4;
-        static bool configured = false;
-        if (!configured) {  // up to 128 KB of keys plus the kernel's own few kilobytes
+        static std::atomic<uint64_t> configured{0};
+        once_per_device(configured, [] {  // up to 128 KB of keys plus the kernel's own few kilobytes
             for (const void* k : {(const void*)drop_select_kernel<256, 1>, (const void*)drop_select_kernel<256, 4>,
                                   (const void*)drop_select_kernel<1024, 1>, (const void*)drop_select_kernel<1024, 4>})
                 (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kSelectCache * 4);
-            configured = true;
-        }
+        });
         const bool wide = n_keys > 4096;                          // threads per block
         const bool vec = N % 4 == 0 && s.seg_tokens % 4 == 0;     // 16-byte loads of four keys
         auto kern = wide ? (vec ? drop_select_kernel<1024, 4> : drop_select_kernel<1024, 1>)

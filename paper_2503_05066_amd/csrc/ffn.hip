@@ -613,11 +613,10 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
                         const TileList& big, const TileList& small, int K, int Nout, hipStream_t st) {
     constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
     auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<uint64_t> configured{0};
+    once_per_device(configured, [&] {
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        configured = true;
-    }
+    });
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
     // a converted last round adds at most one short item per compute unit; + 16: both lists are cut into
     // eight whole chunks
@@ -642,13 +641,7 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
             return TileListArgs{b.expert, b.row0, b.rows, b.count, sm.expert, sm.row0, sm.rows, sm.count,
                                 b.max_tiles, sm.max_tiles, ncol};
         };
-        static int cus = 0;
-        if (cus == 0) {
-            int dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-                cus = 256;
-        }
+        const int cus = compute_units();
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
         // gate/up: a big item covers 128 hidden columns (gate and up rows of them); fp32: one pair of lists, as cut
         const TileListArgs gu = args(ws.big, ws.small, bf16 ? N1 / 128 : 0);

@@ -280,11 +280,10 @@ static void launch_rm_depth(const moe_desc_t& d, const RouteWorkspace& ws, const
                             const float* bias, float* out, hipStream_t st) {
     const size_t lds = (size_t)2 * rm_stage_bytes(TN);
     auto kern = router_mfma_kernel<TN, D>;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<uint64_t> configured{0};
+    once_per_device(configured, [&] {
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        configured = true;
-    }
+    });
     const dim3 grid((d.n_tokens + kRmTokens - 1) / kRmTokens, ws.ksplit, (d.n_experts + 32 * TN - 1) / (32 * TN));
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const uint16_t*)x, w, bias, out, d.n_tokens, d.d_model,
                        d.n_experts, d.d_model / ws.ksplit, ws.ksplit == 1 ? 1 : 0);

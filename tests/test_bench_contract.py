@@ -37,9 +37,29 @@ def test_algorithmic_work_matches_the_stated_formulas():
     assert work["ffn_gate_up"]["flops"] == 4 * d * h * rows and work["ffn_down"]["flops"] == 2 * d * h * rows
     assert work["combine"]["bytes"] == rows * d * elem + n * d * elem
     assert work["router_logits"]["bytes"] == n * d * elem + e * d * 4 + n * e * 4
-    # the constant quoted for the measured traffic belongs to the default workload only
-    assert list(bench.MEASURED_TRAFFIC) == [("olmoe", "token", "local", 1.0)]
-    assert 0.9 < bench.MEASURED_TRAFFIC[("olmoe", "token", "local", 1.0)] / work["ffn_gate_up"]["bytes"] < 1.5
+
+
+def test_recorded_traffic_is_reported_only_for_the_kernel_source_it_was_measured_on(tmp_path, monkeypatch):
+    import hashlib
+
+    src = tmp_path / "ffn.hip"
+    src.write_text("kernel v1")
+    sha = hashlib.sha1(b"kernel v1").hexdigest()[:12]
+    table = tmp_path / "traffic.md"
+    table.write_text("| workload | mode | scope | gamma | kernel | read bytes | written bytes | source |\n|---|---|---|---|---|---|---|---|\n"
+                     f"| mixtral | token | local | 1 | ffn_gate_up | 5.0e9 | 2.5e8 | {sha} |\n"
+                     f"| mixtral | token | local | 1 | ffn_down | 2.0e9 | 7.0e7 | 000000000000 |\n")
+    monkeypatch.setattr(bench, "TRAFFIC_TABLE", str(table))
+    monkeypatch.setattr(bench, "KERNEL_SOURCE", str(src))
+    assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") == pytest.approx(5.25e9)
+    assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_down") is None      # another source version
+    assert bench.recorded_traffic("mixtral", "expanded", "local", 1.0, "ffn_gate_up") is None
+    src.write_text("kernel v2")                                                               # the kernel changed
+    assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") is None
+    # the tracked table parses, whatever it holds today
+    monkeypatch.undo()
+    v = bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up")
+    assert v is None or v > 1e9
 
 
 def test_defaults_name_the_headline_workload():
@@ -49,5 +69,7 @@ def test_defaults_name_the_headline_workload():
         a = bench.parse()
     finally:
         sys.argv = old
-    assert (a.gpus, a.workload, a.mode, a.scope, a.gamma, a.metric) == (1, "olmoe", "token", "local", 1.0, "score")
-    assert a.steps >= 50 and a.warmup >= 10
+    # the largest single-GPU configuration (the Mixtral-shaped layer), Token Drop with the Expanded Drop line beside it
+    assert (a.gpus, a.workload, a.mode, a.scope, a.gamma, a.metric) == (1, "mixtral", "token", "local", 1.0, "score")
+    assert not a.no_expanded and a.steps >= 50 and a.warmup >= 10
+    assert [float(g) for g in a.sweep_gamma.split(",")][:4] == [0.5, 1.0, 1.5, 2.0]

@@ -65,7 +65,8 @@ def check_route_and_plan(orc, logits, n, e, k, g, mode, scope, gamma, what, metr
 # ------------------------------------------------------------------------------------------------
 # router logits
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name,n", [("tiny", 128), ("olmoe", 1000), ("decode", 256), ("finegrained", 777)])
+@pytest.mark.parametrize("name,n", [("tiny", 128), ("olmoe", 1000), ("decode", 256), ("finegrained", 777),
+                                    ("mixtral", 8192), ("olmoe", 4096), ("finegrained", 16384)])
 def test_router_logits(orc, name, n):
     w = synth.scaled(W[name], n_tokens=n, device_groups=1)
     note("router logits", w)
@@ -580,33 +581,144 @@ def test_ffn_random_expert_sizes(orc, trial):
     assert torch.equal(fused.y, buf.y)
 
 
-def sample_tokens(ref, n, count, seed):
+# ------------------------------------------------------------------------------------------------
+# full size: the launch configuration the benchmark times
+# ------------------------------------------------------------------------------------------------
+_layers = {}
+
+
+def full_layer(name):
+    """The workload's inputs on the device and on the host, shared by the full-size tests (one at a time)."""
+    if name not in _layers:
+        _layers.clear()
+        torch.cuda.empty_cache()
+        _layers[name] = DeviceLayer(W[name])
+    return _layers[name]
+
+
+def stratified_rows(plan, seed):
+    """Rows of the plan chosen so that every GEMM tile of the timed launch holds a checked row: one row in
+    every 64-row piece of every expert's rows (64 rows is the shortest tile, and the tiles of a cut last round
+    are 64-row pieces of 256-row tiles, so every full-height tile gets four), plus the first and last row of
+    every expert."""
     rng = np.random.default_rng(seed)
+    off = plan.expert_offset
+    rows = []
+    for e in range(len(off) - 1):
+        lo, hi = int(off[e]), int(off[e + 1])
+        if hi == lo:
+            continue
+        rows += [lo, hi - 1]
+        for p0 in range(lo, hi, 64):
+            rows.append(int(rng.integers(p0, min(p0 + 64, hi))))
+    return np.array(sorted(set(rows)), np.int64)
+
+
+def check_rows_of_yp(orc, layer, buf, ref, rows, what):
+    """yp[r,:] = E_e(x[row_token[r]]) for the listed rows: the oracle computes each row as a one-expert layer with
+    gate weight 1 (Eq. 2 with a single term)."""
+    w = layer.w
+    tok = ref.plan.row_token[rows]
+    expert = np.searchsorted(ref.plan.expert_offset, rows, side="right") - 1
+    ones = np.ones((len(rows), w.n_experts), np.float32)
+    keep = np.zeros((len(rows), w.n_experts), np.uint8)
+    keep[np.arange(len(rows)), expert] = 1
+    ref_rows = orc.layer_output(layer.x_host[tok], ones, keep, layer.host_gate, layer.host_up, layer.host_down)
+    got = to_host_f64(buf.yp[torch.from_numpy(rows).cuda()])
+    assert np.all(np.isfinite(got))
+    assert_output_close(got, ref_rows, TOL[w.dtype], what + " yp rows")
+
+
+def special_tokens(ref, n):
     kept_per_token = ref.keep.sum(1)
-    picks = list(rng.choice(n, size=count, replace=False))
-    empty = np.flatnonzero(kept_per_token == 0)
-    if len(empty):
-        picks += list(empty[:2])                       # tokens that lost every expert
-    picks += [0, n - 1, int(np.argmax(kept_per_token))]  # ends of the batch, the token with most experts
-    return np.array(sorted(set(int(p) for p in picks)), np.int32)
+    picks = [0, n - 1, int(np.argmax(kept_per_token))]          # ends of the batch, the token with most experts
+    picks += list(np.flatnonzero(kept_per_token == 0)[:4])      # tokens that lost every expert
+    return picks
 
 
-@pytest.mark.parametrize("name,cases,count", [
-    ("olmoe", [(TD, LOCAL, 1.0), (TD, LOCAL, 2.0), (NONE, LOCAL, 1.0)], 48),
-    ("decode", [(TD, LOCAL, 1.0), (ED, LOCAL, 1.0)], 24),
-    ("finegrained", [(ED, LOCAL, 1.0), (ED, LOCAL, 1.25)], 32),
-    ("mixtral", [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (ED, LOCAL, 1.0)], 10),
-])
-def test_layer_full_size_sampled(orc, name, cases, count):
-    """The launch configuration the benchmark times, checked on sampled tokens the oracle computes one by one."""
+# (mode, scope, gamma) per workload; full = every token of the batch is compared, otherwise the tokens of a
+# stratified row sample (at least 512)
+FULL_LAYER_CASES = [
+    ("olmoe", True, [(TD, LOCAL, 1.0), (TD, LOCAL, 2.0), (NONE, LOCAL, 1.0)]),
+    ("decode", True, [(TD, LOCAL, 1.0), (ED, LOCAL, 1.0)]),
+    ("finegrained", False, [(ED, LOCAL, 1.0), (ED, LOCAL, 1.25), (TD, LOCAL, 1.0)]),
+    ("mixtral", False, [(NONE, LOCAL, 1.0), (TD, LOCAL, 1.0), (ED, LOCAL, 1.0)]),
+]
+
+
+@pytest.mark.parametrize("name,full,cases", FULL_LAYER_CASES)
+def test_layer_full_size(orc, name, full, cases):
+    """The launch configuration the benchmark times: y on the whole batch (OLMoE- and decode-shaped) or on at
+    least 512 tokens that cover every row tile of every expert, and sampled rows of yp one by one."""
     w = W[name]
-    layer = DeviceLayer(w)
+    layer = full_layer(name)
     logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
     for mode, scope, gamma in cases:
         ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, scope, gamma)
-        toks = sample_tokens(ref, w.n_tokens, count, 11)
-        check_layer(orc, layer, mode, scope, gamma, tokens=toks, what="full size sampled")
-    del layer
+        rows = stratified_rows(ref.plan, 11)
+        if full:
+            toks = None
+        else:
+            picks = set(int(t) for t in ref.plan.row_token[rows]) | set(int(t) for t in special_tokens(ref, w.n_tokens))
+            extra = np.random.default_rng(12).permutation(w.n_tokens)
+            for t in extra:                     # top up to 512 tokens
+                if len(picks) >= 512:
+                    break
+                picks.add(int(t))
+            toks = np.array(sorted(picks), np.int32)
+        note("full size", name, dict(mode=mode, gamma=gamma, rows=ref.plan.rows, sampled_rows=len(rows),
+                                     tokens=w.n_tokens if toks is None else len(toks)))
+        buf, _ = check_layer(orc, layer, mode, scope, gamma, tokens=toks, what=f"{name} full size")
+        check_rows_of_yp(orc, layer, buf, ref, rows, f"{name} full size")
+        del buf
+
+
+@pytest.mark.parametrize("name,mode,full", [("mixtral", TD, False), ("mixtral", ED, False), ("finegrained", ED, False),
+                                            ("decode", ED, True), ("olmoe", TD, True)])
+def test_layer_full_size_own_router(orc, name, mode, full):
+    """The path the benchmark times end to end: the library's own router GEMM feeds the drop.  Its logits are
+    read back and handed to the oracle: scores, top-k and the plan must then be bit-equal, and y within
+    tolerance (whole batch, or at least 512 tokens covering every row tile)."""
+    w = W[name]
+    layer = full_layer(name)
+    desc = layer.desc(mode, LOCAL, 1.0)
+    buf = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(buf, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         fused_dispatch=True)
+    torch.cuda.synchronize()
+    logits = buf.logits.cpu().numpy()
+    ref_logits = orc.router_logits(layer.x_host, layer.w_router_host, layer.bias_host)
+    assert np.abs(logits - ref_logits).max() <= 1e-4 * np.abs(ref_logits).max()
+    ref = orc.route_and_drop(logits, w.top_k, w.device_groups, mode, LOCAL, 1.0)
+    np.testing.assert_array_equal(buf.scores.cpu().numpy().view(np.uint32), ref.scores.view(np.uint32))
+    np.testing.assert_array_equal(buf.topk_idx.cpu().numpy(), ref.topk_idx)
+    assert_plan_equal(buf, ref, f"{name} own router")
+    assert ref.plan.seg_count.max(initial=0) <= ref.cap
+    rows = stratified_rows(ref.plan, 13)
+    if full:
+        toks = None
+    else:
+        picks = set(int(t) for t in ref.plan.row_token[rows]) | set(int(t) for t in special_tokens(ref, w.n_tokens))
+        for t in np.random.default_rng(14).permutation(w.n_tokens):
+            if len(picks) >= 512:
+                break
+            picks.add(int(t))
+        toks = np.array(sorted(picks), np.int32)
+    note("own router", name, dict(mode=mode, rows=ref.plan.rows, tokens=w.n_tokens if toks is None else len(toks)))
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down,
+                             token_list=toks)
+    y = to_host_f64(buf.y)
+    assert_output_close(y if toks is None else y[toks], y_ref, TOL[w.dtype], f"{name} own router")
+    # run to run: the same bits
+    again = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(again, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(again.y, buf.y) and torch.equal(again.yp[:ref.plan.rows], buf.yp[:ref.plan.rows])
+
+
+def test_release_full_size_layers():
+    _layers.clear()
     torch.cuda.empty_cache()
 
 
