@@ -92,19 +92,14 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
     w.big.max_tiles = (int)(s.max_rows / w.big.tile_m) + d.n_experts;
     w.small.tile_m = kFfnTileSmall;
     w.small_max = bf16 ? kFfnSmallMax : 0;
-    // remainders (one per expert at most) or, with a converted last round, at most one short row tile per
-    // compute unit
-    const int regular = d.n_experts * (kFfnSmallMax / kFfnTileSmall);
-    w.small.max_tiles = bf16 ? (regular > kFfnMaxUnits ? regular : kFfnMaxUnits) : 0;
-    w.small.max_launch = bf16 ? regular : 0;
+    // remainders: one per expert at most
+    w.small.max_tiles = bf16 ? d.n_experts * (kFfnSmallMax / kFfnTileSmall) : 0;
+    w.small.max_launch = w.small.max_tiles;
     w.big.max_launch = w.big.max_tiles;
-    w.big_down = w.big;
-    w.small_down = w.small;
 
     w.hidden = p + off;
     off += align256((size_t)(s.max_rows > 0 ? s.max_rows : 1) * d.d_hidden * s.elem);
-    for (TileList* t : {&w.big, &w.small, &w.big_down, &w.small_down}) {
-        if (!bf16 && (t == &w.big_down || t == &w.small_down)) continue;
+    for (TileList* t : {&w.big, &w.small}) {
         const size_t n = align256((size_t)(t->max_tiles > 0 ? t->max_tiles : 1) * 4);
         t->expert = (int32_t*)(p + off);
         off += n;
@@ -115,9 +110,16 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
         t->count = (int32_t*)(p + off);
         off += 256;
     }
-    if (!bf16) {  // one pair of lists
-        w.big_down = w.big;
-        w.small_down = w.small;
+    w.split_hdr = nullptr;
+    w.split_counter = nullptr;
+    w.split_partial = nullptr;
+    if (bf16) {
+        w.split_hdr = (int32_t*)(p + off);
+        off += 256;
+        w.split_counter = (int32_t*)(p + off);
+        off += align256((size_t)4 * kFfnSplitUnits * 4);
+        w.split_partial = (float*)(p + off);
+        off += align256((size_t)kFfnSplitUnits * (kFfnTileM + kFfnTileSmall) * 256 * 4);
     }
     w.bytes = off;
     return w;

@@ -60,24 +60,31 @@ struct RouteWorkspace {
 RouteWorkspace route_workspace(const moe_desc_t& d, void* base);
 
 // Workspace layout of moe_grouped_ffn.
-constexpr int kFfnMaxUnits = 1024;  // upper bound on compute units (short row tiles of a converted last round)
+// Big work items left over after an XCD's last full round are cut along K into units that run side by side.
+constexpr int kFfnSplitUnits = 256;      // most units of cut items in one launch (32 per XCD), also most cut items
+constexpr int kFfnSplitMaxSlices = 8;    // most units per item
+constexpr int kFfnSplitMinSlabs = 16;    // fewest 64-wide K slabs per unit
+constexpr int kFfnSplitMinK = 128;       // GEMMs with fewer K slabs are never cut: a unit costs a fixed ~30 us on top of
+                                         // its slabs (partial tile out, ticket, the sum), an item of 64 slabs only 100 us
 struct TileList {
     int32_t* expert;  // [max_tiles]
     int32_t* row0;    // [max_tiles] first row of the tile
     int32_t* rows;    // [max_tiles] valid rows in the tile
     int32_t* count;   // [1]
     int max_tiles;    // capacity of the arrays
-    int max_launch;   // most tiles a launch can find in the list, per column block, without a converted last
-                      // round (with one, a GEMM has at most one short item per compute unit)
+    int max_launch;   // most tiles a launch can find in the list, per column block
     int tile_m;
 };
 struct FfnWorkspace {
     void* hidden;    // [P_max, h] activations silu(gate)*up in desc->dtype
     TileList big;    // full-height row tiles, and remainders above small_max rows
     TileList small;  // short row tiles covering remainders of at most small_max rows (bf16 only)
-    TileList big_down, small_down;  // the same for the second GEMM (bf16 only): a nearly empty last round of
-                                    // big items is cut into short tiles, and that depends on the GEMM's width
     int small_max;
+    int32_t* split_hdr;      // [2 GEMMs][4]: big items per XCD that are cut along K and units per item, the same
+                             // for the short items (bf16 only)
+    int32_t* split_counter;  // [2 GEMMs][2][kFfnSplitUnits] one ticket per cut item (big, short)
+    float* split_partial;    // [kFfnSplitUnits][256 x 256] fp32 partial tiles of big items, then
+                             // [kFfnSplitUnits][64 x 256] of short ones (the GEMMs run one after the other)
     size_t bytes;
 };
 FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base);

@@ -16,6 +16,13 @@
 
 #include "common.h"
 
+#ifndef FFN_STAGGER
+#define FFN_STAGGER 1
+#endif
+#ifndef FFN_SPLITK
+#define FFN_SPLITK 1
+#endif
+
 namespace capmoe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -25,17 +32,27 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 // ---------------------------------------------------------------------------------------------
 // Expert e with c rows gets floor(c / big) full tiles; a remainder above small_max rows becomes one
 // more (partly filled) big tile, a smaller one is cut into ceil(remainder / small) short tiles, which
-// a kernel with a deeper load pipeline serves (few rows per weight byte: memory-bound work).
+// run the same loop on 64-row blocks (few rows per weight byte: memory-bound work).
 //
-// A GEMM runs its big work items (row tiles x column blocks) in rounds of one item per compute unit.
-// When the last round would be nearly empty, its row tiles are handed to the short-tile kernel
-// instead, as 64-row pieces: a piece costs about 0.6 of a big item and all of them run at once, where
-// the few big items would have held the whole launch for a full item time.  The rule needs the
-// column-block count of the GEMM, so each of the two GEMMs gets its own pair of lists.
+// A GEMM runs its big work items (row tiles x column blocks) in rounds of one item per compute unit, and
+// every XCD (an eighth of the compute units with an L2 of its own) gets a contiguous eighth of them.  The
+// items left over after an XCD's last full round would hold that XCD for a whole item time with most of
+// its compute units idle, so each of them is cut along K into `slices` units that run side by side: a unit
+// multiplies its share of the K slabs and writes its fp32 partial tile to the workspace, and the unit of an
+// item that finishes last (an integer ticket per item) adds the partial tiles in slice order and writes the
+// output tile: no floating-point atomics, the same bits run to run.  The cut depends on the GEMM's
+// column-block count and K, so each of the two GEMMs gets its own header.
+struct SplitArgs {
+    int32_t* hdr;      // [4]: big items per XCD that are cut (taken from the end of the XCD's share) and units per
+                       // item, then the same for the short items
+    int32_t* counter;  // [2 * kFfnSplitUnits] tickets (big, short), zeroed here before every launch
+    int ncol_big;      // column blocks of the GEMM's big items; 0: never cut
+    int ncol_small;    // column blocks of its short items
+    int slabs;         // K slabs of the GEMM
+};
 struct TileListArgs {
     int32_t *b_expert, *b_row0, *b_rows, *b_count, *s_expert, *s_row0, *s_rows, *s_count;
     int b_max, s_max;
-    int ncol;  // column blocks of the GEMM's big items; 0: never convert
 };
 
 struct ExpertTiles {
@@ -54,122 +71,101 @@ __device__ inline ExpertTiles expert_tiles(int lo, int hi, int big_sh, int small
     return t;
 }
 
-// inclusive scan of three counters over the wave
-__device__ inline void wave_scan3(int& a, int& b, int& c) {
+// inclusive scan of two counters over the wave
+__device__ inline void wave_scan2(int& a, int& b) {
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-        const int oa = __shfl_up(a, off, kWave), ob = __shfl_up(b, off, kWave), oc = __shfl_up(c, off, kWave);
+        const int oa = __shfl_up(a, off, kWave), ob = __shfl_up(b, off, kWave);
         if (lane >= off) {
             a += oa;
             b += ob;
-            c += oc;
         }
     }
 }
 
-__global__ __launch_bounds__(128) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big_sh,
-                                                          int small_sh, int small_max, int cus, TileListArgs first,
-                                                          TileListArgs second) {
-    // two waves: each builds the pair of lists of one GEMM (both need the same counts and compute them alike)
-    const int lane = threadIdx.x & (kWave - 1), which = threadIdx.x >> 6;
+// How an XCD's share of `items_per_xcd` big items is cut: the last `cut` of them into `slices` units each.
+// cus_per_xcd compute units run one item each per round; a unit keeps at least kFfnSplitMinSlabs slabs.
+__host__ __device__ inline void split_rule(int items_per_xcd, int cus_per_xcd, int slabs, int& cut, int& slices) {
+    cut = 0;
+    slices = 1;
+    if (items_per_xcd <= 0 || cus_per_xcd <= 0 || slabs < kFfnSplitMinK) return;
+    if (cus_per_xcd > kFfnSplitUnits / 8) cus_per_xcd = kFfnSplitUnits / 8;
+    const int left = items_per_xcd % cus_per_xcd;
+    if (left == 0) return;
+    int s = cus_per_xcd / left;
+    if (s > kFfnSplitMaxSlices) s = kFfnSplitMaxSlices;
+    if (s > slabs / kFfnSplitMinSlabs) s = slabs / kFfnSplitMinSlabs;
+    if (s < 2) return;
+    cut = left;
+    slices = s;
+}
+
+__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big_sh,
+                                                         int small_sh, int small_max, int cus, TileListArgs L,
+                                                         SplitArgs first, SplitArgs second) {
+    const int lane = threadIdx.x & (kWave - 1);
     const int big = 1 << big_sh, small = 1 << small_sh;
     // Every lane's experts, fetched once, and one scan per 64 experts: the kernel is a chain of latencies
     // (a dependent global load costs a microsecond, a wave scan half of one), so nothing is done twice.
     constexpr int kChunks = kMaxExperts / kWave;
-    ExpertTiles t[kChunks];
-    int start_b[kChunks], start_s[kChunks];  // index of the lane's first tile in either list
     int nt_b = 0, nt_s = 0;
-    {
-        int lo[kChunks], hi[kChunks];
+    int lo[kChunks], hi[kChunks];
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
-            const int e = c * kWave + lane;
-            lo[c] = e < E ? expert_offset[e] : 0;
-            hi[c] = e < E ? expert_offset[e + 1] : 0;
+    for (int c = 0; c < kChunks; ++c) {
+        const int e = c * kWave + lane;
+        lo[c] = e < E ? expert_offset[e] : 0;
+        hi[c] = e < E ? expert_offset[e + 1] : 0;
+    }
+    // tickets of both GEMMs start at zero
+    for (int i = lane; i < 2 * kFfnSplitUnits; i += kWave) {
+        if (first.counter) first.counter[i] = 0;
+        if (second.counter) second.counter[i] = 0;
+    }
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+        if (c * kWave >= E) continue;  // the same for every lane
+        const int e = c * kWave + lane;
+        const ExpertTiles x = expert_tiles(lo[c], hi[c], big_sh, small_sh, small_max);
+        int ib = x.nb, is = x.ns;
+        wave_scan2(ib, is);
+        const int start_b = nt_b + ib - x.nb, start_s = nt_s + is - x.ns;
+        nt_b += __shfl(ib, kWave - 1, kWave);
+        nt_s += __shfl(is, kWave - 1, kWave);
+        for (int i = 0; i < x.nb; ++i) {
+            const int idx = start_b + i;
+            const int left = x.rows - i * big;
+            if (idx < L.b_max) {
+                L.b_expert[idx] = e;
+                L.b_row0[idx] = x.lo + i * big;
+                L.b_rows[idx] = left < big ? left : big;
+            }
         }
-#pragma unroll
-        for (int c = 0; c < kChunks; ++c) {
-            t[c] = expert_tiles(lo[c], hi[c], big_sh, small_sh, small_max);
-            start_b[c] = start_s[c] = 0;
-            if (c * kWave >= E) continue;  // the same for every lane
-            int ib = t[c].nb, is = t[c].ns, unused = 0;
-            wave_scan3(ib, is, unused);
-            start_b[c] = nt_b + ib - t[c].nb;
-            start_s[c] = nt_s + is - t[c].ns;
-            nt_b += __shfl(ib, kWave - 1, kWave);
-            nt_s += __shfl(is, kWave - 1, kWave);
+        const int full = x.rows >> big_sh, rem = x.rows - (full << big_sh);
+        for (int i = 0; i < x.ns; ++i) {
+            const int idx = start_s + i;
+            if (idx < L.s_max) {
+                L.s_expert[idx] = e;
+                L.s_row0[idx] = x.lo + full * big + i * small;
+                const int left = rem - i * small;
+                L.s_rows[idx] = left < small ? left : small;
+            }
         }
     }
-    const int pieces = 1 << (big_sh - small_sh);
-    {
-        const TileListArgs& L = which == 0 ? first : second;
-        if (which == 1 && second.b_expert == first.b_expert) return;  // one pair of lists serves both GEMMs
-        // big row tiles of the nearly empty last round, if their pieces fit into one round of short items
-        int conv = 0;
-        const long long items = (long long)nt_b * L.ncol;
-        if (L.ncol > 0 && cus > 0 && items >= cus && items < (1ll << 31)) {
-            const unsigned rem = (unsigned)items % (unsigned)cus;
-            if (rem > 0) {
-                int c = (int)((rem + (unsigned)L.ncol - 1u) / (unsigned)L.ncol);
-                c = c > nt_b ? nt_b : c;
-                if ((long long)(nt_s + pieces * c) * L.ncol <= cus) conv = c;
+    if (lane == 0) {
+        const int nb = nt_b < L.b_max ? nt_b : L.b_max, ns = nt_s < L.s_max ? nt_s : L.s_max;
+        *L.b_count = nb;
+        *L.s_count = ns;
+        for (const SplitArgs* sp : {&first, &second}) {
+            if (!sp->hdr) continue;
+            const long long items[2] = {(long long)nb * sp->ncol_big, (long long)ns * sp->ncol_small};
+            for (int which = 0; which < 2; ++which) {
+                int cut = 0, slices = 1;
+                if (items[which] > 0 && items[which] < (1ll << 30))
+                    split_rule((int)((items[which] + 7) >> 3), cus >> 3, sp->slabs, cut, slices);
+                sp->hdr[2 * which] = cut;
+                sp->hdr[2 * which + 1] = slices;
             }
-        }
-        const int first_conv = nt_b - conv;  // big tiles from this index on are cut into pieces
-        int base_p = nt_s;                   // the pieces follow the regular short tiles
-#pragma unroll
-        for (int ch = 0; ch < kChunks; ++ch) {
-            if (ch * kWave >= E) continue;
-            const int e = ch * kWave + lane;
-            const ExpertTiles& x = t[ch];
-            int p = 0;
-            if (conv > 0) {  // where this expert's pieces go: a scan over the pieces of the converted tiles
-                int ip = 0, d1 = 0, d2 = 0;
-                for (int i = 0; i < x.nb; ++i)
-                    if (start_b[ch] + i >= first_conv) {
-                        const int left = x.rows - i * big;
-                        ip += ((left < big ? left : big) + small - 1) >> small_sh;
-                    }
-                const int np = ip;
-                wave_scan3(ip, d1, d2);
-                p = base_p + ip - np;
-                base_p += __shfl(ip, kWave - 1, kWave);
-            }
-            for (int i = 0; i < x.nb; ++i) {
-                const int idx = start_b[ch] + i;
-                const int left = x.rows - i * big;
-                const int rows = left < big ? left : big;
-                if (idx < first_conv) {
-                    if (idx < L.b_max) {
-                        L.b_expert[idx] = e;
-                        L.b_row0[idx] = x.lo + i * big;
-                        L.b_rows[idx] = rows;
-                    }
-                } else {
-                    for (int r = 0; r < rows; r += small, ++p)
-                        if (p < L.s_max) {
-                            L.s_expert[p] = e;
-                            L.s_row0[p] = x.lo + i * big + r;
-                            L.s_rows[p] = rows - r < small ? rows - r : small;
-                        }
-                }
-            }
-            const int full = x.rows >> big_sh, rem = x.rows - (full << big_sh);
-            for (int i = 0; i < x.ns; ++i) {
-                const int idx = start_s[ch] + i;
-                if (idx < L.s_max) {
-                    L.s_expert[idx] = e;
-                    L.s_row0[idx] = x.lo + full * big + i * small;
-                    const int left = rem - i * small;
-                    L.s_rows[idx] = left < small ? left : small;
-                }
-            }
-        }
-        if (lane == 0) {
-            const int nb = nt_b - conv, ns = base_p;
-            *L.b_count = nb < L.b_max ? nb : L.b_max;
-            *L.s_count = ns < L.s_max ? ns : L.s_max;
         }
     }
 }
@@ -291,18 +287,20 @@ struct PipelinedLoop16 {
     uint8_t* smem;
     const FillsT& fills;
     int a_lane, b_lane;  // byte offset, inside a slot, of this lane's piece of the wave's first row (k-step 0)
-    int KT, wv;
+    int KT, wv;  // slabs this block multiplies, wave index
+    int k0;      // first of them (0 unless the item is cut along K)
 
     // byte offset of weight sub-tile i relative to the wave's first weight row: with SwiGLU the second half
     // of the sub-tiles are the up-projection rows of the same hidden columns
     static __device__ __forceinline__ constexpr int b_tile(int i) {
         return SWIGLU ? ((i / (TN / 2)) * (BN / 2) + (i % (TN / 2)) * 16) * 128 : i * 16 * 128;
     }
+    __device__ __forceinline__ uint32_t k_bytes(int kt) const { return (uint32_t)(kt + k0) * (BK * 2); }
     __device__ __forceinline__ void fill_a(int i, int kt) const {
-        fills.one(i, smem + (kt & 1) * A_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+        fills.one(i, smem + (kt & 1) * A_SLOT + (wv + NW * i) * 1024, k_bytes(kt));
     }
     __device__ __forceinline__ void fill_b(int i, int kt, int slot) const {
-        fills.one(A_LOADS + i, smem + B_BASE + slot * B_SLOT + (wv + NW * i) * 1024, (uint32_t)kt * (BK * 2));
+        fills.one(A_LOADS + i, smem + B_BASE + slot * B_SLOT + (wv + NW * i) * 1024, k_bytes(kt));
     }
     __device__ __forceinline__ void fill_a_all(int kt) const {
 #pragma unroll
@@ -313,7 +311,12 @@ struct PipelinedLoop16 {
         for (int i = 0; i < B_LOADS; ++i) fill_b(i, kt, slot);
     }
 
-    template <int LIVE>
+    // PHASE (0..3): where in a k-step this wave places its fill requests.  The four waves leave every barrier
+    // together and run the same instruction stream; with the same placement they would hand their requests to
+    // the address unit in the same few cycles, its queue fills, and the waves that wait cannot issue their
+    // next matrix instruction.  Each wave therefore shifts its requests by a different number of matrix
+    // instructions.
+    template <int LIVE, int PHASE = 0>
     __device__ __forceinline__ void run(f32x4 (&acc)[TN][TM]) const {
         fill_a_all(0);
         fill_b_all(0, 0);
@@ -337,7 +340,15 @@ struct PipelinedLoop16 {
         // reads go out in the first half of a k-step, so that they have returned long before the barrier
         constexpr int READ_EVERY = NMFMA / 2 / NREAD > 0 ? NMFMA / 2 / NREAD : 1;
         constexpr int B_EVERY = NMFMA / B_LOADS > 0 ? NMFMA / B_LOADS : 1;
+#if FFN_STAGGER
+        constexpr int A_EVERY = NMFMA / A_LOADS > 0 ? NMFMA / A_LOADS : 1;
+        constexpr int B_OFF = PHASE * B_EVERY / 4 + (B_EVERY >= 8 ? B_EVERY / 8 : 0);
+        constexpr int A_OFF = PHASE * A_EVERY / 4 + (A_EVERY >= 8 ? A_EVERY / 8 : 0);
+#else
         constexpr int A_EVERY = NMFMA / 2 / A_LOADS > 0 ? NMFMA / 2 / A_LOADS : 1;
+        constexpr int B_OFF = B_EVERY / 2, A_OFF = A_EVERY / 2;
+#endif
+        static_assert(B_OFF < B_EVERY && A_OFF < A_EVERY, "request placement");
         static_assert(LIVE == 0 || (NMFMA >= NREAD * READ_EVERY && NMFMA >= B_LOADS && NMFMA >= A_LOADS * A_EVERY), "k-step too short");
         bf16x8 xa[2][NL], wb[2][TN];
 
@@ -373,7 +384,7 @@ struct PipelinedLoop16 {
                     const int j = q / TN, i = q % TN;
                     mfma_16x16x32(acc[i][j], wb[0][i], xa[0][j]);
                     if (q % READ_EVERY == 0 && q / READ_EVERY < NREAD) read_item(q / READ_EVERY, 1, pa, pb);
-                    if (REFILL && q % B_EVERY == B_EVERY / 2 && q / B_EVERY < B_LOADS) fill_b(q / B_EVERY, kt + 2, slot2);
+                    if (REFILL && q % B_EVERY == B_OFF && q / B_EVERY < B_LOADS) fill_b(q / B_EVERY, kt + 2, slot2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -393,7 +404,7 @@ struct PipelinedLoop16 {
                     const int j = q / TN, i = q % TN;
                     mfma_16x16x32(acc[i][j], wb[1][i], xa[1][j]);
                     if (MORE && q % READ_EVERY == 0 && q / READ_EVERY < NREAD) read_item(q / READ_EVERY, 0, pa, pb);
-                    if (REFILL && q % A_EVERY == A_EVERY / 2 && q / A_EVERY < A_LOADS) fill_a(q / A_EVERY, kt + 2);
+                    if (REFILL && q % A_EVERY == A_OFF && q / A_EVERY < A_LOADS) fill_a(q / A_EVERY, kt + 2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -413,6 +424,14 @@ struct PipelinedLoop16 {
         // the last matrix instructions retire before anything else reads the accumulators
         asm volatile("s_nop 15\n\ts_nop 15");
     }
+};
+
+// A block's place among the units of an item that is cut along K (slices == 1: the whole item).
+struct SplitUnit {
+    int slices, slice;
+    int stride;      // units between consecutive slices of one item
+    float* partial;  // slice 0 of this item
+    int* counter;    // this item's ticket
 };
 
 // Block tile of BM activation rows x BN weight rows over 64-wide K slabs, WAVES_M x WAVES_N waves, on the
@@ -440,7 +459,7 @@ struct TileConfig16 {
     static __device__ __forceinline__ void run(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
                                                const uint16_t* __restrict__ B1, uint16_t* __restrict__ C,
                                                const int32_t* __restrict__ gather, int e, int row0, int rows, int n0,
-                                               int K, int Nout, uint8_t* smem) {
+                                               int K, int Nout, uint8_t* smem, const SplitUnit& split) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 16, TN = WTN / 16;
@@ -505,10 +524,26 @@ struct TileConfig16 {
 
     using Loop = PipelinedLoop16<BM, BN, NW, TM, TN, WTN, SWIGLU, LOADS, FillsT>;
     static_assert(Loop::LDS_BYTES == kLdsBytes, "LDS size");
-    Loop loop{smem, fills, a_lane, b_lane, K / 64, __builtin_amdgcn_readfirstlane(wv)};
+    // this block's share of the K slabs: all of them, or slice `split.slice` of `split.slices`
+    const int slabs_all = K / 64;
+    const int k_first = split.slices > 1 ? (int)((long long)split.slice * slabs_all / split.slices) : 0;
+    const int k_end = split.slices > 1 ? (int)((long long)(split.slice + 1) * slabs_all / split.slices) : slabs_all;
+    Loop loop{smem, fills, a_lane, b_lane, k_end - k_first, __builtin_amdgcn_readfirstlane(wv), k_first};
+#if FFN_STAGGER
+    if (live == TM) {
+        switch (loop.wv & 3) {
+            case 0: loop.template run<TM, 0>(acc); break;
+            case 1: loop.template run<TM, 1>(acc); break;
+            case 2: loop.template run<TM, 2>(acc); break;
+            default: loop.template run<TM, 3>(acc); break;
+        }
+    } else if
+#else
     if (live == TM)
         loop.template run<TM>(acc);
-    else if (TM > 6 && live == 6)
+    else if
+#endif
+ (TM > 6 && live == 6)
         loop.template run<(TM > 6 ? 6 : TM)>(acc);
     else if (TM > 4 && live == 4)
         loop.template run<(TM > 4 ? 4 : TM)>(acc);
@@ -516,6 +551,69 @@ struct TileConfig16 {
         loop.template run<(TM > 2 ? 2 : TM)>(acc);
     else
         loop.template run<0>(acc);
+
+    // ---- an item cut along K: partial tiles through the workspace, the last unit to finish adds them ----
+    // The units of an item may run on different XCDs, whose L2 caches do not see each other's lines.  A fence
+    // that writes back and invalidates a whole L2 per unit costs more than the cut saves, so the partial tiles
+    // are stored and loaded with device-scope cache policy instead (written through to memory, read around
+    // caches that may be stale), each store is acknowledged before the ticket is taken, and the ticket is a
+    // device-scope atomic.
+    if (split.slices > 1) {
+        // a unit's partial tile is stored in register order (fragment, lane): whole 1 KB lines per wave store
+        constexpr int FRAGS = TN * TM;
+        constexpr int kDeviceScope = 16;  // cache policy bit sc1 of the buffer instructions
+        const size_t unit_floats = (size_t)BM * BN;
+        typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+        const uint32_t at = (uint32_t)((wv * FRAGS * 64 + lane) * 16);  // + fragment * 1024 bytes
+        {
+            const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(split.partial + (size_t)(split.slice * split.stride) * unit_floats), 0, -1, kRsrcFlags);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    const f32x4 v = acc[i][j];
+                    __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)&v, mine, at + (i * TM + j) * 1024, 0, kDeviceScope);
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));  // every store of this lane has been acknowledged
+        __syncthreads();
+        int* ticket = (int*)smem;  // the operand slots are free: the loop's last barrier follows its last read
+        if (tid == 0) *ticket = __hip_atomic_fetch_add(split.counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int order = *ticket;
+        __syncthreads();
+        if (order != split.slices - 1) return;  // another unit of this item finishes later and does the sum
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+        for (int sl = 0; sl < split.slices; ++sl) {  // slice order, whichever unit does it: the same sum every run
+            const __amdgpu_buffer_rsrc_t theirs = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)(split.partial + (size_t)(sl * split.stride) * unit_floats), 0, -1, kRsrcFlags);
+            // up to 32 loads in flight at a time: a load that goes around the caches takes microseconds
+            constexpr int BATCH = FRAGS < 32 ? FRAGS : 32;
+            static_assert(FRAGS % BATCH == 0, "fragment batches");
+#pragma unroll
+            for (int g = 0; g < FRAGS; g += BATCH) {
+                u32x4 q[BATCH];
+#pragma unroll
+                for (int t = 0; t < BATCH; ++t)
+                    q[t] = __builtin_amdgcn_raw_buffer_load_b128(theirs, at + (g + t) * 1024, 0, kDeviceScope);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < BATCH; ++t) {
+                    const f32x4 p = *(const f32x4*)&q[t];
+                    const int i = (g + t) / TM, j = (g + t) % TM;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[i][j][v] += p[v];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
 
     // ---- epilogue ----
     // The tile is transposed through LDS (free after the K loop: its last barrier follows the last operand
@@ -572,8 +670,11 @@ __device__ inline void decode_item(int logical, int nt, int col_group, int& tile
 }
 
 // One launch serves both tile lists.  Every XCD (block id mod 8) gets a contiguous eighth of the
-// big tiles, then a contiguous eighth of the small tiles: long blocks first, short ones fill the
-// tail, and blocks that run together on an XCD share row and weight tiles in its L2.
+// big items, then a contiguous eighth of the small items: long blocks first, short ones fill the
+// tail, and blocks that run together on an XCD share row and weight tiles in its L2.  The last
+// split[0] big items of an XCD's share run as split[1] units each (see the tile schedule); the units
+// follow the XCD's whole items in launch order, slice by slice, so that the units that run together
+// read the same K range of the tiles they share.
 template <class Big, class Small, bool SWIGLU>
 __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
@@ -581,24 +682,65 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const int32_t* __restrict__ b_row0,
     const int32_t* __restrict__ b_rows, const int32_t* __restrict__ b_count, const int32_t* __restrict__ s_expert,
     const int32_t* __restrict__ s_row0, const int32_t* __restrict__ s_rows, const int32_t* __restrict__ s_count, int K,
-    int Nout, int col_group_big, int col_group_small) {
+    int Nout, int col_group_big, int col_group_small, const int32_t* __restrict__ split_hdr, float* split_partial,
+    int32_t* split_counter) {
     static_assert(Big::kThreads == Small::kThreads, "one block size");
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int nt_b = *b_count, nt_s = *s_count;
     const int total_b = nt_b * (Nout / Big::kNCols), total_s = nt_s * (Nout / Small::kNCols);
     const int chunk_b = (total_b + 7) >> 3, chunk_s = (total_s + 7) >> 3;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int cut = split_hdr ? split_hdr[0] : 0, slices = split_hdr ? split_hdr[1] : 1;
+    const int cut_s = split_hdr ? split_hdr[2] : 0, slices_s = split_hdr ? split_hdr[3] : 1;
+    // per XCD: whole big items, whole short items, then the units of the cut big items and of the cut short ones
+    // (longest work first, the shortest pieces fill the end)
+    const int whole = chunk_b - cut, units = cut * slices, whole_s = chunk_s - cut_s, units_s = cut_s * slices_s;
+    const int xcd = blockIdx.x & 7;
+    int slot = blockIdx.x >> 3;
     int tile, nb;
-    if (slot < chunk_b) {
+    const SplitUnit one{1, 0, 0, nullptr, nullptr};
+    constexpr int per_xcd = kFfnSplitUnits / 8;
+    if (slot < whole) {
         const int logical = xcd * chunk_b + slot;
         if (logical >= total_b) return;
         decode_item(logical, nt_b, col_group_big, tile, nb);
-        Big::run(A, B0, B1, C, gather, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem);
-    } else if (slot - chunk_b < chunk_s) {
-        const int logical = xcd * chunk_s + (slot - chunk_b);
+        Big::run(A, B0, B1, C, gather, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem, one);
+        return;
+    }
+    slot -= whole;
+    if (slot < whole_s) {
+        const int logical = xcd * chunk_s + slot;
         if (logical >= total_s) return;
         decode_item(logical, nt_s, col_group_small, tile, nb);
-        Small::run(A, B0, B1, C, gather, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem);
+        Small::run(A, B0, B1, C, gather, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem,
+                   one);
+        return;
+    }
+    slot -= whole_s;
+    if (slot < units) {
+        // unit (xcd, slice, idx) keeps its partial tile at unit index xcd * units-per-XCD + slice * cut + idx
+        const int slice = slot / cut, idx = slot - slice * cut;
+        const int logical = xcd * chunk_b + whole + idx;
+        if (logical >= total_b) return;
+        decode_item(logical, nt_b, col_group_big, tile, nb);
+        const SplitUnit su{slices, slice, cut,
+                           split_partial + (size_t)(xcd * per_xcd + idx) * ((size_t)Big::kBM * Big::kBN),
+                           split_counter + xcd * per_xcd + idx};
+        Big::run(A, B0, B1, C, gather, b_expert[tile], b_row0[tile], b_rows[tile], nb * Big::kNCols, K, Nout, smem, su);
+        return;
+    }
+    slot -= units;
+    if (slot < units_s) {
+        const int slice = slot / cut_s, idx = slot - slice * cut_s;
+        const int logical = xcd * chunk_s + whole_s + idx;
+        if (logical >= total_s) return;
+        decode_item(logical, nt_s, col_group_small, tile, nb);
+        // the short items' partial tiles follow those of the big items
+        float* region = split_partial + (size_t)kFfnSplitUnits * kFfnTileM * 256;
+        const SplitUnit su{slices_s, slice, cut_s,
+                           region + (size_t)(xcd * per_xcd + idx) * ((size_t)Small::kBM * Small::kBN),
+                           split_counter + kFfnSplitUnits + xcd * per_xcd + idx};
+        Small::run(A, B0, B1, C, gather, s_expert[tile], s_row0[tile], s_rows[tile], nb * Small::kNCols, K, Nout, smem,
+                   su);
     }
 }
 
@@ -610,7 +752,8 @@ static int column_group(int nb_total) {
 
 template <class Big, class Small, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const int32_t* gather,
-                        const TileList& big, const TileList& small, int K, int Nout, hipStream_t st) {
+                        const TileList& big, const TileList& small, int K, int Nout, const int32_t* split_hdr,
+                        float* split_partial, int32_t* split_counter, hipStream_t st) {
     constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
     auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
     static std::atomic<uint64_t> configured{0};
@@ -618,13 +761,12 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
-    // a converted last round adds at most one short item per compute unit; + 16: both lists are cut into
-    // eight whole chunks
-    const long long grid = (long long)nb_b * big.max_launch + (long long)nb_s * small.max_launch + kFfnMaxUnits + 16;
+    // items cut along K add at most kFfnSplitUnits blocks per list; + 16: both lists are cut into eight whole chunks
+    const long long grid = (long long)nb_b * big.max_launch + (long long)nb_s * small.max_launch + 2 * kFfnSplitUnits + 16;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
                        (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, big.expert, big.row0, big.rows,
                        big.count, small.expert, small.row0, small.rows, small.count, K, Nout,
-                       column_group(nb_b), column_group(nb_s));
+                       column_group(nb_b), column_group(nb_s), split_hdr, split_partial, split_counter);
 }
 
 // row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
@@ -637,39 +779,44 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
     const bool bf16 = d.dtype == MOE_DTYPE_BF16;
     const int bn_down = N2 % 256 == 0 ? 256 : 128;  // d is a multiple of 128 at least: output columns per block
     {
-        auto args = [](const TileList& b, const TileList& sm, int ncol) {
-            return TileListArgs{b.expert, b.row0, b.rows, b.count, sm.expert, sm.row0, sm.rows, sm.count,
-                                b.max_tiles, sm.max_tiles, ncol};
-        };
         const int cus = compute_units();
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
-        // gate/up: a big item covers 128 hidden columns (gate and up rows of them); fp32: one pair of lists, as cut
-        const TileListArgs gu = args(ws.big, ws.small, bf16 ? N1 / 128 : 0);
-        const TileListArgs dn = bf16 ? args(ws.big_down, ws.small_down, N2 / bn_down) : gu;
+        const TileListArgs lists{ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count, ws.small.expert, ws.small.row0,
+                                 ws.small.rows, ws.small.count, ws.big.max_tiles, ws.small.max_tiles};
+        // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
+        const bool split = bf16 && FFN_SPLITK;
+        const SplitArgs gu{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
+        const SplitArgs dn{split ? ws.split_hdr + 4 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
+                           N2 / bn_down, N2 / bn_down, K2 / 64};
         auto log2i = [](int v) {
             int sh = 0;
             while ((1 << sh) < v) ++sh;
             return sh;
         };
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(128), 0, st, expert_offset, d.n_experts,
-                           log2i(ws.big.tile_m), log2i(ws.small.tile_m), ws.small_max, cus, gu, dn);
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts,
+                           log2i(ws.big.tile_m), log2i(ws.small.tile_m), ws.small_max, cus, lists, gu, dn);
     }
     if (bf16) {
+        const int32_t* split_gu = FFN_SPLITK ? ws.split_hdr : nullptr;
+        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 4 : nullptr;
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig16<kFfnTileSmall, 256, 1, 4, true>,
-                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws.big, ws.small, K1, N1, st);
+                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws.big, ws.small, K1, N1, split_gu, ws.split_partial,
+                              ws.split_counter, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         if (bn_down == 256)
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, false>,
                         TileConfig16<kFfnTileSmall, 256, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
-                                                                                    ws.big_down, ws.small_down, K2, N2, st);
+                                                                                    ws.big, ws.small, K2, N2, split_dn, ws.split_partial,
+                                                                                    ws.split_counter + 2 * kFfnSplitUnits, st);
         else
             launch_bf16<TileConfig16<kFfnTileM, 128, 2, 2, false>,
                         TileConfig16<kFfnTileSmall, 128, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
-                                                                                    ws.big_down, ws.small_down, K2, N2, st);
+                                                                                    ws.big, ws.small, K2, N2, split_dn, ws.split_partial,
+                                                                                    ws.split_counter + 2 * kFfnSplitUnits, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);
         {

@@ -505,9 +505,8 @@ def test_ffn_ragged_expert_sizes(orc):
 
 
 def test_ffn_nearly_empty_last_round(orc):
-    """67 full-height row tiles x 4 column blocks of the down GEMM = 268 work items on 256 compute units: the row
-    tiles of the 12-item last round (two full ones and a 100-row one) run as 64-row pieces instead.  The gate/up
-    GEMM (2 column blocks, 134 items) keeps its tiles: the two GEMMs walk different lists."""
+    """67 full-height row tiles x 4 column blocks of the down GEMM = 268 work items on 256 compute units: a last
+    round of 12 items (K is short here, so they stay whole)."""
     counts = [40 * 256 + 30, 20 * 256, 6 * 256 + 100, 17]
     e, n = len(counts), sum(counts)
     w = synth.scaled(W["olmoe"], name="tail", n_tokens=n, d_model=1024, n_experts=e, top_k=1, d_hidden=256,
@@ -523,6 +522,39 @@ def test_ffn_nearly_empty_last_round(orc):
     assert_plan_equal(buf, ref, "tail")
     y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
     assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "tail")
+
+
+@pytest.mark.parametrize("d,h,counts", [
+    (128, 8192, [5 * 256 + 70, 3 * 256, 40]),        # down GEMM: 128 K slabs, 128-column output tiles, 9 big items and one short
+    (256, 8192, [256, 300, 17, 0, 2 * 256 + 64]),    # 256-column output tiles; two short items
+    (8192, 128, [700, 64]),                          # gate/up GEMM with 128 K slabs: SwiGLU tiles are cut
+])
+def test_ffn_items_cut_along_k(orc, d, h, counts):
+    """Work items left over after the last full round of a long-K GEMM run as several units, each over a share of
+    the K slabs, and the unit that finishes last adds the partial tiles in slice order: with so few items every
+    one of them is cut (eight units each).  Same tolerance as whole items, and the same bits on every run."""
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="cut", n_tokens=n, d_model=d, n_experts=e, top_k=1, d_hidden=h, device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    np.random.default_rng(21).shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    desc = layer.desc(NONE, GLOBAL, 1.0)
+    buf = run_layer(layer, desc, logits)
+    assert_plan_equal(buf, ref, "cut")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "cut along K")
+    for _ in range(3):
+        again = run_layer(layer, desc, logits)
+        assert torch.equal(again.yp[:n], buf.yp[:n]) and torch.equal(again.y, buf.y)
+    fused = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(fused, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         torch.from_numpy(logits).cuda(), fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.y, buf.y)
 
 
 def test_ffn_many_experts(orc):

@@ -43,7 +43,7 @@ def test_per_device_launches_compute_the_rows_of_the_full_call(mixtral, mode):
     """bench.py times each simulated device's experts as a layer call of its own on a slice of the plan (Eq. 4:
     the slowest device sets the pace).  Every row such a launch writes must be the row the full call writes.
     The two launches may cut the K dimension of their last work items differently (a split sum is added in
-    another order), so rows agree to the last bf16 digit, and nearly all of them bit for bit."""
+    another order), so values agree to the last bf16 digit, and nearly all of them bit for bit."""
     w, layer, t = mixtral
     desc = layer.desc(mode, LOCAL, 1.0)
     buf = capmoe.LayerBuffers(desc)
@@ -63,9 +63,11 @@ def test_per_device_launches_compute_the_rows_of_the_full_call(mixtral, mode):
         got, ref = buf.yp[r0:r1].float(), full[r0:r1].float()
         assert torch.equal(buf.yp[:r0], full[:r0]) and torch.equal(buf.yp[r1:rows], full[r1:rows])  # nothing else written
         assert torch.isfinite(got).all()
-        ulp = torch.maximum(ref.abs(), torch.full_like(ref, 2.0 ** -20)) * 2.0 ** -7      # one bf16 step
-        assert ((got - ref).abs() <= ulp).all()
+        # one bf16 step of the value, plus what another order of the fp32 sum can move a value that cancels
+        bound = ref.abs() * 2.0 ** -7 + ref.abs().amax(dim=1, keepdim=True) * 2.0 ** -14
+        assert ((got - ref).abs() <= bound).all()
         assert (got == ref).float().mean() > 0.99
+        buf.yp[r0:r1].copy_(full[r0:r1])
         covered += r1 - r0
     assert covered == rows
 
