@@ -157,6 +157,11 @@ int moe_route_topk_static(const moe_desc_t* desc, const void* x, const float* w_
  *   pair_row      [N,S]   row of the token's slot-th candidate expert (candidates in ascending
  *                         expert id), or -1 if dropped / slot unused
  * Entries of row_token / row_weight at or beyond P are left untouched.
+ * Preconditions the call does not check (they hold for the outputs of moe_route_topk): every score is the
+ * softmax of Eq. (1), 0 <= s <= 1 and not NaN (candidates are ranked on the bit patterns of their scores, which
+ * order like the values only for non-negative numbers, and the two top bits of a key hold the token class); every
+ * row of topk_idx holds distinct expert ids in [0, E).  scores, topk_idx and pair_row must be 16-byte aligned
+ * (checked: MOE_ERR_INVALID_ARG).
  */
 int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,
                       int32_t* expert_count, int32_t* seg_count, int32_t* expert_offset, int32_t* row_token,

@@ -280,6 +280,8 @@ int moe_capacity_drop_ranked(const moe_desc_t* desc, const float* scores, const 
     if (desc->n_tokens > 0 && (!scores || !topk_idx || !pair_row)) return MOE_ERR_INVALID_ARG;
     if (s.max_rows > 0 && (!row_token || !row_weight)) return MOE_ERR_INVALID_ARG;
     if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    // the kernels fetch top-k lists, score rows and keys in 16-byte pieces
+    if (misaligned16(scores) || misaligned16(topk_idx) || misaligned16(pair_row)) return MOE_ERR_INVALID_ARG;
     const DropWorkspace ws = drop_workspace(*desc, s, workspace);
     if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;

@@ -744,8 +744,11 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     }
 }
 
+#ifndef FFN_COLGROUP_MAX
+#define FFN_COLGROUP_MAX 4
+#endif
 static int column_group(int nb_total) {
-    for (int g = 4; g > 1; --g)
+    for (int g = FFN_COLGROUP_MAX; g > 1; --g)
         if (nb_total % g == 0) return g;
     return 1;
 }
@@ -786,7 +789,7 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
         // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
         const bool split = bf16 && FFN_SPLITK;
         const SplitArgs gu{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
-        const SplitArgs dn{split ? ws.split_hdr + 4 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
+        const SplitArgs dn{split ? ws.split_hdr + 8 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
                            N2 / bn_down, N2 / bn_down, K2 / 64};
         auto log2i = [](int v) {
             int sh = 0;
@@ -798,7 +801,7 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
     }
     if (bf16) {
         const int32_t* split_gu = FFN_SPLITK ? ws.split_hdr : nullptr;
-        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 4 : nullptr;
+        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 8 : nullptr;
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);

@@ -124,3 +124,12 @@ def test_bad_arguments_are_refused_on_the_host():
     f = ctypes.c_void_p(0x1000)
     assert lib.moe_dispatch_ffn(ctypes.byref(big), f, f, f, f, f, f, f, f, 0, z) == 2
     assert lib.moe_grouped_ffn(ctypes.byref(big), f, f, f, f, f, f, f, 0, z) == 3
+    # the drop reads its lists in 16-byte pieces: a misaligned scores / topk_idx / pair_row pointer is refused
+    g = ctypes.c_void_p(0x1004)
+    assert lib.moe_capacity_drop(ctypes.byref(ok), g, f, f, f, f, f, f, f, f, 1 << 30, z) == 1
+    assert lib.moe_capacity_drop(ctypes.byref(ok), f, g, f, f, f, f, f, f, f, 1 << 30, z) == 1
+    assert lib.moe_capacity_drop(ctypes.byref(ok), f, f, f, f, f, f, f, g, f, 1 << 30, z) == 1
+    # the static-scratch router: a descriptor whose partial sums exceed the built-in buffer is refused on the host
+    huge = capmoe.make_desc(4096 * 3, 4096, 256, 8, 1024, dtype=1)
+    assert lib.moe_route_topk_static(ctypes.byref(huge), f, f, z, 0, f, f, f, f, z) == 5
+    assert "scratch" in capmoe.status_string(5)
