@@ -354,14 +354,16 @@ def measured_peaks():
                    "1 GiB device copies (read + written bytes)"}
 
 
-def ffn_uniform(w, reps=9):
+def ffn_uniform(w, reps=9, experts=None, vendor=True):
     """The grouped FFN alone on experts of equal size (N*k/E rows each): what the two GEMM kernels sustain when no
-    tile is ragged, and torch.matmul (the vendor library) on one dense GEMM of the same M, N, K for comparison."""
+    tile is ragged, and torch.matmul (the vendor library) on one dense GEMM of the same M, N, K for comparison.
+    experts=1: all N*k rows on the first expert, i.e. the same kernels with the weight traffic of a dense GEMM
+    (one weight matrix, re-read from the memory-side cache instead of streamed from HBM)."""
     import torch
 
     from paper_2503_05066_amd import capmoe
 
-    e, d, h = w.n_experts, w.d_model, w.d_hidden
+    e, d, h = experts or w.n_experts, w.d_model, w.d_hidden
     m = max(1, w.n_tokens * w.top_k // e)
     rows = m * e
     t = upload(w)
@@ -375,7 +377,7 @@ def ffn_uniform(w, reps=9):
     ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
 
     def run():
-        capmoe.moe_grouped_ffn(desc, xp, off, t["w_gate"], t["w_up"], t["w_down"], yp, ws)
+        capmoe.moe_grouped_ffn(desc, xp, off, t["w_gate"][:e], t["w_up"][:e], t["w_down"][:e], yp, ws)
 
     for _ in range(2):
         run()
@@ -400,7 +402,7 @@ def ffn_uniform(w, reps=9):
         out[name] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1),
                      "frac_of_peak": round(flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
     # the same dimensions as one dense NT GEMM each, through the vendor library
-    for name, (mm, nn, kk) in (("vendor_dense_gate_up", (rows, 2 * h, d)), ("vendor_dense_down", (rows, d, h))):
+    for name, (mm, nn, kk) in (("vendor_dense_gate_up", (rows, 2 * h, d)), ("vendor_dense_down", (rows, d, h))) if vendor else ():
         a_ = torch.randn(mm, kk, device="cuda", generator=gen).to(torch.bfloat16)
         b_ = torch.randn(nn, kk, device="cuda", generator=gen).to(torch.bfloat16)
         for _ in range(2):
@@ -414,8 +416,9 @@ def ffn_uniform(w, reps=9):
         ms = sorted(s0.elapsed_time(s1) for s0, s1 in prs)[reps // 2]
         out[name] = {"ms": round(ms, 4), "TFLOP/s": round(2 * mm * nn * kk / ms / 1e9, 1)}
         del a_, b_, c_
-    out["note"] = ("vendor_dense_*: torch.matmul on ONE dense NT GEMM with the same M, N, K (a single weight matrix, "
-                   "so E times less weight traffic than the grouped GEMM: comparable where the matrix cores bind)")
+    if vendor:
+        out["note"] = ("vendor_dense_*: torch.matmul on ONE dense NT GEMM with the same M, N, K (a single weight matrix, "
+                       "so E times less weight traffic than the grouped GEMM: compare it with the experts=1 entry)")
     return out
 
 
@@ -631,7 +634,11 @@ def main():
                                                     max(5, a.warmup // 4), **common)}
     if not a.no_straggler and w.device_groups > 1:
         out["straggler"] = straggler(w, mode, scope, a.gamma, a.overselect, int(a.max_experts))
-    uniform = [] if a.no_peaks else [ffn_uniform(synth.WORKLOADS[n]) for n in a.ffn_uniform.split(",") if n]
+    uniform = []
+    for n in ([] if a.no_peaks else [n for n in a.ffn_uniform.split(",") if n]):
+        uniform.append(ffn_uniform(synth.WORKLOADS[n]))
+        if synth.WORKLOADS[n].n_experts > 1:
+            uniform.append(ffn_uniform(synth.WORKLOADS[n], experts=1, vendor=False))
     if uniform:
         out["ffn_uniform_experts"] = uniform
     others = []

@@ -8,10 +8,11 @@
 // static upper bound and surplus blocks exit at once.
 //
 // bf16: both operands are K-contiguous ("NT" GEMM), staged through LDS in 16-byte pieces with an
-// XOR swizzle, multiplied on the matrix cores with fp32 accumulation: v_mfma_f32_16x16x32_bf16 in the
-// 256-row tiles (the bulk of the flops), v_mfma_f32_32x32x16_bf16 in the 64-row tiles (weight
-// streaming).  The weight rows feed the MFMA's first operand and the activation rows the second, so a
-// lane ends up with 4 consecutive output columns of one row and stores them as one 8-byte piece.
+// XOR swizzle and multiplied on the matrix cores with fp32 accumulation (v_mfma_f32_16x16x32_bf16 in
+// both tile shapes): 256 x 256 blocks of 2 x 2 waves with 128 x 128 wave tiles for full-height row
+// tiles (the bulk of the flops), 64 x 256 blocks of 1 x 4 waves with 64 x 64 wave tiles for the short
+// remainders (weight streaming).  The weight rows feed the MFMA's first operand and the activation
+// rows the second, so a lane ends up with 4 consecutive output columns of one row.
 #include <type_traits>
 
 #include "common.h"
