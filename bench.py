@@ -62,7 +62,7 @@ def parse():
     p.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling probes (MFMA loop, device copy)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--unfused", action="store_true",
-                   help="five separate calls (moe_dispatch + moe_grouped_ffn) instead of moe_dispatch_ffn")
+                   help="the five separate calls (with moe_dispatch and moe_grouped_ffn) instead of moe_layer_forward")
     p.add_argument("--calibration-copy", action="store_true",
                    help="also run a plain 1 GiB device copy (the known-size kernel that scales FETCH_SIZE/WRITE_SIZE)")
     p.add_argument("--ffn-uniform", default="mixtral",
@@ -180,8 +180,12 @@ def measure(w, mode, scope, gamma, steps, warmup, fused=True, metric=0, oversele
     K_GU, K_DN = capmoe.KERNELS.index("ffn_gate_up"), capmoe.KERNELS.index("ffn_down")
 
     def step():
-        capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
-                             fused_dispatch=fused)
+        if fused:   # the whole layer through the one-call entry point
+            capmoe.moe_layer_forward(desc, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"], None, 0,
+                                     buf)
+        else:       # the five separate calls
+            capmoe.layer_forward(buf, t["x"], t["w_router"], t["bias"], t["w_gate"], t["w_up"], t["w_down"],
+                                 fused_dispatch=False)
 
     for _ in range(warmup):
         step()
@@ -534,7 +538,9 @@ def line_of(w, a, mode_name, scope_name, r):
     for name in ("router_logits", "softmax_topk", "drop", "dispatch", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"):
         ms = merged[name]
         if ms is None:
-            stages[name] = {"ms": None, "note": "fused into ffn_gate_up" if name == "dispatch" else "not launched"}
+            note = {"dispatch": "fused into ffn_gate_up",
+                    "ffn_schedule": "no launch of its own: built by the last launch of the drop"}.get(name, "not launched")
+            stages[name] = {"ms": None, "note": note}
             continue
         stages[name] = {"ms": round(ms, 4)}
         wk = r["work"].get(name)
@@ -561,7 +567,8 @@ def line_of(w, a, mode_name, scope_name, r):
         "experts_per_token_mean": round(r["experts_per_token_mean"], 3),
         "experts_per_token_max": r["experts_per_token_max"], "tokens_without_expert": r["tokens_without_expert"],
         "calls": "route_topk, capacity_drop, dispatch, grouped_ffn, combine" if a.unfused else
-                 "route_topk, capacity_drop, dispatch_ffn (dispatch fused into the first GEMM), combine"}
+                 "moe_layer_forward = route_topk, capacity_drop (its last launch also builds the tile schedule of "
+                 "the expert GEMMs), dispatch_ffn (dispatch fused into the first GEMM), combine"}
     return out
 
 

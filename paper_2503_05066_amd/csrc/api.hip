@@ -4,6 +4,7 @@
 #include <mutex>
 
 #include "common.h"
+#include "schedule.h"
 
 namespace capmoe {
 
@@ -210,6 +211,30 @@ static int route_topk_impl(const moe_desc_t* desc, const void* x, const float* w
     return MOE_OK;
 }
 
+// schedule != nullptr: the drop also builds the tile schedule of the expert GEMMs (moe_layer_forward)
+static int capacity_drop_impl(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx,
+                              const uint8_t* token_class, uint32_t seed, int32_t* expert_count, int32_t* seg_count,
+                              int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
+                              void* workspace, size_t workspace_bytes, const FfnScheduleArgs* schedule, void* stream) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (!expert_count || !seg_count || !expert_offset || !workspace) return MOE_ERR_INVALID_ARG;
+    const Sizes s = derive(*desc);
+    // arrays that are empty for this descriptor may be null
+    if (desc->n_tokens > 0 && (!scores || !topk_idx || !pair_row)) return MOE_ERR_INVALID_ARG;
+    if (s.max_rows > 0 && (!row_token || !row_weight)) return MOE_ERR_INVALID_ARG;
+    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    // the kernels fetch top-k lists, score rows and keys in 16-byte pieces
+    if (misaligned16(scores) || misaligned16(topk_idx) || misaligned16(pair_row)) return MOE_ERR_INVALID_ARG;
+    const DropWorkspace ws = drop_workspace(*desc, s, workspace);
+    if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
+    if (launch_capacity_drop(*desc, s, ws, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
+                             row_token, row_weight, pair_row, schedule, (hipStream_t)stream) != hipSuccess)
+        return MOE_ERR_HIP;
+    return MOE_OK;
+}
+
 extern "C" {
 
 const char* moe_status_string(int status) {
@@ -272,23 +297,8 @@ int moe_capacity_drop_ranked(const moe_desc_t* desc, const float* scores, const 
                              const uint8_t* token_class, uint32_t seed, int32_t* expert_count, int32_t* seg_count,
                              int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
                              void* workspace, size_t workspace_bytes, void* stream) {
-    const int v = validate(desc);
-    if (v != MOE_OK) return v;
-    if (!expert_count || !seg_count || !expert_offset || !workspace) return MOE_ERR_INVALID_ARG;
-    const Sizes s = derive(*desc);
-    // arrays that are empty for this descriptor may be null
-    if (desc->n_tokens > 0 && (!scores || !topk_idx || !pair_row)) return MOE_ERR_INVALID_ARG;
-    if (s.max_rows > 0 && (!row_token || !row_weight)) return MOE_ERR_INVALID_ARG;
-    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
-    // the kernels fetch top-k lists, score rows and keys in 16-byte pieces
-    if (misaligned16(scores) || misaligned16(topk_idx) || misaligned16(pair_row)) return MOE_ERR_INVALID_ARG;
-    const DropWorkspace ws = drop_workspace(*desc, s, workspace);
-    if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
-    if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
-    if (launch_capacity_drop(*desc, s, ws, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
-                             row_token, row_weight, pair_row, (hipStream_t)stream) != hipSuccess)
-        return MOE_ERR_HIP;
-    return MOE_OK;
+    return capacity_drop_impl(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
+                              row_token, row_weight, pair_row, workspace, workspace_bytes, nullptr, stream);
 }
 
 int moe_capacity_drop(const moe_desc_t* desc, const float* scores, const int32_t* topk_idx, int32_t* expert_count,
@@ -313,7 +323,7 @@ int moe_dispatch(const moe_desc_t* desc, const void* x, const int32_t* expert_of
 
 static int grouped_ffn_impl(const moe_desc_t* desc, const void* a, const int32_t* row_token,
                             const int32_t* expert_offset, const void* w_gate, const void* w_up, const void* w_down,
-                            void* yp, void* workspace, size_t workspace_bytes, void* stream) {
+                            void* yp, void* workspace, size_t workspace_bytes, bool schedule_ready, void* stream) {
     const int v = validate(desc);
     if (v != MOE_OK) return v;
     if (!a || !expert_offset || !w_gate || !w_up || !w_down || !yp || !workspace) return MOE_ERR_INVALID_ARG;
@@ -326,7 +336,8 @@ static int grouped_ffn_impl(const moe_desc_t* desc, const void* a, const int32_t
     if (workspace_bytes < ws.bytes) return MOE_ERR_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255) != 0) return MOE_ERR_INVALID_ARG;
     if (s.max_rows == 0) return MOE_OK;
-    if (launch_grouped_ffn(*desc, s, ws, a, row_token, expert_offset, w_gate, w_up, w_down, yp, (hipStream_t)stream) !=
+    if (launch_grouped_ffn(*desc, s, ws, a, row_token, expert_offset, w_gate, w_up, w_down, yp, schedule_ready,
+                           (hipStream_t)stream) !=
         hipSuccess)
         return MOE_ERR_HIP;
     return MOE_OK;
@@ -336,7 +347,7 @@ int moe_grouped_ffn(const moe_desc_t* desc, const void* xp, const int32_t* exper
                     const void* w_up, const void* w_down, void* yp, void* workspace, size_t workspace_bytes,
                     void* stream) {
     return grouped_ffn_impl(desc, xp, nullptr, expert_offset, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
-                            stream);
+                            false, stream);
 }
 
 int moe_dispatch_ffn(const moe_desc_t* desc, const void* x, const int32_t* expert_offset, const int32_t* row_token,
@@ -344,7 +355,7 @@ int moe_dispatch_ffn(const moe_desc_t* desc, const void* x, const int32_t* exper
                      size_t workspace_bytes, void* stream) {
     if (!row_token) return MOE_ERR_INVALID_ARG;
     return grouped_ffn_impl(desc, x, row_token, expert_offset, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
-                            stream);
+                            false, stream);
 }
 
 int moe_combine(const moe_desc_t* desc, const void* yp, const float* row_weight, const int32_t* pair_row, void* y,
@@ -393,12 +404,22 @@ int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_rout
     int st = moe_route_topk(desc, x, w_router, bias, 0, logits, scores, topk_idx, topk_score, workspace,
                             workspace_bytes, stream);
     if (st != MOE_OK) return st;
-    st = moe_capacity_drop_ranked(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset,
-                                  row_token, row_weight, pair_row, workspace, workspace_bytes, stream);
+    // The tile schedule of the expert GEMMs lives in the workspace behind the hidden activations.  Where that
+    // place lies beyond what the drop itself uses of the workspace, the drop builds the schedule in the launch
+    // that finishes the plan and the GEMMs start without a schedule kernel of their own.
+    FfnScheduleArgs schedule;
+    bool fold = false;
+    if (s.max_rows > 0) {
+        const FfnWorkspace fw = ffn_workspace(*desc, s, workspace);
+        fold = (size_t)((const char*)fw.big.expert - (const char*)workspace) >= drop_workspace(*desc, s, nullptr).bytes;
+        if (fold) schedule = ffn_schedule_args(*desc, fw);
+    }
+    st = capacity_drop_impl(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset, row_token,
+                            row_weight, pair_row, workspace, workspace_bytes, fold ? &schedule : nullptr, stream);
     if (st != MOE_OK) return st;
     if (s.max_rows > 0) {
-        st = moe_dispatch_ffn(desc, x, expert_offset, row_token, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
-                              stream);
+        st = grouped_ffn_impl(desc, x, row_token, expert_offset, w_gate, w_up, w_down, yp, workspace, workspace_bytes,
+                              fold, stream);
         if (st != MOE_OK) return st;
     }
     return moe_combine(desc, yp, row_weight, pair_row, y, stream);

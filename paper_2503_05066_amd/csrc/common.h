@@ -126,6 +126,8 @@ inline void once_per_device(std::atomic<uint64_t>& seen, F&& configure) {
 }
 int compute_units();  // of the current device
 
+struct FfnScheduleArgs;  // schedule.h
+
 // Launchers (each returns a hipError_t from hipGetLastError after its launches).
 hipError_t launch_router_logits(const moe_desc_t& d, const void* x, const float* w, const float* bias, float* logits,
                                 hipStream_t st);
@@ -138,13 +140,16 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
                                 const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
                                 int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
-                                hipStream_t st);
+                                const FfnScheduleArgs* schedule, hipStream_t st);
 hipError_t launch_dispatch(const moe_desc_t& d, const Sizes& s, const void* x, const int32_t* expert_offset,
                            const int32_t* row_token, void* xp, hipStream_t st);
 hipError_t launch_combine(const moe_desc_t& d, const Sizes& s, const void* yp, const float* row_weight,
                           const int32_t* pair_row, void* y, hipStream_t st);
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
                               const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
-                              const void* w_up, const void* w_down, void* yp, hipStream_t st);
+                              const void* w_up, const void* w_down, void* yp, bool schedule_ready, hipStream_t st);
+// schedule != nullptr (launch_capacity_drop): the drop also builds the tile schedule of the expert GEMMs;
+// schedule_ready (launch_grouped_ffn): it has been built that way, no schedule kernel is launched
+FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws);
 
 }  // namespace capmoe

@@ -19,6 +19,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "schedule.h"
 
 namespace capmoe {
 
@@ -339,6 +340,38 @@ __global__ __launch_bounds__(NT) void drop_select_kernel(const uint32_t* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// The tile schedule of the expert GEMMs, built by the drop itself
+// ---------------------------------------------------------------------------------------------
+// One block of the kernel that finishes the plan adds up every segment's kept count anyway (it needs its own
+// first row).  When the whole layer is enqueued by one call, that block also turns the per-expert totals into
+// row offsets (in LDS) and builds the tile lists of the expert GEMMs from them, so that no kernel has to be
+// launched between the plan and the first GEMM just to read expert_offset back.
+// tot[e]: rows of expert e (complete, block-visible); off: kMaxExperts + 1 words of LDS.  Called by the whole
+// block after a barrier; its first wave does the work.
+__device__ inline void build_schedule_from_totals(const int* tot, int* off, const FfnScheduleArgs& a) {
+    if (threadIdx.x >= kWave) return;
+    const int lane = threadIdx.x;
+    int base = 0;
+#pragma unroll
+    for (int c = 0; c < kMaxExperts / kWave; ++c) {
+        const int e = c * kWave + lane;
+        const int v = e < a.E ? tot[e] : 0;
+        int incl = v;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int up = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += up;
+        }
+        if (e < a.E) off[e] = base + incl - v;
+        base += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) off[a.E] = base;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // LDS operations of one wave complete in order: the offsets are there
+    build_ffn_schedule(off, a);
+}
+
+// ---------------------------------------------------------------------------------------------
 // 3. ordered compaction
 // ---------------------------------------------------------------------------------------------
 constexpr int kEmitRun = 16;                // consecutive tokens per thread
@@ -354,12 +387,19 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
                                                         int32_t* __restrict__ expert_offset,
                                                         int32_t* __restrict__ row_token, float* __restrict__ row_weight,
                                                         int32_t* __restrict__ pair_row, int N, int E, int n_blocks,
-                                                        int seg_tokens, int S, int weight_from_key) {
+                                                        int seg_tokens, int S, int weight_from_key,
+                                                        FfnScheduleArgs sched) {
     // a thread owns a run of 16 consecutive tokens; one padding word per run keeps the runs of
     // neighbouring threads on different LDS banks
     __shared__ uint32_t key_s[kEmitChunk + 256];
     __shared__ uint8_t slot_s[kEmitChunk];
     __shared__ int red[4];
+    __shared__ int sched_tot[kMaxExperts], sched_off[kMaxExperts + 1];
+    const bool scheduler = sched.enabled && blockIdx.x == 0;  // this block also builds the GEMMs' tile schedule
+    if (scheduler) {
+        for (int i = threadIdx.x; i < kMaxExperts; i += 256) sched_tot[i] = 0;
+        __syncthreads();
+    }
     // a block owns one chunk of kEmitChunk tokens of one segment; what the chunks before it keep it counts itself
     const int parts = seg_tokens > kEmitChunk ? (seg_tokens + kEmitChunk - 1) / kEmitChunk : 1;
     const int seg = blockIdx.x / parts;
@@ -382,6 +422,7 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
         const int c = seg_count[i];
         if (ee < e || (ee == e && bb < b)) before += c;
         if (ee == e) own += c;
+        if (scheduler) atomicAdd(&sched_tot[ee], c);
     }
     const int row0 = block_sum_256(before, red);
     const int own_total = block_sum_256(own, red);
@@ -463,6 +504,10 @@ __global__ __launch_bounds__(256) void drop_emit_kernel(const float* __restrict_
         }
         pair_row[(size_t)t * S + slot_s[i]] = keep ? pos : -1;
         pos += keep;
+    }
+    if (scheduler) {
+        __syncthreads();
+        build_schedule_from_totals(sched_tot, sched_off, sched);
     }
 }
 
@@ -622,8 +667,10 @@ __global__ __launch_bounds__(NT) void drop_fused_kernel(
     uint32_t seed, int32_t* __restrict__ expert_count, int32_t* __restrict__ seg_count,
     int32_t* __restrict__ expert_offset, int32_t* __restrict__ row_token, float* __restrict__ row_weight,
     int32_t* __restrict__ pair_row, int N, int E, int k, int S, int group_tokens, int group_experts, int metric,
-    int seg_tokens, int n_blocks, int cap, int weight_from_key) {
+    int seg_tokens, int n_blocks, int cap, int weight_from_key, FfnScheduleArgs sched) {
     constexpr int kWaves = NT / kWave, kMaxTok = NT * 8;
+    __shared__ int sched_tot[kMaxExperts], sched_off[kMaxExperts + 1];
+    const bool scheduler = sched.enabled && blockIdx.x == 0;  // this block also builds the GEMMs' tile schedule
     // a thread owns a run of consecutive tokens of the segment; one padding word per 16 keeps the runs of
     // neighbouring threads on different LDS banks
     __shared__ uint32_t key_s[kMaxTok + kMaxTok / 16];
@@ -646,6 +693,8 @@ __global__ __launch_bounds__(NT) void drop_fused_kernel(
 
     for (int i = tid; i < copies * pitch; i += NT) cand[i] = 0;
     if (tid < 256) hist[tid] = 0;
+    if (scheduler)
+        for (int i = tid; i < kMaxExperts; i += NT) sched_tot[i] = 0;
     __syncthreads();
 
     // ---- one pass over the top-k lists, a thread per token: candidates of every segment (the experts of a
@@ -767,6 +816,7 @@ __global__ __launch_bounds__(NT) void drop_fused_kernel(
             c += z > a ? z - a : 0;
         }
         const int kept = c < cap ? c : cap;
+        if (scheduler) atomicAdd(&sched_tot[ee], kept);
         if (ee < e || (ee == e && bb < b)) before += kept;
         if (ee == e) own_total += kept;
         if (i == seg) n_cand = c;
@@ -891,14 +941,20 @@ __global__ __launch_bounds__(NT) void drop_fused_kernel(
         pair_row[(size_t)t * S + slot_s[tb + j]] = keep ? pos : -1;
         pos += keep;
     }
+    if (scheduler) {
+        __syncthreads();
+        build_schedule_from_totals(sched_tot, sched_off, sched);
+    }
 }
 
 hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropWorkspace& ws, const float* scores,
                                 const int32_t* topk_idx, const uint8_t* token_class, uint32_t seed,
                                 int32_t* expert_count, int32_t* seg_count,
                                 int32_t* expert_offset, int32_t* row_token, float* row_weight, int32_t* pair_row,
-                                hipStream_t st) {
+                                const FfnScheduleArgs* schedule, hipStream_t st) {
     const int N = d.n_tokens, E = d.n_experts;
+    FfnScheduleArgs no_schedule = {};  // enabled = 0
+    const FfnScheduleArgs& sched = schedule ? *schedule : no_schedule;
     {
         const int segs_all = s.n_blocks * E;
         constexpr int kSmallBlock = 256;  // threads of a block for short segments of short batches
@@ -914,7 +970,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
                 hipLaunchKernelGGL(kern, dim3(segs_all), dim3(threads), 0, st, scores, topk_idx, token_class, seed,
                                    expert_count, seg_count, expert_offset, row_token, row_weight, pair_row, N, E, s.list_k,
                                    s.slots, s.group_tokens, s.group_experts, d.metric, s.seg_tokens, s.n_blocks, s.cap,
-                                   d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
+                                   d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0, sched);
             };
             auto by_size = [&](auto ex_c, auto one_c, auto vw_c) {
                 constexpr bool EX = decltype(ex_c)::value, ONE = decltype(one_c)::value;
@@ -972,15 +1028,17 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
         hipLaunchKernelGGL(kern, dim3(segs / s.span), dim3(wide ? 1024 : 256), lds, st, ws.key_t, ws.seg_tau,
                            ws.seg_need, seg_count, N, E, s.seg_tokens, s.span, s.cap);
     }
-    auto emit = [&]() {
+    auto emit = [&](bool last) {
         ProfileScope prof(MOE_KERNEL_DROP_EMIT, st);
         const int parts = s.seg_tokens > kEmitChunk ? (s.seg_tokens + kEmitChunk - 1) / kEmitChunk : 1;
         hipLaunchKernelGGL(drop_emit_kernel, dim3(segs * parts), dim3(256), 0, st, scores, ws.key_t, ws.slot_t, ws.seg_tau,
                            ws.seg_need, seg_count, expert_count, expert_offset, row_token, row_weight, pair_row, N, E,
-                           s.n_blocks, s.seg_tokens, s.slots, d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0);
+                           s.n_blocks, s.seg_tokens, s.slots, d.metric == MOE_METRIC_SCORE && !token_class ? 1 : 0,
+                           last ? sched : no_schedule);
     };
-    emit();
-    if (d.max_experts && s.slots > d.top_k && N > 0) {
+    const bool limit = d.max_experts && s.slots > d.top_k && N > 0;
+    emit(!limit);
+    if (limit) {
         // the first plan tells which pairs survive the capacity; trim every token to k of them, emit again
         // the key tile of 64 tokens and their rows of pair_row: at most 256 * 65 + 64 * 255 words
         const size_t lds = ((size_t)E * kLimitPitch + (size_t)kLimitTokens * s.slots) * 4;
@@ -992,7 +1050,7 @@ hipError_t launch_capacity_drop(const moe_desc_t& d, const Sizes& s, const DropW
             hipLaunchKernelGGL(kern, dim3((N + kLimitTokens - 1) / kLimitTokens), dim3(256), lds, st, scores, ws.key_t,
                                pair_row, ws.seg_tau, ws.seg_need, seg_count, N, E, s.slots, d.top_k, s.seg_tokens, segs);
         }
-        emit();
+        emit(true);
     }
     return hipGetLastError();
 }

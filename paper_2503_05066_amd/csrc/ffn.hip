@@ -16,6 +16,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "schedule.h"
 
 #ifndef FFN_STAGGER
 #define FFN_STAGGER 1
@@ -29,146 +30,10 @@ namespace capmoe {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
 // ---------------------------------------------------------------------------------------------
-// tile schedule
+// tile schedule (schedule.h) as a kernel of its own: one wave
 // ---------------------------------------------------------------------------------------------
-// Expert e with c rows gets floor(c / big) full tiles; a remainder above small_max rows becomes one
-// more (partly filled) big tile, a smaller one is cut into ceil(remainder / small) short tiles, which
-// run the same loop on 64-row blocks (few rows per weight byte: memory-bound work).
-//
-// A GEMM runs its big work items (row tiles x column blocks) in rounds of one item per compute unit, and
-// every XCD (an eighth of the compute units with an L2 of its own) gets a contiguous eighth of them.  The
-// items left over after an XCD's last full round would hold that XCD for a whole item time with most of
-// its compute units idle, so each of them is cut along K into `slices` units that run side by side: a unit
-// multiplies its share of the K slabs and writes its fp32 partial tile to the workspace, and the unit of an
-// item that finishes last (an integer ticket per item) adds the partial tiles in slice order and writes the
-// output tile: no floating-point atomics, the same bits run to run.  The cut depends on the GEMM's
-// column-block count and K, so each of the two GEMMs gets its own header.
-struct SplitArgs {
-    int32_t* hdr;      // [4]: big items per XCD that are cut (taken from the end of the XCD's share) and units per
-                       // item, then the same for the short items
-    int32_t* counter;  // [2 * kFfnSplitUnits] tickets (big, short), zeroed here before every launch
-    int ncol_big;      // column blocks of the GEMM's big items; 0: never cut
-    int ncol_small;    // column blocks of its short items
-    int slabs;         // K slabs of the GEMM
-};
-struct TileListArgs {
-    int32_t *b_expert, *b_row0, *b_rows, *b_count, *s_expert, *s_row0, *s_rows, *s_count;
-    int b_max, s_max;
-};
-
-struct ExpertTiles {
-    int lo, rows, nb, ns;
-};
-// Tile heights are powers of two (big = 1 << big_sh, small = 1 << small_sh): a single wave runs this kernel,
-// every dependent instruction counts, and a division by a run-time value is forty of them.
-__device__ inline ExpertTiles expert_tiles(int lo, int hi, int big_sh, int small_sh, int small_max) {
-    ExpertTiles t;
-    t.lo = lo;
-    t.rows = hi - lo;
-    const int full = t.rows >> big_sh, rem = t.rows - (full << big_sh);
-    const bool rem_small = rem > 0 && rem <= small_max;
-    t.nb = full + (rem > 0 && !rem_small ? 1 : 0);
-    t.ns = rem_small ? (rem + (1 << small_sh) - 1) >> small_sh : 0;
-    return t;
-}
-
-// inclusive scan of two counters over the wave
-__device__ inline void wave_scan2(int& a, int& b) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const int oa = __shfl_up(a, off, kWave), ob = __shfl_up(b, off, kWave);
-        if (lane >= off) {
-            a += oa;
-            b += ob;
-        }
-    }
-}
-
-// How an XCD's share of `items_per_xcd` big items is cut: the last `cut` of them into `slices` units each.
-// cus_per_xcd compute units run one item each per round; a unit keeps at least kFfnSplitMinSlabs slabs.
-__host__ __device__ inline void split_rule(int items_per_xcd, int cus_per_xcd, int slabs, int& cut, int& slices) {
-    cut = 0;
-    slices = 1;
-    if (items_per_xcd <= 0 || cus_per_xcd <= 0 || slabs < kFfnSplitMinK) return;
-    if (cus_per_xcd > kFfnSplitUnits / 8) cus_per_xcd = kFfnSplitUnits / 8;
-    const int left = items_per_xcd % cus_per_xcd;
-    if (left == 0) return;
-    int s = cus_per_xcd / left;
-    if (s > kFfnSplitMaxSlices) s = kFfnSplitMaxSlices;
-    if (s > slabs / kFfnSplitMinSlabs) s = slabs / kFfnSplitMinSlabs;
-    if (s < 2) return;
-    cut = left;
-    slices = s;
-}
-
-__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, int E, int big_sh,
-                                                         int small_sh, int small_max, int cus, TileListArgs L,
-                                                         SplitArgs first, SplitArgs second) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int big = 1 << big_sh, small = 1 << small_sh;
-    // Every lane's experts, fetched once, and one scan per 64 experts: the kernel is a chain of latencies
-    // (a dependent global load costs a microsecond, a wave scan half of one), so nothing is done twice.
-    constexpr int kChunks = kMaxExperts / kWave;
-    int nt_b = 0, nt_s = 0;
-    int lo[kChunks], hi[kChunks];
-#pragma unroll
-    for (int c = 0; c < kChunks; ++c) {
-        const int e = c * kWave + lane;
-        lo[c] = e < E ? expert_offset[e] : 0;
-        hi[c] = e < E ? expert_offset[e + 1] : 0;
-    }
-    // tickets of both GEMMs start at zero
-    for (int i = lane; i < 2 * kFfnSplitUnits; i += kWave) {
-        if (first.counter) first.counter[i] = 0;
-        if (second.counter) second.counter[i] = 0;
-    }
-#pragma unroll
-    for (int c = 0; c < kChunks; ++c) {
-        if (c * kWave >= E) continue;  // the same for every lane
-        const int e = c * kWave + lane;
-        const ExpertTiles x = expert_tiles(lo[c], hi[c], big_sh, small_sh, small_max);
-        int ib = x.nb, is = x.ns;
-        wave_scan2(ib, is);
-        const int start_b = nt_b + ib - x.nb, start_s = nt_s + is - x.ns;
-        nt_b += __shfl(ib, kWave - 1, kWave);
-        nt_s += __shfl(is, kWave - 1, kWave);
-        for (int i = 0; i < x.nb; ++i) {
-            const int idx = start_b + i;
-            const int left = x.rows - i * big;
-            if (idx < L.b_max) {
-                L.b_expert[idx] = e;
-                L.b_row0[idx] = x.lo + i * big;
-                L.b_rows[idx] = left < big ? left : big;
-            }
-        }
-        const int full = x.rows >> big_sh, rem = x.rows - (full << big_sh);
-        for (int i = 0; i < x.ns; ++i) {
-            const int idx = start_s + i;
-            if (idx < L.s_max) {
-                L.s_expert[idx] = e;
-                L.s_row0[idx] = x.lo + full * big + i * small;
-                const int left = rem - i * small;
-                L.s_rows[idx] = left < small ? left : small;
-            }
-        }
-    }
-    if (lane == 0) {
-        const int nb = nt_b < L.b_max ? nt_b : L.b_max, ns = nt_s < L.s_max ? nt_s : L.s_max;
-        *L.b_count = nb;
-        *L.s_count = ns;
-        for (const SplitArgs* sp : {&first, &second}) {
-            if (!sp->hdr) continue;
-            const long long items[2] = {(long long)nb * sp->ncol_big, (long long)ns * sp->ncol_small};
-            for (int which = 0; which < 2; ++which) {
-                int cut = 0, slices = 1;
-                if (items[which] > 0 && items[which] < (1ll << 30))
-                    split_rule((int)((items[which] + 7) >> 3), cus >> 3, sp->slabs, cut, slices);
-                sp->hdr[2 * which] = cut;
-                sp->hdr[2 * which + 1] = slices;
-            }
-        }
-    }
+__global__ __launch_bounds__(64) void ffn_schedule_kernel(const int32_t* __restrict__ expert_offset, FfnScheduleArgs args) {
+    build_ffn_schedule(expert_offset, args);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -775,34 +640,46 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
 
 // row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
 // plan is fetched from x[row_token[r]] (dispatch fused into the first GEMM's operand fetch).
+FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
+    const bool bf16 = d.dtype == MOE_DTYPE_BF16;
+    const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
+    const int bn_down = N2 % 256 == 0 ? 256 : 128;
+    auto log2i = [](int v) {
+        int sh = 0;
+        while ((1 << sh) < v) ++sh;
+        return sh;
+    };
+    FfnScheduleArgs a;
+    a.enabled = 1;
+    a.E = d.n_experts;
+    a.big_sh = log2i(ws.big.tile_m);
+    a.small_sh = log2i(ws.small.tile_m);
+    a.small_max = ws.small_max;
+    a.cus = compute_units();
+    a.L = TileListArgs{ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count, ws.small.expert, ws.small.row0,
+                       ws.small.rows, ws.small.count, ws.big.max_tiles, ws.small.max_tiles};
+    // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
+    const bool split = bf16 && FFN_SPLITK;
+    a.first = SplitArgs{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
+    a.second = SplitArgs{split ? ws.split_hdr + 4 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
+                         N2 / bn_down, N2 / bn_down, K2 / 64};
+    return a;
+}
+
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
                               const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
-                              const void* w_up, const void* w_down, void* yp, hipStream_t st) {
+                              const void* w_up, const void* w_down, void* yp, bool schedule_ready, hipStream_t st) {
     (void)s;
     const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
     const bool bf16 = d.dtype == MOE_DTYPE_BF16;
     const int bn_down = N2 % 256 == 0 ? 256 : 128;  // d is a multiple of 128 at least: output columns per block
-    {
-        const int cus = compute_units();
+    if (!schedule_ready) {
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
-        const TileListArgs lists{ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count, ws.small.expert, ws.small.row0,
-                                 ws.small.rows, ws.small.count, ws.big.max_tiles, ws.small.max_tiles};
-        // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
-        const bool split = bf16 && FFN_SPLITK;
-        const SplitArgs gu{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
-        const SplitArgs dn{split ? ws.split_hdr + 8 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
-                           N2 / bn_down, N2 / bn_down, K2 / 64};
-        auto log2i = [](int v) {
-            int sh = 0;
-            while ((1 << sh) < v) ++sh;
-            return sh;
-        };
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, d.n_experts,
-                           log2i(ws.big.tile_m), log2i(ws.small.tile_m), ws.small_max, cus, lists, gu, dn);
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, ffn_schedule_args(d, ws));
     }
     if (bf16) {
         const int32_t* split_gu = FFN_SPLITK ? ws.split_hdr : nullptr;
-        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 8 : nullptr;
+        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 4 : nullptr;
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);

@@ -435,12 +435,22 @@ def check_layer(orc, layer, mode, scope, gamma, tokens=None, what="", overselect
 
 
 def test_one_call_entry_matches_separate_calls():
-    """moe_layer_forward enqueues the same four calls: every output equal bit for bit."""
+    """moe_layer_forward enqueues the same work as the four calls (the tile schedule of the expert GEMMs comes out of
+    the drop's last launch instead of a kernel of its own): every output equal bit for bit."""
     cases = [(synth.scaled(W["tiny"], device_groups=4), ED, LOCAL, 1.0, 0, False),
              (synth.scaled(W["olmoe"], name="reduced", n_tokens=640, d_model=256, n_experts=8, top_k=2, d_hidden=384,
                            device_groups=4, skew="normal", skew_param=1.5), TD, LOCAL, 1.0, 2, True),
              (synth.scaled(W["olmoe"], name="reduced", n_tokens=300, d_model=384, n_experts=4, top_k=2, d_hidden=256,
-                           device_groups=1), TD, GLOBAL, 0.0, 0, False)]
+                           device_groups=1), TD, GLOBAL, 0.0, 0, False),
+             # many experts, narrow hidden layer: the drop's workspace reaches past the place of the GEMMs' tile
+             # schedule, so the schedule kernel runs as in the separate calls
+             (synth.scaled(W["olmoe"], name="reduced", n_tokens=512, d_model=128, n_experts=64, top_k=1, d_hidden=128,
+                           device_groups=1), TD, GLOBAL, 2.0, 0, False),
+             # long segments: the three-kernel drop, whose last launch builds the schedule
+             (synth.scaled(W["olmoe"], name="reduced", n_tokens=9000, d_model=128, n_experts=8, top_k=2, d_hidden=256,
+                           device_groups=1), TD, GLOBAL, 1.0, 0, False),
+             (synth.scaled(W["olmoe"], name="reduced", n_tokens=9000, d_model=128, n_experts=12, top_k=3, d_hidden=128,
+                           device_groups=3), ED, GLOBAL, 0.9, 3, True)]
     for w, mode, scope, gamma, m, limit in cases:
         layer = DeviceLayer(w, host_weights=False)
         desc = layer.desc(mode, scope, gamma)
@@ -741,12 +751,16 @@ def test_layer_full_size_own_router(orc, name, mode, full):
                              token_list=toks)
     y = to_host_f64(buf.y)
     assert_output_close(y if toks is None else y[toks], y_ref, TOL[w.dtype], f"{name} own router")
-    # run to run: the same bits
-    again = capmoe.LayerBuffers(desc)
+    # run to run, and through the one-call entry point (what the benchmark times): the same bits
+    again, one = capmoe.LayerBuffers(desc), capmoe.LayerBuffers(desc)
     capmoe.layer_forward(again, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
                          fused_dispatch=True)
+    capmoe.moe_layer_forward(desc, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down, None, 0,
+                             one)
     torch.cuda.synchronize()
-    assert torch.equal(again.y, buf.y) and torch.equal(again.yp[:ref.plan.rows], buf.yp[:ref.plan.rows])
+    for other in (again, one):
+        assert torch.equal(other.y, buf.y) and torch.equal(other.yp[:ref.plan.rows], buf.yp[:ref.plan.rows])
+        assert torch.equal(other.pair_row, buf.pair_row) and torch.equal(other.expert_offset, buf.expert_offset)
 
 
 def test_release_full_size_layers():
