@@ -18,13 +18,6 @@
 #include "common.h"
 #include "schedule.h"
 
-#ifndef FFN_STAGGER
-#define FFN_STAGGER 1
-#endif
-#ifndef FFN_SPLITK
-#define FFN_SPLITK 1
-#endif
-
 namespace capmoe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -206,14 +199,9 @@ struct PipelinedLoop16 {
         // reads go out in the first half of a k-step, so that they have returned long before the barrier
         constexpr int READ_EVERY = NMFMA / 2 / NREAD > 0 ? NMFMA / 2 / NREAD : 1;
         constexpr int B_EVERY = NMFMA / B_LOADS > 0 ? NMFMA / B_LOADS : 1;
-#if FFN_STAGGER
         constexpr int A_EVERY = NMFMA / A_LOADS > 0 ? NMFMA / A_LOADS : 1;
         constexpr int B_OFF = PHASE * B_EVERY / 4 + (B_EVERY >= 8 ? B_EVERY / 8 : 0);
         constexpr int A_OFF = PHASE * A_EVERY / 4 + (A_EVERY >= 8 ? A_EVERY / 8 : 0);
-#else
-        constexpr int A_EVERY = NMFMA / 2 / A_LOADS > 0 ? NMFMA / 2 / A_LOADS : 1;
-        constexpr int B_OFF = B_EVERY / 2, A_OFF = A_EVERY / 2;
-#endif
         static_assert(B_OFF < B_EVERY && A_OFF < A_EVERY, "request placement");
         static_assert(LIVE == 0 || (NMFMA >= NREAD * READ_EVERY && NMFMA >= B_LOADS && NMFMA >= A_LOADS * A_EVERY), "k-step too short");
         bf16x8 xa[2][NL], wb[2][TN];
@@ -395,7 +383,6 @@ struct TileConfig16 {
     const int k_first = split.slices > 1 ? (int)((long long)split.slice * slabs_all / split.slices) : 0;
     const int k_end = split.slices > 1 ? (int)((long long)(split.slice + 1) * slabs_all / split.slices) : slabs_all;
     Loop loop{smem, fills, a_lane, b_lane, k_end - k_first, __builtin_amdgcn_readfirstlane(wv), k_first};
-#if FFN_STAGGER
     if (live == TM) {
         switch (loop.wv & 3) {
             case 0: loop.template run<TM, 0>(acc); break;
@@ -403,13 +390,7 @@ struct TileConfig16 {
             case 2: loop.template run<TM, 2>(acc); break;
             default: loop.template run<TM, 3>(acc); break;
         }
-    } else if
-#else
-    if (live == TM)
-        loop.template run<TM>(acc);
-    else if
-#endif
- (TM > 6 && live == 6)
+    } else if (TM > 6 && live == 6)
         loop.template run<(TM > 6 ? 6 : TM)>(acc);
     else if (TM > 4 && live == 4)
         loop.template run<(TM > 4 ? 4 : TM)>(acc);
@@ -610,11 +591,8 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     }
 }
 
-#ifndef FFN_COLGROUP_MAX
-#define FFN_COLGROUP_MAX 4
-#endif
 static int column_group(int nb_total) {
-    for (int g = FFN_COLGROUP_MAX; g > 1; --g)
+    for (int g = 4; g > 1; --g)
         if (nb_total % g == 0) return g;
     return 1;
 }
@@ -638,8 +616,7 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
                        column_group(nb_b), column_group(nb_s), split_hdr, split_partial, split_counter);
 }
 
-// row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
-// plan is fetched from x[row_token[r]] (dispatch fused into the first GEMM's operand fetch).
+// The arguments of the tile schedule for a descriptor and its workspace layout (host side).
 FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
     const bool bf16 = d.dtype == MOE_DTYPE_BF16;
     const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
@@ -659,13 +636,16 @@ FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
     a.L = TileListArgs{ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count, ws.small.expert, ws.small.row0,
                        ws.small.rows, ws.small.count, ws.big.max_tiles, ws.small.max_tiles};
     // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
-    const bool split = bf16 && FFN_SPLITK;
+    const bool split = bf16;
     a.first = SplitArgs{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
     a.second = SplitArgs{split ? ws.split_hdr + 4 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
                          N2 / bn_down, N2 / bn_down, K2 / 64};
     return a;
 }
 
+// row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
+// plan is fetched from x[row_token[r]] (dispatch fused into the first GEMM's operand fetch).
+// schedule_ready: the tile schedule is in the workspace already (built by the drop), no schedule kernel is launched.
 hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWorkspace& ws, const void* xp,
                               const int32_t* row_token, const int32_t* expert_offset, const void* w_gate,
                               const void* w_up, const void* w_down, void* yp, bool schedule_ready, hipStream_t st) {
@@ -678,8 +658,8 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
         hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, ffn_schedule_args(d, ws));
     }
     if (bf16) {
-        const int32_t* split_gu = FFN_SPLITK ? ws.split_hdr : nullptr;
-        const int32_t* split_dn = FFN_SPLITK ? ws.split_hdr + 4 : nullptr;
+        const int32_t* split_gu = ws.split_hdr;
+        const int32_t* split_dn = ws.split_hdr + 4;
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
