@@ -100,7 +100,11 @@ FfnWorkspace ffn_workspace(const moe_desc_t& d, const Sizes& s, void* base) {
 
     w.hidden = p + off;
     off += align256((size_t)(s.max_rows > 0 ? s.max_rows : 1) * d.d_hidden * s.elem);
-    for (TileList* t : {&w.big, &w.small}) {
+    // both kinds in one list (the gate/up GEMM's order)
+    w.all.tile_m = 0;
+    w.all.max_tiles = w.big.max_tiles + w.small.max_tiles;
+    w.all.max_launch = w.all.max_tiles;
+    for (TileList* t : {&w.big, &w.small, &w.all}) {
         const size_t n = align256((size_t)(t->max_tiles > 0 ? t->max_tiles : 1) * 4);
         t->expert = (int32_t*)(p + off);
         off += n;

@@ -66,6 +66,9 @@ constexpr int kFfnSplitMaxSlices = 8;    // most units per item
 constexpr int kFfnSplitMinSlabs = 16;    // fewest 64-wide K slabs per unit
 constexpr int kFfnSplitMinK = 128;       // GEMMs with fewer K slabs are never cut: a unit costs a fixed ~30 us on top of
                                          // its slabs (partial tile out, ticket, the sum), an item of 64 slabs only 100 us
+constexpr int kFfnSplitHdr = 8;          // ints per GEMM in the schedule's header
+constexpr int kFfnJointMinRounds = 8;    // work items per compute unit from which an uncut GEMM walks the joint tile
+                                         // list (measured: 16 and 20 rounds gain 2 %, 3 rounds lose 7 %, 5 neither)
 struct TileList {
     int32_t* expert;  // [max_tiles]
     int32_t* row0;    // [max_tiles] first row of the tile
@@ -79,9 +82,10 @@ struct FfnWorkspace {
     void* hidden;    // [P_max, h] activations silu(gate)*up in desc->dtype
     TileList big;    // full-height row tiles, and remainders above small_max rows
     TileList small;  // short row tiles covering remainders of at most small_max rows (bf16 only)
+    TileList all;    // both kinds in one list, expert by expert (bf16 only; tile_m unused)
     int small_max;
-    int32_t* split_hdr;      // [2 GEMMs][4]: big items per XCD that are cut along K and units per item, the same
-                             // for the short items (bf16 only)
+    int32_t* split_hdr;      // [2 GEMMs][kFfnSplitHdr]: big items per XCD that are cut along K and units per item,
+                             // the same for the short items, whether the GEMM walks the joint list (bf16 only)
     int32_t* split_counter;  // [2 GEMMs][2][kFfnSplitUnits] one ticket per cut item (big, short)
     float* split_partial;    // [kFfnSplitUnits][256 x 256] fp32 partial tiles of big items, then
                              // [kFfnSplitUnits][64 x 256] of short ones (the GEMMs run one after the other)

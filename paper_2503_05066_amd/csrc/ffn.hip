@@ -516,35 +516,58 @@ __device__ inline void decode_item(int logical, int nt, int col_group, int& tile
     nb = cg * col_group + (rem - tile * col_group);
 }
 
-// One launch serves both tile lists.  Every XCD (block id mod 8) gets a contiguous eighth of the
-// big items, then a contiguous eighth of the small items: long blocks first, short ones fill the
-// tail, and blocks that run together on an XCD share row and weight tiles in its L2.  The last
-// split[0] big items of an XCD's share run as split[1] units each (see the tile schedule); the units
-// follow the XCD's whole items in launch order, slice by slice, so that the units that run together
-// read the same K range of the tiles they share.
+// One launch serves both kinds of tile.  Every XCD (block id mod 8) gets a contiguous eighth of the work, and
+// blocks that run together on an XCD share row and weight tiles in its L2.
+//
+// split_hdr[4] set (see the tile schedule: a long launch that is never cut along K): the blocks walk the list
+// that holds both kinds expert by expert, so the short tiles of an expert run next to its big tiles and their
+// weight streaming overlaps matrix work.
+//
+// Otherwise the two lists one after the other: the XCD's eighth of the big items, then its eighth of the short
+// ones (longest first).  The last split_hdr[0] big items of an XCD's share run as split_hdr[1] units each; the
+// units follow the XCD's whole items in launch order, slice by slice, so that the units that run together read
+// the same K range of the tiles they share.
 template <class Big, class Small, bool SWIGLU>
 __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
-    uint16_t* __restrict__ C, const int32_t* __restrict__ gather, const int32_t* __restrict__ b_expert,
-    const int32_t* __restrict__ b_row0,
-    const int32_t* __restrict__ b_rows, const int32_t* __restrict__ b_count, const int32_t* __restrict__ s_expert,
-    const int32_t* __restrict__ s_row0, const int32_t* __restrict__ s_rows, const int32_t* __restrict__ s_count, int K,
-    int Nout, int col_group_big, int col_group_small, const int32_t* __restrict__ split_hdr, float* split_partial,
+    uint16_t* __restrict__ C, const int32_t* __restrict__ gather, const TileListArgs L, int K, int Nout,
+    int col_group_big, int col_group_small, const int32_t* __restrict__ split_hdr, float* split_partial,
     int32_t* split_counter) {
     static_assert(Big::kThreads == Small::kThreads, "one block size");
+    static_assert(Big::kNCols == Small::kNCols, "one column-block width: the joint list is decoded with it");
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    const int nt_b = *b_count, nt_s = *s_count;
-    const int total_b = nt_b * (Nout / Big::kNCols), total_s = nt_s * (Nout / Small::kNCols);
-    const int chunk_b = (total_b + 7) >> 3, chunk_s = (total_s + 7) >> 3;
+    const int32_t* __restrict__ b_expert = L.b_expert;
+    const int32_t* __restrict__ b_row0 = L.b_row0;
+    const int32_t* __restrict__ b_rows = L.b_rows;
+    const int32_t* __restrict__ s_expert = L.s_expert;
+    const int32_t* __restrict__ s_row0 = L.s_row0;
+    const int32_t* __restrict__ s_rows = L.s_rows;
     const int cut = split_hdr ? split_hdr[0] : 0, slices = split_hdr ? split_hdr[1] : 1;
     const int cut_s = split_hdr ? split_hdr[2] : 0, slices_s = split_hdr ? split_hdr[3] : 1;
-    // per XCD: whole big items, whole short items, then the units of the cut big items and of the cut short ones
-    // (longest work first, the shortest pieces fill the end)
-    const int whole = chunk_b - cut, units = cut * slices, whole_s = chunk_s - cut_s, units_s = cut_s * slices_s;
     const int xcd = blockIdx.x & 7;
     int slot = blockIdx.x >> 3;
     int tile, nb;
     const SplitUnit one{1, 0, 0, nullptr, nullptr};
+    if (split_hdr && split_hdr[4]) {
+        const int nt = *L.u_count;
+        const int total = nt * (Nout / Big::kNCols), chunk = (total + 7) >> 3;
+        const int logical = xcd * chunk + slot;
+        if (slot >= chunk || logical >= total) return;
+        decode_item(logical, nt, col_group_big, tile, nb);
+        const int rows = L.u_rows[tile];
+        if (rows >= kShortTileFlag)
+            Small::run(A, B0, B1, C, gather, L.u_expert[tile], L.u_row0[tile], rows - kShortTileFlag, nb * Small::kNCols,
+                       K, Nout, smem, one);
+        else
+            Big::run(A, B0, B1, C, gather, L.u_expert[tile], L.u_row0[tile], rows, nb * Big::kNCols, K, Nout, smem, one);
+        return;
+    }
+    const int nt_b = *L.b_count, nt_s = *L.s_count;
+    const int total_b = nt_b * (Nout / Big::kNCols), total_s = nt_s * (Nout / Small::kNCols);
+    const int chunk_b = (total_b + 7) >> 3, chunk_s = (total_s + 7) >> 3;
+    // per XCD: whole big items, whole short items, then the units of the cut big items and of the cut short ones
+    // (longest work first, the shortest pieces fill the end)
+    const int whole = chunk_b - cut, units = cut * slices, whole_s = chunk_s - cut_s, units_s = cut_s * slices_s;
     constexpr int per_xcd = kFfnSplitUnits / 8;
     if (slot < whole) {
         const int logical = xcd * chunk_b + slot;
@@ -591,6 +614,14 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     }
 }
 
+// The three tile lists of a workspace as the kernels take them; joint == false leaves the joint list unwritten
+// (the fp32 kernels walk the list of big tiles only).
+static TileListArgs tile_list_args(const FfnWorkspace& ws, bool joint) {
+    return TileListArgs{ws.big.expert, ws.big.row0,  ws.big.rows,      ws.big.count,       ws.small.expert,
+                        ws.small.row0, ws.small.rows, ws.small.count,   ws.big.max_tiles,   ws.small.max_tiles,
+                        ws.all.expert, ws.all.row0,  ws.all.rows,      ws.all.count,       joint ? ws.all.max_tiles : 0};
+}
+
 static int column_group(int nb_total) {
     for (int g = 4; g > 1; --g)
         if (nb_total % g == 0) return g;
@@ -599,8 +630,8 @@ static int column_group(int nb_total) {
 
 template <class Big, class Small, bool SWIGLU>
 static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, const int32_t* gather,
-                        const TileList& big, const TileList& small, int K, int Nout, const int32_t* split_hdr,
-                        float* split_partial, int32_t* split_counter, hipStream_t st) {
+                        const FfnWorkspace& ws, int K, int Nout, const int32_t* split_hdr, int32_t* split_counter,
+                        hipStream_t st) {
     constexpr int lds = Big::kLdsBytes > Small::kLdsBytes ? Big::kLdsBytes : Small::kLdsBytes;
     auto kern = ffn_gemm_bf16_kernel<Big, Small, SWIGLU>;
     static std::atomic<uint64_t> configured{0};
@@ -609,11 +640,11 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
     });
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
     // items cut along K add at most kFfnSplitUnits blocks per list; + 16: both lists are cut into eight whole chunks
-    const long long grid = (long long)nb_b * big.max_launch + (long long)nb_s * small.max_launch + 2 * kFfnSplitUnits + 16;
+    const long long grid =
+        (long long)nb_b * ws.big.max_launch + (long long)nb_s * ws.small.max_launch + 2 * kFfnSplitUnits + 16;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
-                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, big.expert, big.row0, big.rows,
-                       big.count, small.expert, small.row0, small.rows, small.count, K, Nout,
-                       column_group(nb_b), column_group(nb_s), split_hdr, split_partial, split_counter);
+                       (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, tile_list_args(ws, true), K, Nout,
+                       column_group(nb_b), column_group(nb_s), split_hdr, ws.split_partial, split_counter);
 }
 
 // The arguments of the tile schedule for a descriptor and its workspace layout (host side).
@@ -633,12 +664,11 @@ FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
     a.small_sh = log2i(ws.small.tile_m);
     a.small_max = ws.small_max;
     a.cus = compute_units();
-    a.L = TileListArgs{ws.big.expert, ws.big.row0, ws.big.rows, ws.big.count, ws.small.expert, ws.small.row0,
-                       ws.small.rows, ws.small.count, ws.big.max_tiles, ws.small.max_tiles};
+    a.L = tile_list_args(ws, bf16);
     // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
     const bool split = bf16;
     a.first = SplitArgs{split ? ws.split_hdr : nullptr, split ? ws.split_counter : nullptr, N1 / 128, N1 / 128, K1 / 64};
-    a.second = SplitArgs{split ? ws.split_hdr + 4 : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
+    a.second = SplitArgs{split ? ws.split_hdr + kFfnSplitHdr : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
                          N2 / bn_down, N2 / bn_down, K2 / 64};
     return a;
 }
@@ -659,24 +689,23 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
     }
     if (bf16) {
         const int32_t* split_gu = ws.split_hdr;
-        const int32_t* split_dn = ws.split_hdr + 4;
+        const int32_t* split_dn = ws.split_hdr + kFfnSplitHdr;
         // full-height row tiles: 256 x 256 blocks; short remainders: 64 x 256 blocks; four waves each
         {
             ProfileScope prof(MOE_KERNEL_FFN_GATE_UP, st);
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, true>, TileConfig16<kFfnTileSmall, 256, 1, 4, true>,
-                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws.big, ws.small, K1, N1, split_gu, ws.split_partial,
-                              ws.split_counter, st);
+                        true>(xp, w_gate, w_up, ws.hidden, row_token, ws, K1, N1, split_gu, ws.split_counter, st);
         }
         ProfileScope prof(MOE_KERNEL_FFN_DOWN, st);
         if (bn_down == 256)
             launch_bf16<TileConfig16<kFfnTileM, 256, 2, 2, false>,
                         TileConfig16<kFfnTileSmall, 256, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
-                                                                                    ws.big, ws.small, K2, N2, split_dn, ws.split_partial,
+                                                                                    ws, K2, N2, split_dn,
                                                                                     ws.split_counter + 2 * kFfnSplitUnits, st);
         else
             launch_bf16<TileConfig16<kFfnTileM, 128, 2, 2, false>,
                         TileConfig16<kFfnTileSmall, 128, 1, 4, false>, false>(ws.hidden, w_down, nullptr, yp, nullptr,
-                                                                                    ws.big, ws.small, K2, N2, split_dn, ws.split_partial,
+                                                                                    ws, K2, N2, split_dn,
                                                                                     ws.split_counter + 2 * kFfnSplitUnits, st);
     } else {
         const dim3 g1(((N1 + 15) / 16) * ws.big.max_tiles), g2(((N2 + 15) / 16) * ws.big.max_tiles);

@@ -20,9 +20,15 @@ namespace capmoe {
 // item that finishes last (an integer ticket per item) adds the partial tiles in slice order and writes the
 // output tile: no floating-point atomics, the same bits run to run.  The cut depends on the GEMM's
 // column-block count and K, so each of the two GEMMs gets its own header.
+//
+// A GEMM that is never cut walks either the two lists one after the other (big items first, short ones at the
+// end) or the joint list, in which an expert's short tiles follow its big ones.  In a long launch of compute-bound
+// big items the joint order hides the short items' weight streaming behind matrix work; in a launch of a few
+// rounds, big items that start late because short ones went first are the longer end.  The schedule picks the
+// joint order from kFfnJointMinRounds items per compute unit on.
 struct SplitArgs {
-    int32_t* hdr;      // [4]: big items per XCD that are cut (taken from the end of the XCD's share) and units per
-                       // item, then the same for the short items
+    int32_t* hdr;      // [kFfnSplitHdr]: big items per XCD that are cut (taken from the end of the XCD's share) and
+                       // units per item, then the same for the short items, then 1 if the GEMM walks the joint list
     int32_t* counter;  // [2 * kFfnSplitUnits] tickets (big, short), zeroed here before every launch
     int ncol_big;      // column blocks of the GEMM's big items; 0: never cut
     int ncol_small;    // column blocks of its short items
@@ -31,7 +37,12 @@ struct SplitArgs {
 struct TileListArgs {
     int32_t *b_expert, *b_row0, *b_rows, *b_count, *s_expert, *s_row0, *s_rows, *s_count;
     int b_max, s_max;
+    // both kinds in one list, expert by expert (an expert's big tiles, then its short ones); a short tile's row
+    // count carries kShortTileFlag.  u_max == 0: not written.
+    int32_t *u_expert, *u_row0, *u_rows, *u_count;
+    int u_max;
 };
+constexpr int kShortTileFlag = 1 << 16;  // above every tile height
 
 struct ExpertTiles {
     int lo, rows, nb, ns;
@@ -121,6 +132,7 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
         const int start_b = nt_b + ib - x.nb, start_s = nt_s + is - x.ns;
         nt_b += __shfl(ib, kWave - 1, kWave);
         nt_s += __shfl(is, kWave - 1, kWave);
+        const int start_u = start_b + start_s;
         for (int i = 0; i < x.nb; ++i) {
             const int idx = start_b + i;
             const int left = x.rows - i * big;
@@ -128,6 +140,11 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
                 L.b_expert[idx] = e;
                 L.b_row0[idx] = x.lo + i * big;
                 L.b_rows[idx] = left < big ? left : big;
+            }
+            if (start_u + i < L.u_max) {
+                L.u_expert[start_u + i] = e;
+                L.u_row0[start_u + i] = x.lo + i * big;
+                L.u_rows[start_u + i] = left < big ? left : big;
             }
         }
         const int full = x.rows >> big_sh, rem = x.rows - (full << big_sh);
@@ -139,12 +156,20 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
                 const int left = rem - i * small;
                 L.s_rows[idx] = left < small ? left : small;
             }
+            const int ui = start_u + x.nb + i;
+            if (ui < L.u_max) {
+                L.u_expert[ui] = e;
+                L.u_row0[ui] = x.lo + full * big + i * small;
+                const int left = rem - i * small;
+                L.u_rows[ui] = (left < small ? left : small) + kShortTileFlag;
+            }
         }
     }
     if (lane == 0) {
         const int nb = nt_b < L.b_max ? nt_b : L.b_max, ns = nt_s < L.s_max ? nt_s : L.s_max;
         *L.b_count = nb;
         *L.s_count = ns;
+        *L.u_count = nb + ns < L.u_max ? nb + ns : L.u_max;
         for (const SplitArgs* sp : {&first, &second}) {
             if (!sp->hdr) continue;
             const long long items[2] = {(long long)nb * sp->ncol_big, (long long)ns * sp->ncol_small};
@@ -155,6 +180,9 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
                 sp->hdr[2 * which] = cut;
                 sp->hdr[2 * which + 1] = slices;
             }
+            const long long joint_items = (long long)(nb + ns) * sp->ncol_big;
+            sp->hdr[4] = L.u_max > 0 && ns > 0 && sp->slabs < kFfnSplitMinK &&
+                         joint_items >= (long long)kFfnJointMinRounds * cus;
         }
     }
 }
