@@ -567,6 +567,37 @@ def test_ffn_items_cut_along_k(orc, d, h, counts):
     assert torch.equal(fused.y, buf.y)
 
 
+@pytest.mark.parametrize("d,h,counts", [
+    # gate/up: 32 column blocks x 74 tiles = 9.2 rounds on 256 compute units -> joint list; down: 74 items, two lists
+    (128, 4096, [1000, 30, 300, 64, 2000, 5, 700, 0, 3000, 61, 4500, 257, 11 * 256 + 63, 2300]),
+    # both GEMMs at 4 column blocks x 525 tiles = 8.2 rounds: both walk the joint list
+    (1024, 512, [156 * 256 + 64, 17, 35 * 256 + 50, 0, 25000, 64, 117 * 256 + 51, 700, 1, 109 * 256 + 62]),
+])
+def test_ffn_joint_tile_list(orc, d, h, counts):
+    """A GEMM that is never cut along K and is at least eight rounds of work items long walks one list that holds
+    the big and the short row tiles expert by expert.  Experts with only a short tile, with big tiles and a short
+    remainder, with a partly filled big tile, and an empty one: every token against the oracle (Eq. 2)."""
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="joint", n_tokens=n, d_model=d, n_experts=e, top_k=1, d_hidden=h, device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    np.random.default_rng(33).shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    desc = layer.desc(NONE, GLOBAL, 1.0)
+    buf = run_layer(layer, desc, logits)
+    assert_plan_equal(buf, ref, "joint")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "joint tile list")
+    fused = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(fused, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         torch.from_numpy(logits).cuda(), fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.y, buf.y)
+
+
 def test_ffn_many_experts(orc):
     """200 experts (the tile schedule walks them 64 at a time), most with a handful of rows, some empty, a few with
     several tiles."""
