@@ -34,7 +34,16 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per launch, recorded beside the kernel source they were measured on
 TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_of_the_expert_gemms.md")
-KERNEL_SOURCE = os.path.join(ROOT, "paper_2503_05066_amd", "csrc", "ffn.hip")
+# the expert GEMMs, their tile schedule and the constants both share
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2503_05066_amd", "csrc", f) for f in ("ffn.hip", "schedule.h", "common.h")]
+
+
+def kernel_source_version():
+    """First 12 hex digits of the SHA-1 over the sources that decide how the expert GEMMs run."""
+    h = hashlib.sha1()
+    for path in KERNEL_SOURCES:
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:12]
 
 MODES = {"none": 0, "token": 1, "expanded": 2}
 SCOPES = {"local": 0, "global": 1, "local_device": 2, "global_device": 3}
@@ -447,7 +456,7 @@ def recorded_traffic(workload, mode, scope, gamma, kernel):
     recorded for another version of the kernel is not reported."""
     try:
         text = open(TRAFFIC_TABLE).read()
-        sha = hashlib.sha1(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:12]
+        sha = kernel_source_version()
     except OSError:
         return None
     for line in text.splitlines():

@@ -73,16 +73,20 @@ __device__ inline void wave_scan2(int& a, int& b) {
     }
 }
 
-// How an XCD's share of `items_per_xcd` big items is cut: the last `cut` of them into `slices` units each.
-// cus_per_xcd compute units run one item each per round; a unit keeps at least kFfnSplitMinSlabs slabs.
-__host__ __device__ inline void split_rule(int items_per_xcd, int cus_per_xcd, int slabs, int& cut, int& slices) {
+// How an XCD's share of `items_per_xcd` items of one kind is cut: the last `cut` of them into `slices` units each.
+// cus_per_xcd compute units run one item each per round; the units of the cut items may occupy unit_cus of them
+// side by side; a unit keeps at least kFfnSplitMinSlabs slabs.
+__host__ __device__ inline void split_rule(int items_per_xcd, int cus_per_xcd, int unit_cus, int slabs, int& cut,
+                                           int& slices) {
     cut = 0;
     slices = 1;
     if (items_per_xcd <= 0 || cus_per_xcd <= 0 || slabs < kFfnSplitMinK) return;
     if (cus_per_xcd > kFfnSplitUnits / 8) cus_per_xcd = kFfnSplitUnits / 8;
+    if (unit_cus > cus_per_xcd) unit_cus = cus_per_xcd;
     const int left = items_per_xcd % cus_per_xcd;
     if (left == 0) return;
-    int s = cus_per_xcd / left;
+    int s = unit_cus / left;
+    if (s < 2 && cus_per_xcd / left >= 2) s = 2;  // halves still beat whole items at the end of a launch
     if (s > kFfnSplitMaxSlices) s = kFfnSplitMaxSlices;
     if (s > slabs / kFfnSplitMinSlabs) s = slabs / kFfnSplitMinSlabs;
     if (s < 2) return;
@@ -173,10 +177,18 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
         for (const SplitArgs* sp : {&first, &second}) {
             if (!sp->hdr) continue;
             const long long items[2] = {(long long)nb * sp->ncol_big, (long long)ns * sp->ncol_small};
+            const int per_xcd = cus >> 3;
+            int chunk[2] = {0, 0};
+            for (int which = 0; which < 2; ++which)
+                if (items[which] > 0 && items[which] < (1ll << 30)) chunk[which] = (int)((items[which] + 7) >> 3);
+            // The units of the big items start first; when the XCD also has short items to run after them, those
+            // units take only the big items' share of the tail's work (a short item counted as half a big one),
+            // so that short items start at once on the other compute units and both kinds end together.
+            const int left_big = per_xcd > 0 ? chunk[0] % per_xcd : 0;
+            const int big_cus = chunk[1] > 0 ? per_xcd * 2 * left_big / (2 * left_big + chunk[1]) : per_xcd;
             for (int which = 0; which < 2; ++which) {
                 int cut = 0, slices = 1;
-                if (items[which] > 0 && items[which] < (1ll << 30))
-                    split_rule((int)((items[which] + 7) >> 3), cus >> 3, sp->slabs, cut, slices);
+                split_rule(chunk[which], per_xcd, which == 0 ? big_cus : per_xcd, sp->slabs, cut, slices);
                 sp->hdr[2 * which] = cut;
                 sp->hdr[2 * which + 1] = slices;
             }

@@ -42,18 +42,23 @@ def test_algorithmic_work_matches_the_stated_formulas():
 def test_recorded_traffic_is_reported_only_for_the_kernel_source_it_was_measured_on(tmp_path, monkeypatch):
     import hashlib
 
-    src = tmp_path / "ffn.hip"
+    src, sched = tmp_path / "ffn.hip", tmp_path / "schedule.h"
     src.write_text("kernel v1")
-    sha = hashlib.sha1(b"kernel v1").hexdigest()[:12]
+    sched.write_text("schedule v1")
+    sha = hashlib.sha1(b"kernel v1schedule v1").hexdigest()[:12]
     table = tmp_path / "traffic.md"
     table.write_text("| workload | mode | scope | gamma | kernel | read bytes | written bytes | source |\n|---|---|---|---|---|---|---|---|\n"
                      f"| mixtral | token | local | 1 | ffn_gate_up | 5.0e9 | 2.5e8 | {sha} |\n"
                      f"| mixtral | token | local | 1 | ffn_down | 2.0e9 | 7.0e7 | 000000000000 |\n")
     monkeypatch.setattr(bench, "TRAFFIC_TABLE", str(table))
-    monkeypatch.setattr(bench, "KERNEL_SOURCE", str(src))
+    monkeypatch.setattr(bench, "KERNEL_SOURCES", [str(src), str(sched)])
     assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") == pytest.approx(5.25e9)
     assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_down") is None      # another source version
     assert bench.recorded_traffic("mixtral", "expanded", "local", 1.0, "ffn_gate_up") is None
+    sched.write_text("schedule v2")                                                           # the schedule changed
+    assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") is None
+    sched.write_text("schedule v1")
+    assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") == pytest.approx(5.25e9)
     src.write_text("kernel v2")                                                               # the kernel changed
     assert bench.recorded_traffic("mixtral", "token", "local", 1.0, "ffn_gate_up") is None
     # the tracked table parses, whatever it holds today
