@@ -69,6 +69,7 @@ constexpr int kFfnSplitMinK = 128;       // GEMMs with fewer K slabs are never c
 constexpr int kFfnSplitHdr = 8;          // ints per GEMM in the schedule's header
 constexpr int kFfnJointMinRounds = 8;    // work items per compute unit from which an uncut GEMM walks the joint tile
                                          // list (measured: 16 and 20 rounds gain 2 %, 3 rounds lose 7 %, 5 neither)
+constexpr int kFfnJointPoolRounds = 1;   // rounds of work items at the end of the joint order that any XCD may take
 struct TileList {
     int32_t* expert;  // [max_tiles]
     int32_t* row0;    // [max_tiles] first row of the tile
@@ -86,7 +87,8 @@ struct FfnWorkspace {
     int small_max;
     int32_t* split_hdr;      // [2 GEMMs][kFfnSplitHdr]: big items per XCD that are cut along K and units per item,
                              // the same for the short items, whether the GEMM walks the joint list (bf16 only)
-    int32_t* split_counter;  // [2 GEMMs][2][kFfnSplitUnits] one ticket per cut item (big, short)
+    int32_t* split_counter;  // [2 GEMMs][2][kFfnSplitUnits] one ticket per cut item (big, short); a GEMM that walks the
+                             // joint list is never cut and counts the shared items of its end in its first ticket
     float* split_partial;    // [kFfnSplitUnits][256 x 256] fp32 partial tiles of big items, then
                              // [kFfnSplitUnits][64 x 256] of short ones (the GEMMs run one after the other)
     size_t bytes;

@@ -550,9 +550,26 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const SplitUnit one{1, 0, 0, nullptr, nullptr};
     if (split_hdr && split_hdr[4]) {
         const int nt = *L.u_count;
-        const int total = nt * (Nout / Big::kNCols), chunk = (total + 7) >> 3;
-        const int logical = xcd * chunk + slot;
-        if (slot >= chunk || logical >= total) return;
+        const int total = nt * (Nout / Big::kNCols);
+        // The last split_hdr[5] items of the order are not dealt out in eighths: whichever XCD has a compute
+        // unit free takes the next one (a counter), so that an XCD that runs a few per cent slower than the others
+        // (they differ) does not end the launch alone.  Every XCD brings blocks for a quarter of that pool, twice
+        // its even share; the ones that find the pool empty leave.
+        const int pool = split_hdr[5], fixed = total - pool, chunk = (fixed + 7) >> 3;
+        int logical = xcd * chunk + slot;
+        if (slot >= chunk) {
+            if (slot - chunk >= (pool + 3) >> 2) return;
+            int* next = (int*)smem;
+            if (threadIdx.x == 0)
+                *next = __hip_atomic_fetch_add(split_counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const int taken = *next;
+            __syncthreads();
+            if (taken >= pool) return;
+            logical = fixed + taken;
+        } else if (logical >= fixed) {
+            return;
+        }
         decode_item(logical, nt, col_group_big, tile, nb);
         const int rows = L.u_rows[tile];
         if (rows >= kShortTileFlag)
@@ -639,9 +656,11 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
-    // items cut along K add at most kFfnSplitUnits blocks per list; + 16: both lists are cut into eight whole chunks
+    // items cut along K add at most kFfnSplitUnits blocks per list, the pool at the end of the joint order as many
+    // blocks as it has items; + 16: both lists are cut into eight whole chunks
     const long long grid =
-        (long long)nb_b * ws.big.max_launch + (long long)nb_s * ws.small.max_launch + 2 * kFfnSplitUnits + 16;
+        (long long)nb_b * ws.big.max_launch + (long long)nb_s * ws.small.max_launch +
+        std::max(2 * kFfnSplitUnits, kFfnJointPoolRounds * compute_units()) + 16;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Big::kThreads), lds, st, (const uint16_t*)A,
                        (const uint16_t*)B0, (const uint16_t*)B1, (uint16_t*)C, gather, tile_list_args(ws, true), K, Nout,
                        column_group(nb_b), column_group(nb_s), split_hdr, ws.split_partial, split_counter);

@@ -28,7 +28,8 @@ namespace capmoe {
 // joint order from kFfnJointMinRounds items per compute unit on.
 struct SplitArgs {
     int32_t* hdr;      // [kFfnSplitHdr]: big items per XCD that are cut (taken from the end of the XCD's share) and
-                       // units per item, then the same for the short items, then 1 if the GEMM walks the joint list
+                       // units per item, then the same for the short items, then 1 if the GEMM walks the joint list,
+                       // then how many items at the end of that list the XCDs share out by a counter (counter[0])
     int32_t* counter;  // [2 * kFfnSplitUnits] tickets (big, short), zeroed here before every launch
     int ncol_big;      // column blocks of the GEMM's big items; 0: never cut
     int ncol_small;    // column blocks of its short items
@@ -195,6 +196,8 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
             const long long joint_items = (long long)(nb + ns) * sp->ncol_big;
             sp->hdr[4] = L.u_max > 0 && ns > 0 && sp->slabs < kFfnSplitMinK &&
                          joint_items >= (long long)kFfnJointMinRounds * cus;
+            // the end of the joint order that the XCDs share out among themselves as they get free
+            sp->hdr[5] = sp->hdr[4] ? kFfnJointPoolRounds * cus : 0;
         }
     }
 }
