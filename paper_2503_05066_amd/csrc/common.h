@@ -69,6 +69,7 @@ constexpr int kFfnSplitMinK = 128;       // GEMMs with fewer K slabs are never c
 constexpr int kFfnSplitHdr = 8;          // ints per GEMM in the schedule's header
 constexpr int kFfnJointMinRounds = 8;    // work items per compute unit from which an uncut GEMM walks the joint tile
                                          // list (measured: 16 and 20 rounds gain 2 %, 3 rounds lose 7 %, 5 neither)
+constexpr int kFfnRowPieces = kFfnTileM / kFfnTileSmall;  // short-tile blocks that cover one big item
 constexpr int kFfnJointPoolRounds = 1;   // rounds of work items at the end of the joint order that any XCD may take
 struct TileList {
     int32_t* expert;  // [max_tiles]

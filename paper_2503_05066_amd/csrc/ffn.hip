@@ -582,9 +582,10 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
     const int nt_b = *L.b_count, nt_s = *L.s_count;
     const int total_b = nt_b * (Nout / Big::kNCols), total_s = nt_s * (Nout / Small::kNCols);
     const int chunk_b = (total_b + 7) >> 3, chunk_s = (total_s + 7) >> 3;
-    // per XCD: whole big items, whole short items, then the units of the cut big items and of the cut short ones
-    // (longest work first, the shortest pieces fill the end)
-    const int whole = chunk_b - cut, units = cut * slices, whole_s = chunk_s - cut_s, units_s = cut_s * slices_s;
+    // per XCD: whole big items, the row pieces of big items (see below), whole short items, then the units of the cut
+    // big items and of the cut short ones (longest work first, the shortest pieces fill the end)
+    const int in_rows = split_hdr ? split_hdr[6] : 0;
+    const int whole = chunk_b - cut - in_rows, units = cut * slices, whole_s = chunk_s - cut_s, units_s = cut_s * slices_s;
     constexpr int per_xcd = kFfnSplitUnits / 8;
     if (slot < whole) {
         const int logical = xcd * chunk_b + slot;
@@ -594,6 +595,23 @@ __global__ __launch_bounds__(Big::kThreads) void ffn_gemm_bf16_kernel(
         return;
     }
     slot -= whole;
+    // A GEMM too short in K to be cut there runs the few big items left over after the XCD's last full round as
+    // kRowPieces short-tile blocks each (rows 0-63, 64-127, ... of the item): twice the compute-unit time, on
+    // compute units that would have idled, in half the item's time.
+    constexpr int kRowPieces = Big::kBM / Small::kBM;
+    static_assert(Big::kBM % Small::kBM == 0, "a big tile is a whole number of short tiles");
+    if (slot < in_rows * kRowPieces) {
+        const int idx = slot / kRowPieces, piece = slot - idx * kRowPieces;
+        const int logical = xcd * chunk_b + whole + idx;
+        if (logical >= total_b) return;
+        decode_item(logical, nt_b, col_group_big, tile, nb);
+        const int first = piece * Small::kBM, left = b_rows[tile] - first;
+        if (left <= 0) return;
+        Small::run(A, B0, B1, C, gather, b_expert[tile], b_row0[tile] + first, left < Small::kBM ? left : Small::kBM,
+                   nb * Small::kNCols, K, Nout, smem, one);
+        return;
+    }
+    slot -= in_rows * kRowPieces;
     if (slot < whole_s) {
         const int logical = xcd * chunk_s + slot;
         if (logical >= total_s) return;
@@ -656,8 +674,8 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
         (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     const int nb_b = Nout / Big::kNCols, nb_s = Nout / Small::kNCols;
-    // items cut along K add at most kFfnSplitUnits blocks per list, the pool at the end of the joint order as many
-    // blocks as it has items; + 16: both lists are cut into eight whole chunks
+    // items cut along K (or into row pieces) add at most kFfnSplitUnits blocks per list, the pool at the end of the
+    // joint order as many blocks as it has items; + 16: both lists are cut into eight whole chunks
     const long long grid =
         (long long)nb_b * ws.big.max_launch + (long long)nb_s * ws.small.max_launch +
         std::max(2 * kFfnSplitUnits, kFfnJointPoolRounds * compute_units()) + 16;

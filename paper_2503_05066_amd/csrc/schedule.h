@@ -29,7 +29,8 @@ namespace capmoe {
 struct SplitArgs {
     int32_t* hdr;      // [kFfnSplitHdr]: big items per XCD that are cut (taken from the end of the XCD's share) and
                        // units per item, then the same for the short items, then 1 if the GEMM walks the joint list,
-                       // then how many items at the end of that list the XCDs share out by a counter (counter[0])
+                       // then how many items at the end of that list the XCDs share out by a counter (counter[0]),
+                       // then how many big items at the end of an XCD's share run as row pieces
     int32_t* counter;  // [2 * kFfnSplitUnits] tickets (big, short), zeroed here before every launch
     int ncol_big;      // column blocks of the GEMM's big items; 0: never cut
     int ncol_small;    // column blocks of its short items
@@ -198,6 +199,14 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
                          joint_items >= (long long)kFfnJointMinRounds * cus;
             // the end of the joint order that the XCDs share out among themselves as they get free
             sp->hdr[5] = sp->hdr[4] ? kFfnJointPoolRounds * cus : 0;
+            // Big items left over after the XCD's last full round, in a GEMM too short in K to be cut there: run
+            // as row pieces (four short-tile blocks each) when those and the XCD's short items fit in one round
+            // together, which then takes half an item's time instead of a whole one.
+            const int left_over = per_xcd > 0 && chunk[0] > per_xcd ? chunk[0] % per_xcd : 0;
+            sp->hdr[6] = !sp->hdr[4] && sp->slabs < kFfnSplitMinK && L.s_max > 0 && left_over > 0 &&
+                                 left_over * kFfnRowPieces + chunk[1] <= per_xcd
+                             ? left_over
+                             : 0;
         }
     }
 }

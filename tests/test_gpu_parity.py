@@ -598,6 +598,34 @@ def test_ffn_joint_tile_list(orc, d, h, counts):
     assert torch.equal(fused.y, buf.y)
 
 
+def test_ffn_leftover_items_in_row_pieces(orc):
+    """A GEMM too short in K to be cut there, with one big item per XCD left over after a full round (66 big
+    tiles x 4 column blocks = 33 items per XCD): the leftover items run as four 64-row blocks each, the last of them
+    on a partly filled tile (100 rows: a whole piece, a piece of 36 rows, two empty ones).  Every token against the
+    oracle (Eq. 2), and the same bits with the gather fused into the first GEMM."""
+    d, h = 128, 512
+    counts = [20 * 256, 30 * 256 + 30, 0, 50, 15 * 256 + 100]
+    e, n = len(counts), sum(counts)
+    w = synth.scaled(W["olmoe"], name="pieces", n_tokens=n, d_model=d, n_experts=e, top_k=1, d_hidden=h, device_groups=1)
+    layer = DeviceLayer(w)
+    owner = np.repeat(np.arange(e), counts)
+    np.random.default_rng(34).shuffle(owner)
+    logits = np.zeros((n, e), np.float32)
+    logits[np.arange(n), owner] = 6.0
+    ref = orc.route_and_drop(logits, 1, 1, NONE, GLOBAL, 1.0)
+    np.testing.assert_array_equal(ref.plan.expert_count, counts)
+    desc = layer.desc(NONE, GLOBAL, 1.0)
+    buf = run_layer(layer, desc, logits)
+    assert_plan_equal(buf, ref, "row pieces")
+    y_ref = orc.layer_output(layer.x_host, ref.scores, ref.keep, layer.host_gate, layer.host_up, layer.host_down)
+    assert_output_close(to_host_f64(buf.y), y_ref, TOL[w.dtype], "row pieces")
+    fused = capmoe.LayerBuffers(desc)
+    capmoe.layer_forward(fused, layer.x, layer.w_router, layer.bias, layer.w_gate, layer.w_up, layer.w_down,
+                         torch.from_numpy(logits).cuda(), fused_dispatch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.y, buf.y)
+
+
 def test_ffn_many_experts(orc):
     """200 experts (the tile schedule walks them 64 at a time), most with a handful of rows, some empty, a few with
     several tiles."""
