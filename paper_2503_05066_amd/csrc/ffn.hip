@@ -3,9 +3,9 @@
 //   hidden[r,:] = silu(W_gate[e] xp[r,:]) * (W_up[e] xp[r,:])        (GEMM 1, fused epilogue)
 //   yp[r,:]     = W_down[e] hidden[r,:]                               (GEMM 2)
 //
-// Rows per expert are only known on the device, so a one-block kernel first turns expert_offset
-// into a list of row tiles (expert, first row, valid rows); the GEMM grids are sized for the
-// static upper bound and surplus blocks exit at once.
+// Rows per expert are only known on the device, so one wave (a kernel of its own, or the tail of the
+// capacity drop's last launch) first turns expert_offset into lists of row tiles (expert, first row,
+// valid rows); the GEMM grids are sized for the static upper bound and surplus blocks exit at once.
 //
 // bf16: both operands are K-contiguous ("NT" GEMM), staged through LDS in 16-byte pieces with an
 // XOR swizzle and multiplied on the matrix cores with fp32 accumulation (v_mfma_f32_16x16x32_bf16 in
@@ -186,8 +186,13 @@ struct PipelinedLoop16 {
         if (LIVE == 0) {  // nothing to multiply in this wave: it only fills its share and keeps the barriers
             int slot2 = 2;  // slot of slab kt + 2
             for (int kt = 0; kt < KT; ++kt) {
-                if (kt + 2 < KT) fill_b_all(kt + 2, slot2);
-                __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                // as in the waves that multiply: the weights of slab kt+2 may still fly at the barrier
+                if (kt + 2 < KT) {
+                    fill_b_all(kt + 2, slot2);
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm(B_LOADS));
+                } else {
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+                }
                 __builtin_amdgcn_s_barrier();
                 if (kt + 2 < KT) fill_a_all(kt + 2);
                 slot2 = slot2 == 2 ? 0 : slot2 + 1;
