@@ -342,14 +342,17 @@ def measured_peaks():
     from paper_2503_05066_amd import capmoe
 
     sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
-    best = 0.0
-    for _ in range(3):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        flops = capmoe.moe_probe_mfma_bf16(2048, 4096, sink)
-        b.record()
-        torch.cuda.synchronize()
-        best = max(best, flops / (a.elapsed_time(b) * 1e-3) / 1e12)
+    loop = {}
+    for random_operands in (False, True):
+        best = 0.0
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            flops = capmoe.moe_probe_mfma_bf16(2048, 4096, sink, random_operands)
+            b.record()
+            torch.cuda.synchronize()
+            best = max(best, flops / (a.elapsed_time(b) * 1e-3) / 1e12)
+        loop[random_operands] = best
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty_like(src)
     copy = 0.0
@@ -362,9 +365,11 @@ def measured_peaks():
         copy = max(copy, 2 * (1 << 30) / (a.elapsed_time(b) * 1e-3) / 1e9)
     del src, dst
     torch.cuda.empty_cache()
-    return {"mfma_bf16_TFLOPs": round(best, 1), "copy_GBs": round(copy, 1),
-            "how": "best of 3 launches of 2048 blocks x 4 waves x 4096 x 8 register-only MFMAs; best of 4 "
-                   "1 GiB device copies (read + written bytes)"}
+    return {"mfma_bf16_TFLOPs": round(loop[False], 1), "mfma_bf16_random_operands_TFLOPs": round(loop[True], 1),
+            "copy_GBs": round(copy, 1),
+            "how": "best of 3 launches of 2048 blocks x 4 waves x 4096 x 64 register-only MFMAs (the big GEMM tile's "
+                   "k-step), operands of zeros and ones / random bf16 values in (-2, 2): the clock under the loop depends "
+                   "on the switching operand bits; best of 4 1 GiB device copies (read + written bytes)"}
 
 
 def ffn_uniform(w, reps=9, experts=None, vendor=True):
@@ -643,6 +648,9 @@ def main():
                 if rf:
                     ceiling = pk["mfma_bf16_TFLOPs"] if rf["bound"] == "mfma" else pk["copy_GBs"]
                     rf["frac_of_measured_ceiling"] = round(rf["achieved"] / ceiling, 4)
+                    if rf["bound"] == "mfma":   # the same loop on operands like the layer's (random bits)
+                        rf["frac_of_mfma_loop_on_random_operands"] = round(
+                            rf["achieved"] / pk["mfma_bf16_random_operands_TFLOPs"], 4)
     if a.sweep_gamma:
         gammas = [float(g) for g in a.sweep_gamma.split(",")]
         out["gamma_sweep"] = {"mode": a.mode, "scope": a.scope, "steps": max(20, a.steps // 10),

@@ -267,13 +267,16 @@ int moe_profile_attach(moe_profile_t* table);
 
 /*
  * Matrix-core ceiling probe (instrumentation, not part of the method): launches `blocks` workgroups of
- * 4 wavefronts that each issue iterations * 8 independent bf16 MFMAs (32x32x16) on register operands.
+ * 4 wavefronts that each repeat `iterations` times the 64 independent bf16 MFMAs (16x16x32) of one k-step of
+ * the layer's big GEMM tile, on register operands.
+ *   random_operands  0: operands of zeros and ones; otherwise random bf16 values in (-2, 2).  The clock the
+ *                    chip holds under the loop, and so the rate, depends on how many operand bits switch.
  *   sink   device, at least blocks * 256 floats (receives checksums)
- *   flops  host, optional: floating-point operations of the launch, 2*32*32*16 per MFMA
+ *   flops  host, optional: floating-point operations of the launch, 2*16*16*32 per MFMA
  * The caller times the launch; flops / time is what the matrix cores sustain with no memory traffic.
  * blocks <= 65536, iterations <= 2^20.
  */
-int moe_probe_mfma_bf16(int blocks, int iterations, float* sink, int64_t* flops, void* stream);
+int moe_probe_mfma_bf16(int blocks, int iterations, int random_operands, float* sink, int64_t* flops, void* stream);
 
 #ifdef __cplusplus
 }

@@ -89,7 +89,7 @@ def load():
         lib.moe_layer_forward.restype = i32
         lib.moe_profile_attach.argtypes = [ctypes.POINTER(MoeProfile)]
         lib.moe_profile_attach.restype = i32
-        lib.moe_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
+        lib.moe_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
         lib.moe_probe_mfma_bf16.restype = i32
         for f in ("moe_query", "moe_route_topk", "moe_route_topk_static", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
                   "moe_grouped_ffn",
@@ -206,12 +206,12 @@ def moe_profile_attach(table: "MoeProfile | None"):
     _check(load().moe_profile_attach(ctypes.byref(table) if table is not None else None), "moe_profile_attach")
 
 
-def moe_probe_mfma_bf16(blocks: int, iterations: int, sink, stream=None) -> int:
+def moe_probe_mfma_bf16(blocks: int, iterations: int, sink, random_operands: bool = False, stream=None) -> int:
     """Launch the matrix-core probe; returns the flops of the launch (the caller times it)."""
     flops = ctypes.c_int64(0)
     assert sink.numel() >= blocks * 256
-    _check(load().moe_probe_mfma_bf16(int(blocks), int(iterations), _ptr(sink), ctypes.byref(flops), _stream(stream)),
-           "moe_probe_mfma_bf16")
+    _check(load().moe_probe_mfma_bf16(int(blocks), int(iterations), int(bool(random_operands)), _ptr(sink),
+                                      ctypes.byref(flops), _stream(stream)), "moe_probe_mfma_bf16")
     return int(flops.value)
 
 
