@@ -572,6 +572,8 @@ def test_ffn_items_cut_along_k(orc, d, h, counts):
     (128, 4096, [1000, 30, 300, 64, 2000, 5, 700, 0, 3000, 61, 4500, 257, 11 * 256 + 63, 2300]),
     # both GEMMs at 4 column blocks x 525 tiles = 8.2 rounds: both walk the joint list
     (1024, 512, [156 * 256 + 64, 17, 35 * 256 + 50, 0, 25000, 64, 117 * 256 + 51, 700, 1, 109 * 256 + 62]),
+    # seven column blocks (column groups of one): 298 tiles x 7 = 8.1 rounds in gate/up
+    (128, 896, [30010, 17, 25040, 20064, 300]),
 ])
 def test_ffn_joint_tile_list(orc, d, h, counts):
     """A GEMM that is never cut along K and is at least eight rounds of work items long walks one list that holds
