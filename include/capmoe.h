@@ -266,6 +266,24 @@ typedef struct {
 int moe_profile_attach(moe_profile_t* table);
 
 /*
+ * What the tile schedule of the expert GEMMs decides for a plan with the given rows per expert (diagnostic; the
+ * library runs the same code on the device when it builds the schedule, here it runs on the host and launches
+ * nothing).  Lets a caller or a test see which launch form a workload gets.
+ *   expert_count    host [E]: rows per expert of the plan (their sum at most max_rows of moe_query)
+ *   compute_units   compute units of the GPU the answer is for (256 on MI355X; a multiple of 8)
+ *   tiles           host [2], out: full-height (256-row) tiles, short (64-row) tiles
+ *   header          host [2][8], out: for the gate/up GEMM, then the down GEMM:
+ *                   [0] big work items per XCD that are cut along K, [1] units per such item,
+ *                   [2], [3] the same for the short items, [4] 1 if the GEMM walks the joint tile list,
+ *                   [5] work items at the end of that list that the XCDs share out by a counter,
+ *                   [6] big work items per XCD that run as four 64-row blocks, [7] 0.
+ *                   All zero for desc->dtype == fp32, whose kernels use none of this.
+ * Errors: MOE_ERR_INVALID_ARG for null pointers, negative counts, more rows than max_rows.
+ */
+int moe_ffn_schedule_query(const moe_desc_t* desc, const int32_t* expert_count, int compute_units, int32_t* tiles,
+                           int32_t* header);
+
+/*
  * Matrix-core ceiling probe (instrumentation, not part of the method): launches `blocks` workgroups of
  * 4 wavefronts that each repeat `iterations` times the 64 independent bf16 MFMAs (16x16x32) of one k-step of
  * the layer's big GEMM tile, on register operands.

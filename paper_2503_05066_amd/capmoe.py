@@ -89,6 +89,8 @@ def load():
         lib.moe_layer_forward.restype = i32
         lib.moe_profile_attach.argtypes = [ctypes.POINTER(MoeProfile)]
         lib.moe_profile_attach.restype = i32
+        lib.moe_ffn_schedule_query.argtypes = [ctypes.POINTER(MoeDesc), vp, i32, vp, vp]
+        lib.moe_ffn_schedule_query.restype = i32
         lib.moe_probe_mfma_bf16.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_int64), vp]
         lib.moe_probe_mfma_bf16.restype = i32
         for f in ("moe_query", "moe_route_topk", "moe_route_topk_static", "moe_capacity_drop", "moe_capacity_drop_ranked", "moe_dispatch",
@@ -204,6 +206,17 @@ def moe_layer_forward(desc, x, w_router, bias, w_gate, w_up, w_down, token_class
 def moe_profile_attach(table: "MoeProfile | None"):
     """Attach the caller's profile table to this thread (None detaches).  The caller keeps the table alive."""
     _check(load().moe_profile_attach(ctypes.byref(table) if table is not None else None), "moe_profile_attach")
+
+
+def moe_ffn_schedule_query(desc: MoeDesc, expert_count, compute_units: int = 256):
+    """What the tile schedule of the expert GEMMs decides for these rows per expert (host only, nothing is launched):
+    ((big tiles, short tiles), [gate/up header of 8 ints, down header of 8 ints])."""
+    counts = (ctypes.c_int32 * desc.n_experts)(*[int(c) for c in expert_count])
+    tiles = (ctypes.c_int32 * 2)()
+    header = (ctypes.c_int32 * 16)()
+    _check(load().moe_ffn_schedule_query(ctypes.byref(desc), counts, int(compute_units), tiles, header),
+           "moe_ffn_schedule_query")
+    return (tiles[0], tiles[1]), [list(header[:8]), list(header[8:])]
 
 
 def moe_probe_mfma_bf16(blocks: int, iterations: int, sink, random_operands: bool = False, stream=None) -> int:

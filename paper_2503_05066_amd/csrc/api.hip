@@ -276,6 +276,23 @@ int moe_query(const moe_desc_t* desc, int32_t* cap, int32_t* slots_per_token, in
     return MOE_OK;
 }
 
+int moe_ffn_schedule_query(const moe_desc_t* desc, const int32_t* expert_count, int compute_units, int32_t* tiles,
+                           int32_t* header) {
+    const int v = validate(desc);
+    if (v != MOE_OK) return v;
+    if (!expert_count || !tiles || !header || compute_units < 8 || compute_units > 4096) return MOE_ERR_INVALID_ARG;
+    const Sizes s = derive(*desc);
+    if (s.max_rows >= (int64_t)1 << 31) return MOE_ERR_UNSUPPORTED;
+    int64_t rows = 0;
+    for (int e = 0; e < desc->n_experts; ++e) {
+        if (expert_count[e] < 0) return MOE_ERR_INVALID_ARG;
+        rows += expert_count[e];
+    }
+    if (rows > s.max_rows) return MOE_ERR_INVALID_ARG;
+    ffn_schedule_on_host(*desc, ffn_workspace(*desc, s, nullptr), expert_count, compute_units, tiles, header);
+    return MOE_OK;
+}
+
 int moe_route_topk(const moe_desc_t* desc, const void* x, const float* w_router, const float* bias,
                    int use_given_logits, float* logits, float* scores, int32_t* topk_idx, float* topk_score,
                    void* workspace, size_t workspace_bytes, void* stream) {
@@ -416,7 +433,7 @@ int moe_layer_forward(const moe_desc_t* desc, const void* x, const float* w_rout
     if (s.max_rows > 0) {
         const FfnWorkspace fw = ffn_workspace(*desc, s, workspace);
         fold = (size_t)((const char*)fw.big.expert - (const char*)workspace) >= drop_workspace(*desc, s, nullptr).bytes;
-        if (fold) schedule = ffn_schedule_args(*desc, fw);
+        if (fold) schedule = ffn_schedule_args(*desc, fw, compute_units());
     }
     st = capacity_drop_impl(desc, scores, topk_idx, token_class, seed, expert_count, seg_count, expert_offset, row_token,
                             row_weight, pair_row, workspace, workspace_bytes, fold ? &schedule : nullptr, stream);

@@ -157,6 +157,8 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
                               const void* w_up, const void* w_down, void* yp, bool schedule_ready, hipStream_t st);
 // schedule != nullptr (launch_capacity_drop): the drop also builds the tile schedule of the expert GEMMs;
 // schedule_ready (launch_grouped_ffn): it has been built that way, no schedule kernel is launched
-FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws);
+FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws, int cus);
+void ffn_schedule_on_host(const moe_desc_t& d, const FfnWorkspace& ws, const int32_t* expert_count, int cus,
+                          int32_t* tiles, int32_t* header);
 
 }  // namespace capmoe

@@ -690,7 +690,7 @@ static void launch_bf16(const void* A, const void* B0, const void* B1, void* C, 
 }
 
 // The arguments of the tile schedule for a descriptor and its workspace layout (host side).
-FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
+FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws, int cus) {
     const bool bf16 = d.dtype == MOE_DTYPE_BF16;
     const int K1 = d.d_model, N1 = d.d_hidden, K2 = d.d_hidden, N2 = d.d_model;
     const int bn_down = N2 % 256 == 0 ? 256 : 128;
@@ -705,7 +705,7 @@ FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
     a.big_sh = log2i(ws.big.tile_m);
     a.small_sh = log2i(ws.small.tile_m);
     a.small_max = ws.small_max;
-    a.cus = compute_units();
+    a.cus = cus;
     a.L = tile_list_args(ws, bf16);
     // gate/up: a big item covers 128 hidden columns (gate and up rows of them)
     const bool split = bf16;
@@ -713,6 +713,31 @@ FfnScheduleArgs ffn_schedule_args(const moe_desc_t& d, const FfnWorkspace& ws) {
     a.second = SplitArgs{split ? ws.split_hdr + kFfnSplitHdr : nullptr, split ? ws.split_counter + 2 * kFfnSplitUnits : nullptr,
                          N2 / bn_down, N2 / bn_down, K2 / 64};
     return a;
+}
+
+// What the schedule decides for given per-expert row counts, on the host (moe_ffn_schedule_query).
+void ffn_schedule_on_host(const moe_desc_t& d, const FfnWorkspace& ws, const int32_t* expert_count, int cus,
+                          int32_t* tiles, int32_t* header) {
+    FfnWorkspace layout = ws;
+    int32_t hdr_gate_up[kFfnSplitHdr] = {}, hdr_down[kFfnSplitHdr] = {};
+    layout.split_hdr = nullptr;  // the headers are written below, not through the workspace
+    const FfnScheduleArgs a = ffn_schedule_args(d, layout, cus);
+    int nb = 0, ns = 0;
+    for (int e = 0; e < d.n_experts; ++e) {
+        const ExpertTiles t = expert_tiles(0, expert_count[e], a.big_sh, a.small_sh, a.small_max);
+        nb += t.nb;
+        ns += t.ns;
+    }
+    if (d.dtype == MOE_DTYPE_BF16) {
+        ffn_schedule_header(nb, ns, a.first.ncol_big, a.first.ncol_small, a.first.slabs, cus, true, true, hdr_gate_up);
+        ffn_schedule_header(nb, ns, a.second.ncol_big, a.second.ncol_small, a.second.slabs, cus, true, true, hdr_down);
+    }
+    tiles[0] = nb;
+    tiles[1] = ns;
+    for (int i = 0; i < kFfnSplitHdr; ++i) {
+        header[i] = hdr_gate_up[i];
+        header[kFfnSplitHdr + i] = hdr_down[i];
+    }
 }
 
 // row_token == nullptr: xp holds the permuted rows.  Otherwise xp is the unpermuted x and row r of the
@@ -727,7 +752,7 @@ hipError_t launch_grouped_ffn(const moe_desc_t& d, const Sizes& s, const FfnWork
     const int bn_down = N2 % 256 == 0 ? 256 : 128;  // d is a multiple of 128 at least: output columns per block
     if (!schedule_ready) {
         ProfileScope prof(MOE_KERNEL_FFN_SCHEDULE, st);
-        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, ffn_schedule_args(d, ws));
+        hipLaunchKernelGGL(ffn_schedule_kernel, dim3(1), dim3(64), 0, st, expert_offset, ffn_schedule_args(d, ws, compute_units()));
     }
     if (bf16) {
         const int32_t* split_gu = ws.split_hdr;

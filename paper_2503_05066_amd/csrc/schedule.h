@@ -51,7 +51,7 @@ struct ExpertTiles {
 };
 // Tile heights are powers of two (big = 1 << big_sh, small = 1 << small_sh): a single wave runs this kernel,
 // every dependent instruction counts, and a division by a run-time value is forty of them.
-__device__ inline ExpertTiles expert_tiles(int lo, int hi, int big_sh, int small_sh, int small_max) {
+__host__ __device__ inline ExpertTiles expert_tiles(int lo, int hi, int big_sh, int small_sh, int small_max) {
     ExpertTiles t;
     t.lo = lo;
     t.rows = hi - lo;
@@ -94,6 +94,43 @@ __host__ __device__ inline void split_rule(int items_per_xcd, int cus_per_xcd, i
     if (s < 2) return;
     cut = left;
     slices = s;
+}
+
+// The header of one GEMM (kFfnSplitHdr ints, see SplitArgs::hdr) from the number of big and short row tiles:
+// every decision of the schedule that depends on the plan.  joint_list: the joint tile list is written (bf16);
+// short_tiles: the short-tile configuration exists.  Host and device run the same code (the host copy answers
+// moe_ffn_schedule_query).
+__host__ __device__ inline void ffn_schedule_header(int nb, int ns, int ncol_big, int ncol_small, int slabs, int cus,
+                                                    bool joint_list, bool short_tiles, int32_t* hdr) {
+    const long long items[2] = {(long long)nb * ncol_big, (long long)ns * ncol_small};
+    const int per_xcd = cus >> 3;
+    int chunk[2] = {0, 0};
+    for (int which = 0; which < 2; ++which)
+        if (items[which] > 0 && items[which] < (1ll << 30)) chunk[which] = (int)((items[which] + 7) >> 3);
+    // The units of the big items start first; when the XCD also has short items to run after them, those
+    // units take only the big items' share of the tail's work (a short item counted as half a big one),
+    // so that short items start at once on the other compute units and both kinds end together.
+    const int left_big = per_xcd > 0 ? chunk[0] % per_xcd : 0;
+    const int big_cus = chunk[1] > 0 ? per_xcd * 2 * left_big / (2 * left_big + chunk[1]) : per_xcd;
+    for (int which = 0; which < 2; ++which) {
+        int cut = 0, slices = 1;
+        split_rule(chunk[which], per_xcd, which == 0 ? big_cus : per_xcd, slabs, cut, slices);
+        hdr[2 * which] = cut;
+        hdr[2 * which + 1] = slices;
+    }
+    const long long joint_items = (long long)(nb + ns) * ncol_big;
+    hdr[4] = joint_list && ns > 0 && slabs < kFfnSplitMinK && joint_items >= (long long)kFfnJointMinRounds * cus;
+    // the end of the joint order that the XCDs share out among themselves as they get free
+    hdr[5] = hdr[4] ? kFfnJointPoolRounds * cus : 0;
+    // Big items left over after the XCD's last full round, in a GEMM too short in K to be cut there: run
+    // as row pieces (four short-tile blocks each) when those and the XCD's short items fit in one round
+    // together, which then takes half an item's time instead of a whole one.
+    const int left_over = per_xcd > 0 && chunk[0] > per_xcd ? chunk[0] % per_xcd : 0;
+    hdr[6] = !hdr[4] && slabs < kFfnSplitMinK && short_tiles && left_over > 0 &&
+                     left_over * kFfnRowPieces + chunk[1] <= per_xcd
+                 ? left_over
+                 : 0;
+    hdr[7] = 0;
 }
 
 // Everything the schedule needs besides the row offsets (passed by value to a kernel).
@@ -178,35 +215,7 @@ __device__ inline void build_ffn_schedule(const int32_t* expert_offset, const Ff
         *L.u_count = nb + ns < L.u_max ? nb + ns : L.u_max;
         for (const SplitArgs* sp : {&first, &second}) {
             if (!sp->hdr) continue;
-            const long long items[2] = {(long long)nb * sp->ncol_big, (long long)ns * sp->ncol_small};
-            const int per_xcd = cus >> 3;
-            int chunk[2] = {0, 0};
-            for (int which = 0; which < 2; ++which)
-                if (items[which] > 0 && items[which] < (1ll << 30)) chunk[which] = (int)((items[which] + 7) >> 3);
-            // The units of the big items start first; when the XCD also has short items to run after them, those
-            // units take only the big items' share of the tail's work (a short item counted as half a big one),
-            // so that short items start at once on the other compute units and both kinds end together.
-            const int left_big = per_xcd > 0 ? chunk[0] % per_xcd : 0;
-            const int big_cus = chunk[1] > 0 ? per_xcd * 2 * left_big / (2 * left_big + chunk[1]) : per_xcd;
-            for (int which = 0; which < 2; ++which) {
-                int cut = 0, slices = 1;
-                split_rule(chunk[which], per_xcd, which == 0 ? big_cus : per_xcd, sp->slabs, cut, slices);
-                sp->hdr[2 * which] = cut;
-                sp->hdr[2 * which + 1] = slices;
-            }
-            const long long joint_items = (long long)(nb + ns) * sp->ncol_big;
-            sp->hdr[4] = L.u_max > 0 && ns > 0 && sp->slabs < kFfnSplitMinK &&
-                         joint_items >= (long long)kFfnJointMinRounds * cus;
-            // the end of the joint order that the XCDs share out among themselves as they get free
-            sp->hdr[5] = sp->hdr[4] ? kFfnJointPoolRounds * cus : 0;
-            // Big items left over after the XCD's last full round, in a GEMM too short in K to be cut there: run
-            // as row pieces (four short-tile blocks each) when those and the XCD's short items fit in one round
-            // together, which then takes half an item's time instead of a whole one.
-            const int left_over = per_xcd > 0 && chunk[0] > per_xcd ? chunk[0] % per_xcd : 0;
-            sp->hdr[6] = !sp->hdr[4] && sp->slabs < kFfnSplitMinK && L.s_max > 0 && left_over > 0 &&
-                                 left_over * kFfnRowPieces + chunk[1] <= per_xcd
-                             ? left_over
-                             : 0;
+            ffn_schedule_header(nb, ns, sp->ncol_big, sp->ncol_small, sp->slabs, cus, L.u_max > 0, L.s_max > 0, sp->hdr);
         }
     }
 }

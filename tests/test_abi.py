@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"moe_route_topk", "moe_capacity_drop", "moe_dispatch", "moe_grouped_ffn", "moe_dispatch_ffn", "moe_combine",
             "moe_query", "moe_profile_attach", "moe_layer_forward", "moe_probe_mfma_bf16", "moe_capacity_drop_ranked",
-            "moe_status_string", "moe_route_topk_static"} <= set(names)
+            "moe_status_string", "moe_route_topk_static", "moe_ffn_schedule_query"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
     assert capmoe.status_string(0) == "ok" and "workspace" in capmoe.status_string(3)
@@ -83,6 +83,54 @@ def test_capacity_truncation_matches_oracle(orc):
             assert capmoe.moe_query(d)[0] == orc.capacity(gamma, n // g, k, e)
 
 
+MODES = {"none": 0, "token": 1, "expanded": 2}
+
+
+@pytest.mark.parametrize("name,mode,tiles,gate_up,down", [
+    # Mixtral shape, Token Drop: 34 big + 3 short tiles.  Gate/up (K = 4096: never cut; 37 x 112 items = 16 rounds)
+    # walks the joint list and shares out its last 256 items; down (K = 14336) cuts the 4 big items an XCD has
+    # left after two rounds into 4 units (18 of 32 compute units: the 6 short items count half) and the 6 short
+    # ones into 5
+    ("mixtral", "token", (34, 3), [0, 1, 0, 1, 1, 256, 0, 0], [4, 4, 6, 5, 0, 0, 0, 0]),
+    # no drop: 130 big items per XCD are four rounds and 2 left (5 units each beside 8 short items in 4 units)
+    ("mixtral", "none", (65, 4), [0, 1, 0, 1, 1, 256, 0, 0], [2, 5, 8, 4, 0, 0, 0, 0]),
+    # Expanded Drop: 86 big items per XCD leave 22, too many to cut; the 4 short ones run as 8 units each
+    ("mixtral", "expanded", (43, 2), [0, 1, 0, 1, 1, 256, 0, 0], [0, 1, 4, 8, 0, 0, 0, 0]),
+    # OLMoE shape: 2.7 rounds of items, K too short to cut, exactly two rounds of big items: nothing special
+    ("olmoe", "token", (64, 22), [0, 1, 0, 1, 0, 0, 0, 0], [0, 1, 0, 1, 0, 0, 0, 0]),
+    # fine-grained, Expanded Drop: gate/up has 161.25 big items per XCD, the 2 after the fifth round run as row pieces
+    ("finegrained", "expanded", (215, 11), [0, 1, 0, 1, 0, 0, 2, 0], [0, 1, 0, 1, 0, 0, 0, 0]),
+    # decode shape: short tiles only
+    ("decode", "token", (0, 64), [0, 1, 0, 1, 0, 0, 0, 0], [0, 1, 0, 1, 0, 0, 0, 0]),
+])
+def test_tile_schedule_decisions_on_the_named_workloads(orc, name, mode, tiles, gate_up, down):
+    """The launch form each benchmarked workload gets on 256 compute units (the library runs the same decision
+    code on the device): a change that silently sends a workload down a slower form fails here."""
+    w = synth.WORKLOADS[name]
+    logits = orc.router_logits(synth.tokens(w).f32, synth.router_weight(w), synth.router_bias(w))
+    ref = orc.route_and_drop(logits, w.top_k, w.device_groups, MODES[mode], 0, 1.0)
+    d = capmoe.make_desc(w.n_tokens, w.d_model, w.n_experts, w.top_k, w.d_hidden, w.device_groups, MODES[mode], 0, 1.0,
+                         w.dtype)
+    got_tiles, (got_gate_up, got_down) = capmoe.moe_ffn_schedule_query(d, ref.plan.expert_count, 256)
+    assert got_tiles == tiles
+    assert got_gate_up == gate_up and got_down == down
+
+
+def test_tile_schedule_query_edge_cases():
+    d = capmoe.make_desc(1024, 256, 4, 1, 512, 1, 0, 1, 1.0, 1)
+    # empty plan; one row; more rows than the plan can hold; a negative count
+    assert capmoe.moe_ffn_schedule_query(d, [0, 0, 0, 0])[0] == (0, 0)
+    assert capmoe.moe_ffn_schedule_query(d, [0, 1, 0, 0])[0] == (0, 1)
+    assert capmoe.moe_ffn_schedule_query(d, [64, 65, 256, 257])[0] == (3, 2)   # 64 -> short, 65 -> partly filled big
+    for bad in ([1024, 1, 0, 0], [-1, 0, 0, 0]):
+        with pytest.raises(capmoe.CapMoeError) as ei:
+            capmoe.moe_ffn_schedule_query(d, bad)
+        assert ei.value.status == 1
+    # fp32 layers use none of it
+    f = capmoe.make_desc(128, 64, 8, 2, 128, 1, 1, 0, 1.0, 0)
+    assert capmoe.moe_ffn_schedule_query(f, [32] * 8)[1] == [[0] * 8, [0] * 8]
+
+
 def test_bad_arguments_are_refused_on_the_host():
     lib = capmoe.load()
     ok = capmoe.make_desc(128, 64, 8, 2, 128)
@@ -118,6 +166,7 @@ def test_bad_arguments_are_refused_on_the_host():
     assert lib.moe_combine(ctypes.byref(ok), z, z, z, z, z) == 1
     assert lib.moe_layer_forward(ctypes.byref(ok), *([z] * 7), 0, *([z] * 13), 0, z) == 1
     assert lib.moe_query(None, None, None, None, None) == 1
+    assert lib.moe_ffn_schedule_query(ctypes.byref(ok), z, 256, z, z) == 1
     # x of 4 GiB or more: the gathered form of the bf16 FFN refuses (it addresses x with 32-bit byte offsets), the
     # form on permuted rows does not (it stops at the workspace check here; nothing is launched either way)
     big = capmoe.make_desc(1 << 21, 1024, 8, 2, 1024, dtype=1)
